@@ -1,0 +1,287 @@
+"""Seeded synthetic inputs for one block-wise diffusion decode step.
+
+This module only *draws and rounds numbers*: it holds no attention, softmax,
+threshold or commit arithmetic.  Both the CPU oracle's tests and the HIP path's
+tests / bench take their inputs from here, so that the two sides see identical
+bits.  The tensors stand in for the *shapes* of the 7-8B diffusion-LLM workloads
+the paper evaluates (heads, head_dim, vocabulary, prompt / generation / block
+lengths, threshold tau0 = 0.9, alpha 0.1..0.7, block 32 -- paper Table 12); no
+benchmark item or trained weight is involved.
+
+Notation (paper section 3.1 / 3.3): B batch, Hq / Hkv query / KV heads, D head
+dim, P prefix length (prompt + committed blocks), K block length, S full suffix
+length, s = n_keep kept suffix rows, V vocabulary.
+
+Layouts (row-major, last dim contiguous):
+  q_block  [B,Hq,K,D]   q_suffix [B,Hq,S,D]
+  k_cache / v_cache [B,Hkv,cap,D]  (rows 0..P-1 valid)
+  k_block / v_block [B,Hkv,K,D]    k_suffix / v_suffix [B,Hkv,S,D]
+  keep_idx [s] int32, strictly increasing, values in [0,S)
+  logits [B,K,ld] (first V of each row valid), tokens [B,K] int32, masked [B,K] uint8
+
+bf16 tensors are returned as uint16 bit patterns (round-to-nearest-even from
+fp32, done once here); `to_f64` widens either dtype exactly to float64.
+"""
+from __future__ import annotations
+
+import dataclasses
+import zlib
+from typing import Dict, Optional
+
+import numpy as np
+
+MASK_TOKEN = -1  # placeholder id stored in `tokens` at masked positions
+
+
+# --------------------------------------------------------------------------
+# dtype helpers (data preparation only)
+# --------------------------------------------------------------------------
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round fp32 -> bf16 (nearest even); returns the uint16 bit patterns."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    u = x.view(np.uint32)
+    rounded = u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
+    return (rounded >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def to_f64(x: np.ndarray) -> np.ndarray:
+    """Exact widening of a generated tensor (bf16 bits or fp32) to float64."""
+    if x.dtype == np.uint16:
+        return bf16_bits_to_f32(x).astype(np.float64)
+    return x.astype(np.float64)
+
+
+def _rng(seed: int, name: str, layer: int = 0) -> np.random.Generator:
+    """One independent Philox stream per (seed, tensor name, layer)."""
+    tag = zlib.crc32(name.encode()) & 0xFFFFFFFF
+    return np.random.Generator(np.random.Philox(key=[(seed << 32) | tag, layer]))
+
+
+def _normal(seed, name, layer, shape, std, dtype):
+    g = _rng(seed, name, layer)
+    x = g.standard_normal(size=shape, dtype=np.float32)
+    if std != 1.0:
+        x *= np.float32(std)
+    if dtype == "bf16":
+        return f32_to_bf16_bits(x)
+    return x
+
+
+# --------------------------------------------------------------------------
+# workload descriptions
+# --------------------------------------------------------------------------
+@dataclasses.dataclass(frozen=True)
+class Workload:
+    name: str
+    dtype: str            # "fp32" | "bf16"
+    B: int
+    Hq: int
+    Hkv: int
+    D: int
+    prompt: int
+    gen: int
+    K: int                # block length
+    active_block: int     # 0-based index of the block being decoded
+    n_keep: int           # kept suffix rows (s)
+    keep_rule: str        # "first" | "window+last" | "all"
+    V: int
+    qkv_std: float
+    logit_std: float
+    boost: bool           # one boosted logit per row, U(18,26)
+    masked_rule: str      # "half" | "all" | "fraction"
+    tau0: float
+    alpha: float
+    n_layers: int = 1
+
+    @property
+    def P(self) -> int:
+        return self.prompt + self.active_block * self.K
+
+    @property
+    def S(self) -> int:
+        return self.gen - (self.active_block + 1) * self.K
+
+    @property
+    def cap(self) -> int:
+        return self.prompt + self.gen
+
+    @property
+    def Nq(self) -> int:
+        return self.K + self.n_keep
+
+    @property
+    def Nkv(self) -> int:
+        return self.P + self.K + self.n_keep
+
+    @property
+    def scale(self) -> float:
+        return 1.0 / float(np.sqrt(self.D))
+
+    @property
+    def elem_bytes(self) -> int:
+        return 4 if self.dtype == "fp32" else 2
+
+    def attn_flops(self) -> int:
+        """4*B*Hq*Nq*Nkv*D per layer (QK^T and PV, 2 flop per multiply-add)."""
+        return 4 * self.B * self.Hq * self.Nq * self.Nkv * self.D
+
+    def attn_bytes(self) -> int:
+        """Algorithmic HBM bytes of one attention layer: every K and V row of every
+        KV head once, the gathered Q rows once, the output once."""
+        kv = 2 * self.B * self.Hkv * self.Nkv * self.D * self.elem_bytes
+        qo = 2 * self.B * self.Hq * self.Nq * self.D * self.elem_bytes
+        return kv + qo
+
+
+WORKLOADS: Dict[str, Workload] = {
+    # tiny single-layer step, fp32
+    "cfg1": Workload("cfg1", "fp32", 1, 4, 4, 64, 64, 256, 32, 0, 16, "first", 2048,
+                     1.0, 3.0, False, "half", 0.9, 0.0),
+    # LLaDA-8B-shaped layer step (0-based block 3 of 8: P = 608, S = 128)
+    "cfg2": Workload("cfg2", "bf16", 1, 32, 32, 128, 512, 256, 32, 3, 32, "window+last", 126464,
+                     1.0 / float(np.sqrt(128.0)), 4.0, True, "half", 0.9, 0.3),
+    # suffix-pruning ablation pair: A keeps 32 of 992, B keeps all 992
+    "cfg3A": Workload("cfg3A", "bf16", 8, 32, 32, 128, 1024, 1024, 32, 0, 32, "window+last", 126464,
+                      1.0, 4.0, False, "all", 0.9, 0.0),
+    "cfg3B": Workload("cfg3B", "bf16", 8, 32, 32, 128, 1024, 1024, 32, 0, 992, "all", 126464,
+                      1.0, 4.0, False, "all", 0.9, 0.0),
+    # Dream-7B-shaped GQA step
+    "cfg4": Workload("cfg4", "bf16", 16, 28, 4, 128, 256, 512, 32, 8, 32, "window+last", 152064,
+                     1.0, 4.0, False, "fraction", 0.9, 0.3),
+    # same shapes with boosted rows, so block_done varies across the batch
+    "cfg4boost": Workload("cfg4boost", "bf16", 16, 28, 4, 128, 256, 512, 32, 8, 32, "window+last", 152064,
+                          1.0, 4.0, True, "fraction", 0.9, 0.3),
+    # long-context 32-layer stack
+    "cfg5": Workload("cfg5", "bf16", 4, 32, 32, 128, 4096, 2048, 64, 16, 64, "window+last", 126464,
+                     1.0, 4.0, False, "all", 0.9, 0.3, n_layers=32),
+    # small bf16 case the oracle finishes instantly; spans several 32-key tiles and a ragged tail
+    "small_bf16": Workload("small_bf16", "bf16", 2, 4, 2, 128, 75, 160, 32, 1, 33, "window+last", 5000,
+                           1.0, 4.0, True, "half", 0.9, 0.3),
+}
+
+
+def make_keep_idx(w: Workload) -> np.ndarray:
+    """Index list of kept suffix rows (an *input* of the hot path)."""
+    S, s = w.S, w.n_keep
+    if s == 0:
+        return np.zeros((0,), dtype=np.int32)
+    if w.keep_rule == "first":
+        idx = np.arange(s)
+    elif w.keep_rule == "all":
+        assert s == S
+        idx = np.arange(S)
+    elif w.keep_rule == "window+last":
+        # nearest s-1 suffix positions plus the trailing position (paper Eq. 7 / Fig. 4)
+        idx = np.concatenate([np.arange(min(s - 1, S - 1)), [S - 1]])
+    else:
+        raise ValueError(w.keep_rule)
+    idx = np.unique(idx).astype(np.int32)
+    assert idx.shape[0] == s, (idx.shape, s)
+    return idx
+
+
+def make_attention_inputs(w: Workload, seed: int = 0, layer: int = 0) -> Dict[str, np.ndarray]:
+    B, Hq, Hkv, D, K, S, P, cap = w.B, w.Hq, w.Hkv, w.D, w.K, w.S, w.P, w.cap
+    sd, dt = w.qkv_std, w.dtype
+    out = {
+        "q_block": _normal(seed, "q_block", layer, (B, Hq, K, D), sd, dt),
+        "q_suffix": _normal(seed, "q_suffix", layer, (B, Hq, S, D), sd, dt),
+        "k_cache": _normal(seed, "k_cache", layer, (B, Hkv, cap, D), sd, dt),
+        "v_cache": _normal(seed, "v_cache", layer, (B, Hkv, cap, D), sd, dt),
+        "k_block": _normal(seed, "k_block", layer, (B, Hkv, K, D), sd, dt),
+        "v_block": _normal(seed, "v_block", layer, (B, Hkv, K, D), sd, dt),
+        "k_suffix": _normal(seed, "k_suffix", layer, (B, Hkv, S, D), sd, dt),
+        "v_suffix": _normal(seed, "v_suffix", layer, (B, Hkv, S, D), sd, dt),
+        "keep_idx": make_keep_idx(w),
+    }
+    return out
+
+
+def make_custom_attention_inputs(dtype: str, B: int, Hq: int, Hkv: int, D: int, P: int, cap: int, K: int,
+                                 S: int, keep_idx, seed: int = 0, std: float = 1.0) -> Dict[str, np.ndarray]:
+    """Free-form shapes for edge-case tests (ragged tails, empty suffix, ...)."""
+    keep_idx = np.asarray(keep_idx, dtype=np.int32).reshape(-1)
+    out = {
+        "q_block": _normal(seed, "q_block", 0, (B, Hq, K, D), std, dtype),
+        "q_suffix": _normal(seed, "q_suffix", 0, (B, Hq, S, D), std, dtype),
+        "k_cache": _normal(seed, "k_cache", 0, (B, Hkv, cap, D), std, dtype),
+        "v_cache": _normal(seed, "v_cache", 0, (B, Hkv, cap, D), std, dtype),
+        "k_block": _normal(seed, "k_block", 0, (B, Hkv, K, D), std, dtype),
+        "v_block": _normal(seed, "v_block", 0, (B, Hkv, K, D), std, dtype),
+        "k_suffix": _normal(seed, "k_suffix", 0, (B, Hkv, S, D), std, dtype),
+        "v_suffix": _normal(seed, "v_suffix", 0, (B, Hkv, S, D), std, dtype),
+        "keep_idx": keep_idx,
+    }
+    return out
+
+
+def make_masked(w: Workload, seed: int = 0, B: Optional[int] = None, K: Optional[int] = None,
+                rule: Optional[str] = None) -> np.ndarray:
+    B = w.B if B is None else B
+    K = w.K if K is None else K
+    rule = w.masked_rule if rule is None else rule
+    g = _rng(seed, "masked", 0)
+    masked = np.zeros((B, K), dtype=np.uint8)
+    for b in range(B):
+        if rule == "all":
+            m = K
+        elif rule == "half":
+            m = K // 2
+        elif rule == "fraction":
+            f = g.uniform(0.1, 1.0)
+            m = max(1, int(np.floor(K * f)))
+        else:
+            raise ValueError(rule)
+        pos = g.permutation(K)[:m]
+        masked[b, pos] = 1
+    return masked
+
+
+def make_logits(dtype: str, B: int, K: int, V: int, std: float, boost: bool, seed: int = 0,
+                ld: Optional[int] = None, step: int = 0) -> np.ndarray:
+    """[B,K,ld] logits ~ N(0, std^2); with `boost`, one seeded random token per row is
+    overwritten with u ~ U(18, 26) so that max-probabilities straddle the threshold."""
+    ld = V if ld is None else ld
+    assert ld >= V
+    g = _rng(seed, "logits", step)
+    x = g.standard_normal(size=(B, K, ld), dtype=np.float32)
+    x *= np.float32(std)
+    if boost:
+        gb = _rng(seed, "boost", step)
+        tok = gb.integers(0, V, size=(B, K))
+        val = gb.uniform(18.0, 26.0, size=(B, K)).astype(np.float32)
+        bi, ki = np.meshgrid(np.arange(B), np.arange(K), indexing="ij")
+        x[bi, ki, tok] = val
+    if dtype == "bf16":
+        return f32_to_bf16_bits(x)
+    return x
+
+
+def make_unmask_inputs(w: Workload, seed: int = 0, step: int = 0, ld: Optional[int] = None) -> Dict[str, np.ndarray]:
+    masked = make_masked(w, seed)
+    g = _rng(seed, "tokens", 0)
+    tokens = g.integers(0, w.V, size=(w.B, w.K)).astype(np.int32)
+    tokens[masked != 0] = MASK_TOKEN
+    return {
+        "logits": make_logits(w.dtype, w.B, w.K, w.V, w.logit_std, w.boost, seed, ld, step),
+        "tokens": tokens,
+        "masked": masked,
+        "eos_seen": np.zeros((w.B,), dtype=np.uint8),
+    }
+
+
+def make_append_inputs(dtype: str, n_layers: int, B: int, Hkv: int, D: int, K: int, cap: int,
+                       seed: int = 0) -> Dict[str, np.ndarray]:
+    """Caches [L,B,Hkv,cap,D] pre-filled with seeded data (so untouched rows can be
+    checked bit-for-bit) and block K/V [L,B,Hkv,K,D]."""
+    return {
+        "k_caches": _normal(seed, "k_caches", 0, (n_layers, B, Hkv, cap, D), 1.0, dtype),
+        "v_caches": _normal(seed, "v_caches", 0, (n_layers, B, Hkv, cap, D), 1.0, dtype),
+        "k_blocks": _normal(seed, "k_blocks", 0, (n_layers, B, Hkv, K, D), 1.0, dtype),
+        "v_blocks": _normal(seed, "v_blocks", 0, (n_layers, B, Hkv, K, D), 1.0, dtype),
+    }
