@@ -1,0 +1,196 @@
+/*
+ * sdllm.h -- C ABI of the MI355X (gfx950) hot path of one Streaming-dLLM
+ * block-wise diffusion decode step.
+ *
+ * Three operations, one call each:
+ *   sdllm_block_attention    bidirectional attention of (active block + kept suffix)
+ *                            queries over (prefix cache + active block + kept suffix) K/V
+ *   sdllm_confidence_unmask  vocab softmax -> max-probability / argmax -> dynamic-threshold
+ *                            commit -> block-done / EOS early-exit flags
+ *   sdllm_kv_append          copy the finished block's K/V into the prefix cache
+ *
+ * Conventions common to all calls
+ *   - Every buffer is CALLER-ALLOCATED DEVICE memory unless said otherwise; the library
+ *     never allocates, frees or keeps a pointer.  Scratch memory comes from a caller-provided
+ *     device workspace whose size the *_workspace_bytes query returns (0 = none needed).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work: they never synchronise and never read device data on the host.  Results,
+ *     including counters and flags, land in device memory.
+ *   - Layouts are row-major with the last dimension contiguous: [B, H, T, D].  All base
+ *     pointers must be 16-byte aligned.
+ *   - dtype is SDLLM_FP32 (float) or SDLLM_BF16 (bfloat16 bit patterns, uint16_t).
+ *   - Return value: SDLLM_OK or an SDLLM_ERR_* code.  Argument validation happens on the
+ *     host before any HIP call, so it works on a machine without a GPU.  A human-readable
+ *     message for the calling thread's last failure is available from sdllm_last_error().
+ *   - Concurrent calls are allowed when they use different workspaces and outputs.
+ */
+#ifndef SDLLM_H
+#define SDLLM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SDLLM_VERSION 100
+
+enum {
+  SDLLM_OK = 0,
+  SDLLM_ERR_INVALID_ARG = 1, /* NULL pointer, negative size, inconsistent shape, misalignment */
+  SDLLM_ERR_UNSUPPORTED = 2, /* dtype / head_dim / size outside the compiled set              */
+  SDLLM_ERR_WORKSPACE = 3,   /* workspace NULL or smaller than *_workspace_bytes()            */
+  SDLLM_ERR_HIP = 4          /* a HIP launch failed; text in sdllm_last_error()               */
+};
+
+enum { SDLLM_FP32 = 0, SDLLM_BF16 = 1 };
+
+/* ---------------------------------------------------------------------------------------
+ * Attention over the pruned sequence  x~ = prefix U current U kept-suffix  (paper Eq. 8).
+ * The queries are the current block and the kept suffix; they attend, without any mask
+ * (bidirectional), to the K/V of the whole pruned sequence (paper section 3.3, paragraph
+ * after Eq. 8; bidirectionality: sections 1 and 3.2).  The kept suffix rows are selected
+ * on the device through keep_idx; nothing is materialised.
+ *
+ *   B, Hq, Hkv, D   batch, query heads, KV heads (Hq % Hkv == 0; query head h reads KV head
+ *                   h / (Hq/Hkv)), head dim.  bf16: D in {64, 128}; fp32: D % 4 == 0, D <= 256.
+ *   prefix_len      P: valid rows of the caches (prompt + committed blocks), >= 0
+ *   prefix_cap      row capacity of the caches (row stride of the cache's T axis), >= P
+ *   K               block length (>= 1);  S: full suffix length (>= 0)
+ *   n_keep          s: number of kept suffix rows, 0 <= s <= S
+ *   scale           softmax scale; <= 0 selects 1/sqrt(D)
+ *   kv_splits       0 = choose automatically; n >= 1 forces n key-range splits (bf16 only)
+ * ------------------------------------------------------------------------------------- */
+typedef struct sdllm_attn_params {
+  int32_t dtype;
+  int32_t B, Hq, Hkv, D;
+  int32_t prefix_len, prefix_cap;
+  int32_t K, S, n_keep;
+  float scale;
+  int32_t kv_splits;
+} sdllm_attn_params;
+
+/* Bytes of device workspace sdllm_block_attention needs for these parameters (0 if none);
+ * (size_t)-1 if the parameters are invalid. */
+size_t sdllm_attention_workspace_bytes(const sdllm_attn_params* p);
+
+/*
+ *   q_block  [B,Hq,K,D]        q_suffix [B,Hq,S,D]      (q_suffix may be NULL iff n_keep == 0)
+ *   k_cache, v_cache [B,Hkv,prefix_cap,D]  rows 0..P-1 are read  (may be NULL iff P == 0)
+ *   k_block, v_block [B,Hkv,K,D]
+ *   k_suffix, v_suffix [B,Hkv,S,D]                         (may be NULL iff n_keep == 0)
+ *   keep_idx [n_keep] int32 on the device, shared by the batch; PRECONDITION (not checked,
+ *            it would need a sync): strictly increasing, every value in [0, S).
+ *   out      [B,Hq,K+n_keep,D], same dtype: block rows first, then the kept suffix rows in
+ *            keep_idx order.  Written entirely.
+ * Inputs are only read.  Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP.
+ */
+int sdllm_block_attention(const sdllm_attn_params* p,
+                          const void* q_block, const void* q_suffix,
+                          const void* k_cache, const void* v_cache,
+                          const void* k_block, const void* v_block,
+                          const void* k_suffix, const void* v_suffix,
+                          const int32_t* keep_idx,
+                          void* out,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Confidence-aware unmasking of the active block.
+ *   For every masked position i (paper Eq. 4):  xhat_i = argmax_j z_ij (lowest id on ties),
+ *   c_i = max softmax(z_i) = 1 / sum_j exp(z_ij - max_j z_ij).
+ *   Threshold (paper Eq. 10):  tau = tau0 * (1 - alpha * (1 - r_mask)),
+ *   r_mask = (m + r_extra_masked) / (K + r_extra_total), m = masked positions of this
+ *   sequence's block before the call (r_extra_* = 0: ratio over the block; = n_keep: ratio over
+ *   the whole query).
+ *   Selection (paper Eq. 9 and the sentence before it): commit every masked i with
+ *   c_i >= tau; if there is none, commit the single masked position of highest confidence
+ *   (lowest position on ties).  Update (paper Eq. 5): committed positions get tokens = xhat,
+ *   masked = 0; every other element of tokens / masked is left untouched.
+ *   block_done[b] = 1 iff no masked position is left (end of paper section 3.1), else 0.
+ *   eos_seen[b] is OR-ed with (a token committed by this call equals eos_id and its
+ *   confidence >= tau_eos) -- the early-exit test of paper section 3.3; skipped if eos_id < 0.
+ *   Sequences are independent (per-sequence m, tau, fallback, flags).
+ *
+ *   dtype of logits, B, K (1..4096), V (>= 1), ld = row stride of logits in elements (>= V;
+ *   ld * sizeof(element) must be a multiple of 16).
+ * ------------------------------------------------------------------------------------- */
+typedef struct sdllm_unmask_params {
+  int32_t dtype;
+  int32_t B, K, V;
+  int64_t ld;
+  float tau0, alpha;
+  int32_t r_extra_masked, r_extra_total;
+  int32_t eos_id;
+  float tau_eos;
+} sdllm_unmask_params;
+
+size_t sdllm_unmask_workspace_bytes(const sdllm_unmask_params* p);
+
+/*
+ *   logits      [B,K,ld]  read only; only rows of masked positions are read
+ *   tokens      [B,K] int32   in/out        masked [B,K] uint8 (0 / non-zero)  in/out
+ *   confidence  [B,K] float   out, optional (NULL ok): c_i for positions masked on entry,
+ *               other entries untouched
+ *   n_committed [B] int32 out      block_done [B] uint8 out
+ *   eos_seen    [B] uint8 in/out, optional (NULL ok)
+ */
+int sdllm_confidence_unmask(const sdllm_unmask_params* p,
+                            const void* logits,
+                            int32_t* tokens, uint8_t* masked,
+                            float* confidence,
+                            int32_t* n_committed, uint8_t* block_done,
+                            uint8_t* eos_seen,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * KV append: the prefix K/V is kept and reused instead of recomputed (paper section 3.3,
+ * first paragraph on decoding).  When a block is finished its K/V rows become rows
+ * P..P+K-1 of every layer's cache:
+ *     cache[l][b,h,P+r,:] <- block[l][b,h,r,:]   for all layers, K and V, bit for bit.
+ * Nothing else in the caches is written.  The caller then advances prefix_len by K.
+ *
+ *   n_layers >= 1; B, Hkv, D, K >= 1; prefix_len + K <= prefix_cap; D * sizeof(element) % 16 == 0
+ *   cache_layer_stride / block_layer_stride: distance between layers in ELEMENTS
+ *   (0 = densely packed: B*Hkv*prefix_cap*D resp. B*Hkv*K*D).
+ * ------------------------------------------------------------------------------------- */
+typedef struct sdllm_append_params {
+  int32_t dtype;
+  int32_t n_layers, B, Hkv, D, K;
+  int32_t prefix_len, prefix_cap;
+  int64_t cache_layer_stride, block_layer_stride;
+} sdllm_append_params;
+
+/*
+ *   k_caches, v_caches [n_layers][B,Hkv,prefix_cap,D]  in/out
+ *   k_blocks, v_blocks [n_layers][B,Hkv,K,D]           read only
+ *   do_append [B] uint8 on the device, or NULL = every sequence; sequences with 0 are skipped
+ */
+int sdllm_kv_append(const sdllm_append_params* p,
+                    void* k_caches, void* v_caches,
+                    const void* k_blocks, const void* v_blocks,
+                    const uint8_t* do_append,
+                    void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Diagnostics.  sdllm_plan_attention reports the launch plan the library would use (host
+ * only, no HIP call): number of key-range splits, query rows per workgroup, workgroups.
+ * Returns SDLLM_OK or the validation error.
+ * ------------------------------------------------------------------------------------- */
+typedef struct sdllm_attn_plan {
+  int32_t kv_splits;
+  int32_t rows_per_workgroup;
+  int32_t workgroups;
+  int32_t key_tiles_per_split;
+} sdllm_attn_plan;
+
+int sdllm_plan_attention(const sdllm_attn_params* p, sdllm_attn_plan* plan);
+
+const char* sdllm_status_string(int status);
+const char* sdllm_last_error(void); /* calling thread's last failure text ("" if none) */
+int sdllm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SDLLM_H */

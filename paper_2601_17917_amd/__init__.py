@@ -1,0 +1,230 @@
+"""Thin Python binding of the sdllm C ABI (include/sdllm.h).
+
+Argument marshalling only: every step of the hot path runs in the HIP kernels of
+libsdllm.so.  PyTorch tensors provide device memory and the stream.  There is no CPU
+fallback: if the library has not been built, `load_library` raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsdllm.so")
+
+SDLLM_OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
+FP32, BF16 = 0, 1
+
+EXPORTED_SYMBOLS = (
+    "sdllm_block_attention", "sdllm_attention_workspace_bytes", "sdllm_plan_attention",
+    "sdllm_confidence_unmask", "sdllm_unmask_workspace_bytes",
+    "sdllm_kv_append",
+    "sdllm_status_string", "sdllm_last_error", "sdllm_version",
+)
+
+
+class AttnParams(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+                ("D", ctypes.c_int32), ("prefix_len", ctypes.c_int32), ("prefix_cap", ctypes.c_int32),
+                ("K", ctypes.c_int32), ("S", ctypes.c_int32), ("n_keep", ctypes.c_int32),
+                ("scale", ctypes.c_float), ("kv_splits", ctypes.c_int32)]
+
+
+class UnmaskParams(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("B", ctypes.c_int32), ("K", ctypes.c_int32), ("V", ctypes.c_int32),
+                ("ld", ctypes.c_int64), ("tau0", ctypes.c_float), ("alpha", ctypes.c_float),
+                ("r_extra_masked", ctypes.c_int32), ("r_extra_total", ctypes.c_int32),
+                ("eos_id", ctypes.c_int32), ("tau_eos", ctypes.c_float)]
+
+
+class AppendParams(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("n_layers", ctypes.c_int32), ("B", ctypes.c_int32),
+                ("Hkv", ctypes.c_int32), ("D", ctypes.c_int32), ("K", ctypes.c_int32),
+                ("prefix_len", ctypes.c_int32), ("prefix_cap", ctypes.c_int32),
+                ("cache_layer_stride", ctypes.c_int64), ("block_layer_stride", ctypes.c_int64)]
+
+
+class AttnPlan(ctypes.Structure):
+    _fields_ = [("kv_splits", ctypes.c_int32), ("rows_per_workgroup", ctypes.c_int32),
+                ("workgroups", ctypes.c_int32), ("key_tiles_per_split", ctypes.c_int32)]
+
+
+class SdllmError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"sdllm status {status}: {text}")
+        self.status = status
+
+
+_lib = None
+
+
+def load_library(path: Optional[str] = None):
+    """Load libsdllm.so (once).  Raises if it has not been built -- there is no fallback."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = path or LIB_PATH
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} not found: build it with `python -m paper_2601_17917_amd.build`")
+    lib = ctypes.CDLL(path)
+    vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+    lib.sdllm_version.restype = i32
+    lib.sdllm_last_error.restype = ctypes.c_char_p
+    lib.sdllm_status_string.restype = ctypes.c_char_p
+    lib.sdllm_status_string.argtypes = [i32]
+    lib.sdllm_attention_workspace_bytes.restype = sz
+    lib.sdllm_attention_workspace_bytes.argtypes = [ctypes.POINTER(AttnParams)]
+    lib.sdllm_plan_attention.restype = i32
+    lib.sdllm_plan_attention.argtypes = [ctypes.POINTER(AttnParams), ctypes.POINTER(AttnPlan)]
+    lib.sdllm_block_attention.restype = i32
+    lib.sdllm_block_attention.argtypes = [ctypes.POINTER(AttnParams)] + [vp] * 10 + [vp, sz, vp]
+    lib.sdllm_unmask_workspace_bytes.restype = sz
+    lib.sdllm_unmask_workspace_bytes.argtypes = [ctypes.POINTER(UnmaskParams)]
+    lib.sdllm_confidence_unmask.restype = i32
+    lib.sdllm_confidence_unmask.argtypes = [ctypes.POINTER(UnmaskParams)] + [vp] * 7 + [vp, sz, vp]
+    lib.sdllm_kv_append.restype = i32
+    lib.sdllm_kv_append.argtypes = [ctypes.POINTER(AppendParams)] + [vp] * 5 + [vp]
+    _lib = lib
+    return lib
+
+
+def _check(status: int):
+    if status != SDLLM_OK:
+        raise SdllmError(status, load_library().sdllm_last_error().decode())
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.float32:
+        return FP32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise SdllmError(ERR_UNSUPPORTED, f"dtype {t.dtype} not supported (float32, bfloat16)")
+
+
+def _require(t, name, dtype=None):
+    if t is None:
+        return
+    if not t.is_cuda:
+        raise SdllmError(ERR_INVALID_ARG, f"{name} must be a device tensor")
+    if not t.is_contiguous():
+        raise SdllmError(ERR_INVALID_ARG, f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise SdllmError(ERR_INVALID_ARG, f"{name} must have dtype {dtype}, has {t.dtype}")
+
+
+# ---------------------------------------------------------------------------------------------
+def attn_params(dtype, B, Hq, Hkv, D, prefix_len, prefix_cap, K, S, n_keep, scale=0.0, kv_splits=0) -> AttnParams:
+    return AttnParams(dtype, B, Hq, Hkv, D, prefix_len, prefix_cap, K, S, n_keep, scale, kv_splits)
+
+
+def attention_workspace_bytes(p: AttnParams) -> int:
+    n = load_library().sdllm_attention_workspace_bytes(ctypes.byref(p))
+    if n == ctypes.c_size_t(-1).value:
+        raise SdllmError(ERR_INVALID_ARG, load_library().sdllm_last_error().decode())
+    return n
+
+
+def plan_attention(p: AttnParams) -> AttnPlan:
+    plan = AttnPlan()
+    _check(load_library().sdllm_plan_attention(ctypes.byref(p), ctypes.byref(plan)))
+    return plan
+
+
+def block_attention(q_block, q_suffix, k_cache, v_cache, k_block, v_block, k_suffix, v_suffix, keep_idx,
+                    prefix_len: int, out=None, scale: float = 0.0, kv_splits: int = 0, workspace=None, stream=None):
+    """sdllm_block_attention.  Tensors in [B,H,T,D] layout; returns out [B,Hq,K+n_keep,D].
+    The cache tensors may be None when prefix_len == 0, the suffix tensors when keep_idx is empty."""
+    import torch
+    B, Hq, K, D = q_block.shape
+    Hkv = k_block.shape[1]
+    S = 0 if q_suffix is None else q_suffix.shape[2]
+    n_keep = 0 if keep_idx is None else int(keep_idx.shape[0])
+    cap = prefix_len if k_cache is None else k_cache.shape[2]
+    for name, t in (("q_block", q_block), ("q_suffix", q_suffix), ("k_cache", k_cache), ("v_cache", v_cache),
+                    ("k_block", k_block), ("v_block", v_block), ("k_suffix", k_suffix), ("v_suffix", v_suffix)):
+        _require(t, name, q_block.dtype)
+    _require(keep_idx, "keep_idx", torch.int32)
+    p = attn_params(_dtype_code(q_block), B, Hq, Hkv, D, prefix_len, cap, K, S, n_keep, scale, kv_splits)
+    if out is None:
+        out = torch.empty((B, Hq, K + n_keep, D), dtype=q_block.dtype, device=q_block.device)
+    _require(out, "out", q_block.dtype)
+    need = attention_workspace_bytes(p)
+    if need and workspace is None:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=q_block.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    kidx = keep_idx if n_keep else None
+    _check(load_library().sdllm_block_attention(
+        ctypes.byref(p), _ptr(q_block), _ptr(q_suffix), _ptr(k_cache), _ptr(v_cache), _ptr(k_block), _ptr(v_block),
+        _ptr(k_suffix), _ptr(v_suffix), _ptr(kidx), _ptr(out), _ptr(workspace), ws_bytes, _stream(stream)))
+    return out
+
+
+# ---------------------------------------------------------------------------------------------
+def unmask_params(dtype, B, K, V, ld, tau0, alpha, r_extra_masked=0, r_extra_total=0, eos_id=-1,
+                  tau_eos=None) -> UnmaskParams:
+    return UnmaskParams(dtype, B, K, V, ld, tau0, alpha, r_extra_masked, r_extra_total, eos_id,
+                        tau0 if tau_eos is None else tau_eos)
+
+
+def unmask_workspace_bytes(p: UnmaskParams) -> int:
+    n = load_library().sdllm_unmask_workspace_bytes(ctypes.byref(p))
+    if n == ctypes.c_size_t(-1).value:
+        raise SdllmError(ERR_INVALID_ARG, load_library().sdllm_last_error().decode())
+    return n
+
+
+def confidence_unmask(logits, tokens, masked, tau0: float, alpha: float, V: Optional[int] = None,
+                      confidence=None, n_committed=None, block_done=None, eos_seen=None, eos_id: int = -1,
+                      tau_eos: Optional[float] = None, r_extra_masked: int = 0, r_extra_total: int = 0,
+                      workspace=None, stream=None):
+    """sdllm_confidence_unmask.  logits [B,K,ld]; tokens int32 [B,K] and masked uint8 [B,K] are updated
+    in place.  Returns (n_committed int32 [B], block_done uint8 [B])."""
+    import torch
+    B, K, ld = logits.shape
+    V = ld if V is None else V
+    _require(logits, "logits")
+    _require(tokens, "tokens", torch.int32)
+    _require(masked, "masked", torch.uint8)
+    _require(confidence, "confidence", torch.float32)
+    _require(eos_seen, "eos_seen", torch.uint8)
+    if n_committed is None:
+        n_committed = torch.empty((B,), dtype=torch.int32, device=logits.device)
+    if block_done is None:
+        block_done = torch.empty((B,), dtype=torch.uint8, device=logits.device)
+    _require(n_committed, "n_committed", torch.int32)
+    _require(block_done, "block_done", torch.uint8)
+    p = unmask_params(_dtype_code(logits), B, K, V, ld, tau0, alpha, r_extra_masked, r_extra_total, eos_id, tau_eos)
+    need = unmask_workspace_bytes(p)
+    if workspace is None:
+        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=logits.device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    _check(load_library().sdllm_confidence_unmask(
+        ctypes.byref(p), _ptr(logits), _ptr(tokens), _ptr(masked), _ptr(confidence), _ptr(n_committed),
+        _ptr(block_done), _ptr(eos_seen), _ptr(workspace), ws_bytes, _stream(stream)))
+    return n_committed, block_done
+
+
+# ---------------------------------------------------------------------------------------------
+def kv_append(k_caches, v_caches, k_blocks, v_blocks, prefix_len: int, do_append=None, stream=None):
+    """sdllm_kv_append.  caches [L,B,Hkv,cap,D] (updated in place), blocks [L,B,Hkv,K,D]."""
+    import torch
+    L, B, Hkv, cap, D = k_caches.shape
+    K = k_blocks.shape[3]
+    for name, t in (("k_caches", k_caches), ("v_caches", v_caches), ("k_blocks", k_blocks), ("v_blocks", v_blocks)):
+        _require(t, name, k_caches.dtype)
+    _require(do_append, "do_append", torch.uint8)
+    p = AppendParams(_dtype_code(k_caches), L, B, Hkv, D, K, prefix_len, cap, 0, 0)
+    _check(load_library().sdllm_kv_append(ctypes.byref(p), _ptr(k_caches), _ptr(v_caches), _ptr(k_blocks),
+                                          _ptr(v_blocks), _ptr(do_append), _stream(stream)))

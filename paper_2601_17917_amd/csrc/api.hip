@@ -1,0 +1,205 @@
+// Host side of the C ABI: argument validation (before any HIP call), plan / workspace queries,
+// error text, dispatch to the kernel launchers.
+#include "common.h"
+#include <cstdio>
+#include <cstdarg>
+#include <cstring>
+#include <cmath>
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_attn_params(const sdllm_attn_params* p) {
+  if (!p) return fail(SDLLM_ERR_INVALID_ARG, "attention: params is NULL");
+  if (p->dtype != SDLLM_FP32 && p->dtype != SDLLM_BF16)
+    return fail(SDLLM_ERR_UNSUPPORTED, "attention: dtype %d not supported (fp32=0, bf16=1)", p->dtype);
+  if (p->B < 1 || p->Hq < 1 || p->Hkv < 1 || p->D < 1 || p->K < 1)
+    return fail(SDLLM_ERR_INVALID_ARG, "attention: B, Hq, Hkv, D, K must be >= 1");
+  if (p->Hq % p->Hkv != 0)
+    return fail(SDLLM_ERR_INVALID_ARG, "attention: Hq (%d) must be a multiple of Hkv (%d)", p->Hq, p->Hkv);
+  if (p->prefix_len < 0 || p->prefix_cap < p->prefix_len)
+    return fail(SDLLM_ERR_INVALID_ARG, "attention: need 0 <= prefix_len (%d) <= prefix_cap (%d)", p->prefix_len, p->prefix_cap);
+  if (p->S < 0 || p->n_keep < 0 || p->n_keep > p->S)
+    return fail(SDLLM_ERR_INVALID_ARG, "attention: need 0 <= n_keep (%d) <= S (%d)", p->n_keep, p->S);
+  if (p->kv_splits < 0) return fail(SDLLM_ERR_INVALID_ARG, "attention: kv_splits must be >= 0");
+  if (!(p->scale == p->scale) || std::isinf(p->scale)) return fail(SDLLM_ERR_INVALID_ARG, "attention: scale is not finite");
+  if (p->dtype == SDLLM_BF16) {
+    if (p->D != 64 && p->D != 128)
+      return fail(SDLLM_ERR_UNSUPPORTED, "attention: bf16 head_dim %d not compiled (64, 128)", p->D);
+  } else {
+    if (p->D % 4 != 0 || p->D > 256)
+      return fail(SDLLM_ERR_UNSUPPORTED, "attention: fp32 head_dim %d not supported (multiple of 4, <= 256)", p->D);
+    if (p->Hq > 65535 || p->B > 65535)
+      return fail(SDLLM_ERR_UNSUPPORTED, "attention: fp32 path needs Hq, B <= 65535");
+  }
+  const long long nkv = (long long)p->prefix_len + p->K + p->n_keep;
+  const long long rows = (long long)p->B * p->Hq * (p->K + p->n_keep);
+  if (nkv > (1LL << 30) || rows > (1LL << 31) - 1)
+    return fail(SDLLM_ERR_UNSUPPORTED, "attention: sequence or batch too large");
+  return SDLLM_OK;
+}
+
+int check_unmask_params(const sdllm_unmask_params* p) {
+  if (!p) return fail(SDLLM_ERR_INVALID_ARG, "unmask: params is NULL");
+  if (p->dtype != SDLLM_FP32 && p->dtype != SDLLM_BF16)
+    return fail(SDLLM_ERR_UNSUPPORTED, "unmask: dtype %d not supported (fp32=0, bf16=1)", p->dtype);
+  if (p->B < 1 || p->K < 1 || p->V < 1) return fail(SDLLM_ERR_INVALID_ARG, "unmask: B, K, V must be >= 1");
+  if (p->K > 4096) return fail(SDLLM_ERR_UNSUPPORTED, "unmask: K (%d) > 4096", p->K);
+  if (p->ld < p->V) return fail(SDLLM_ERR_INVALID_ARG, "unmask: ld (%lld) < V (%d)", (long long)p->ld, p->V);
+  const int elem = p->dtype == SDLLM_FP32 ? 4 : 2;
+  if ((p->ld * elem) % 16 != 0)
+    return fail(SDLLM_ERR_INVALID_ARG, "unmask: ld * element size (%lld bytes) must be a multiple of 16", (long long)p->ld * elem);
+  if ((long long)p->B * p->K > (1LL << 24)) return fail(SDLLM_ERR_UNSUPPORTED, "unmask: B*K too large");
+  if (p->r_extra_masked < 0 || p->r_extra_total < p->r_extra_masked)
+    return fail(SDLLM_ERR_INVALID_ARG, "unmask: need 0 <= r_extra_masked <= r_extra_total");
+  if (!(p->tau0 == p->tau0) || !(p->alpha == p->alpha) || !(p->tau_eos == p->tau_eos))
+    return fail(SDLLM_ERR_INVALID_ARG, "unmask: tau0 / alpha / tau_eos is NaN");
+  return SDLLM_OK;
+}
+
+int check_append_params(const sdllm_append_params* p) {
+  if (!p) return fail(SDLLM_ERR_INVALID_ARG, "kv_append: params is NULL");
+  if (p->dtype != SDLLM_FP32 && p->dtype != SDLLM_BF16)
+    return fail(SDLLM_ERR_UNSUPPORTED, "kv_append: dtype %d not supported (fp32=0, bf16=1)", p->dtype);
+  if (p->n_layers < 1 || p->B < 1 || p->Hkv < 1 || p->D < 1 || p->K < 1)
+    return fail(SDLLM_ERR_INVALID_ARG, "kv_append: n_layers, B, Hkv, D, K must be >= 1");
+  if (p->prefix_len < 0 || (long long)p->prefix_len + p->K > p->prefix_cap)
+    return fail(SDLLM_ERR_INVALID_ARG, "kv_append: prefix_len (%d) + K (%d) exceeds prefix_cap (%d)", p->prefix_len, p->K, p->prefix_cap);
+  const int elem = p->dtype == SDLLM_FP32 ? 4 : 2;
+  if ((p->D * elem) % 16 != 0)
+    return fail(SDLLM_ERR_UNSUPPORTED, "kv_append: row size %d bytes must be a multiple of 16", p->D * elem);
+  const long long dense_c = (long long)p->B * p->Hkv * p->prefix_cap * p->D;
+  const long long dense_b = (long long)p->B * p->Hkv * p->K * p->D;
+  if (p->cache_layer_stride != 0 && (p->cache_layer_stride < dense_c || (p->cache_layer_stride * elem) % 16 != 0))
+    return fail(SDLLM_ERR_INVALID_ARG, "kv_append: cache_layer_stride too small or not 16-byte aligned");
+  if (p->block_layer_stride != 0 && (p->block_layer_stride < dense_b || (p->block_layer_stride * elem) % 16 != 0))
+    return fail(SDLLM_ERR_INVALID_ARG, "kv_append: block_layer_stride too small or not 16-byte aligned");
+  return SDLLM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sdllm_version(void) { return SDLLM_VERSION; }
+
+const char* sdllm_last_error(void) { return g_err; }
+
+const char* sdllm_status_string(int status) {
+  switch (status) {
+    case SDLLM_OK: return "ok";
+    case SDLLM_ERR_INVALID_ARG: return "invalid argument";
+    case SDLLM_ERR_UNSUPPORTED: return "unsupported dtype / shape";
+    case SDLLM_ERR_WORKSPACE: return "workspace missing or too small";
+    case SDLLM_ERR_HIP: return "HIP launch failure";
+    default: return "unknown status";
+  }
+}
+
+int sdllm_plan_attention(const sdllm_attn_params* p, sdllm_attn_plan* plan) {
+  int rc = check_attn_params(p);
+  if (rc != SDLLM_OK) return rc;
+  if (!plan) return fail(SDLLM_ERR_INVALID_ARG, "plan_attention: plan is NULL");
+  if (p->dtype == SDLLM_FP32) {
+    plan->kv_splits = 1; plan->rows_per_workgroup = 4;
+    plan->workgroups = ((p->K + p->n_keep + 3) / 4) * p->Hq * p->B;
+    plan->key_tiles_per_split = (p->prefix_len + p->K + p->n_keep + 63) / 64;
+    return SDLLM_OK;
+  }
+  sdllm::AttnPlan pl = sdllm::plan_attention_bf16(*p);
+  plan->kv_splits = pl.kv_splits; plan->rows_per_workgroup = 64 * pl.rb;
+  plan->workgroups = pl.workgroups; plan->key_tiles_per_split = pl.tiles_per_split;
+  return SDLLM_OK;
+}
+
+size_t sdllm_attention_workspace_bytes(const sdllm_attn_params* p) {
+  if (check_attn_params(p) != SDLLM_OK) return (size_t)-1;
+  if (p->dtype == SDLLM_FP32) return 0;
+  return sdllm::attention_bf16_workspace_bytes(*p, sdllm::plan_attention_bf16(*p));
+}
+
+int sdllm_block_attention(const sdllm_attn_params* p,
+                          const void* q_block, const void* q_suffix,
+                          const void* k_cache, const void* v_cache,
+                          const void* k_block, const void* v_block,
+                          const void* k_suffix, const void* v_suffix,
+                          const int32_t* keep_idx, void* out,
+                          void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_attn_params(p);
+  if (rc != SDLLM_OK) return rc;
+  if (!q_block || !k_block || !v_block || !out)
+    return fail(SDLLM_ERR_INVALID_ARG, "attention: q_block, k_block, v_block, out must not be NULL");
+  if (p->prefix_len > 0 && (!k_cache || !v_cache))
+    return fail(SDLLM_ERR_INVALID_ARG, "attention: k_cache / v_cache is NULL with prefix_len > 0");
+  if (p->n_keep > 0 && (!q_suffix || !k_suffix || !v_suffix || !keep_idx))
+    return fail(SDLLM_ERR_INVALID_ARG, "attention: q_suffix / k_suffix / v_suffix / keep_idx is NULL with n_keep > 0");
+  const void* ptrs[] = {q_block, q_suffix, k_cache, v_cache, k_block, v_block, k_suffix, v_suffix, out, workspace};
+  for (const void* q : ptrs)
+    if (q && !aligned16(q)) return fail(SDLLM_ERR_INVALID_ARG, "attention: a base pointer is not 16-byte aligned");
+  if (p->dtype == SDLLM_FP32) {
+    hipError_t e = sdllm::launch_attention_f32(*p, q_block, q_suffix, k_cache, v_cache, k_block, v_block,
+                                               k_suffix, v_suffix, keep_idx, out, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(SDLLM_ERR_HIP, "attention (fp32): %s", hipGetErrorString(e));
+    return SDLLM_OK;
+  }
+  sdllm::AttnPlan pl = sdllm::plan_attention_bf16(*p);
+  const size_t need = sdllm::attention_bf16_workspace_bytes(*p, pl);
+  if (need > 0 && (!workspace || workspace_bytes < need))
+    return fail(SDLLM_ERR_WORKSPACE, "attention: workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : (size_t)0);
+  hipError_t e = sdllm::launch_attention_bf16(*p, pl, q_block, q_suffix, k_cache, v_cache, k_block, v_block,
+                                              k_suffix, v_suffix, keep_idx, out, need ? workspace : nullptr,
+                                              (hipStream_t)stream);
+  if (e != hipSuccess) return fail(SDLLM_ERR_HIP, "attention (bf16): %s", hipGetErrorString(e));
+  return SDLLM_OK;
+}
+
+size_t sdllm_unmask_workspace_bytes(const sdllm_unmask_params* p) {
+  if (check_unmask_params(p) != SDLLM_OK) return (size_t)-1;
+  return sdllm::unmask_workspace_bytes(*p);
+}
+
+int sdllm_confidence_unmask(const sdllm_unmask_params* p, const void* logits,
+                            int32_t* tokens, uint8_t* masked, float* confidence,
+                            int32_t* n_committed, uint8_t* block_done, uint8_t* eos_seen,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_unmask_params(p);
+  if (rc != SDLLM_OK) return rc;
+  if (!logits || !tokens || !masked || !n_committed || !block_done)
+    return fail(SDLLM_ERR_INVALID_ARG, "unmask: logits, tokens, masked, n_committed, block_done must not be NULL");
+  if (!aligned16(logits)) return fail(SDLLM_ERR_INVALID_ARG, "unmask: logits is not 16-byte aligned");
+  const size_t need = sdllm::unmask_workspace_bytes(*p);
+  if (!workspace || workspace_bytes < need)
+    return fail(SDLLM_ERR_WORKSPACE, "unmask: workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : (size_t)0);
+  if ((reinterpret_cast<uintptr_t>(workspace) & 3u) != 0)
+    return fail(SDLLM_ERR_INVALID_ARG, "unmask: workspace is not 4-byte aligned");
+  hipError_t e = sdllm::launch_unmask(*p, logits, tokens, masked, confidence, n_committed, block_done, eos_seen,
+                                      workspace, (hipStream_t)stream);
+  if (e != hipSuccess) return fail(SDLLM_ERR_HIP, "unmask: %s", hipGetErrorString(e));
+  return SDLLM_OK;
+}
+
+int sdllm_kv_append(const sdllm_append_params* p, void* k_caches, void* v_caches,
+                    const void* k_blocks, const void* v_blocks, const uint8_t* do_append, void* stream) {
+  int rc = check_append_params(p);
+  if (rc != SDLLM_OK) return rc;
+  if (!k_caches || !v_caches || !k_blocks || !v_blocks)
+    return fail(SDLLM_ERR_INVALID_ARG, "kv_append: caches and blocks must not be NULL");
+  if (!aligned16(k_caches) || !aligned16(v_caches) || !aligned16(k_blocks) || !aligned16(v_blocks))
+    return fail(SDLLM_ERR_INVALID_ARG, "kv_append: a base pointer is not 16-byte aligned");
+  hipError_t e = sdllm::launch_kv_append(*p, k_caches, v_caches, k_blocks, v_blocks, do_append, (hipStream_t)stream);
+  if (e != hipSuccess) return fail(SDLLM_ERR_HIP, "kv_append: %s", hipGetErrorString(e));
+  return SDLLM_OK;
+}
+
+}  // extern "C"

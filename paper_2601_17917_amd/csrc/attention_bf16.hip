@@ -1,0 +1,381 @@
+// bf16 attention over [prefix cache | block | gathered suffix] for gfx950 (paper Eq. 8 and the
+// paragraph after it: block + kept-suffix queries attend, unmasked, to the whole pruned sequence).
+//
+// Work decomposition
+//   group   = (batch, KV head).  The g = Hq/Hkv query heads of a group share its K/V, so their
+//             g*Nq query rows are treated as one list of "virtual rows" and tiled together.
+//   workgroup = (group, query tile of 64*RB rows, key-range split); 4 waves, wave w owns the
+//             16*RB rows  [w*16*RB, (w+1)*16*RB) of the tile for all keys of the split.
+//   K/V tiles of 64 keys are staged in LDS (two stages, one barrier per tile); rows come from
+//             three places (cache, block, suffix[keep_idx]) and are addressed per row, so the
+//             gather costs nothing extra: a row is 16 lanes x 16 B, fully coalesced.
+// Math (all MFMA v_mfma_f32_16x16x32_bf16, fp32 accumulate)
+//   S^T = K Q^T  : A = K rows from LDS, B = Q rows from registers.  The accumulator of lane
+//                  (q = lane%16, G = lane/16) holds keys 16*kb + 4*G + i of query row q, so a
+//                  softmax row reduction is 15 in-lane ops + 2 cross-lane steps.
+//   O^T = V^T P^T: A = V^T through the LDS transpose read (ds_read_b64_tr_b16), B = P^T taken
+//                  straight from the S^T accumulators (same lane layout), converted to bf16.
+//   Online softmax in the log2 domain; a split writes (unnormalised O, m, l) and a second
+//   kernel merges the splits in a fixed order (deterministic, no atomics).
+#include "common.h"
+
+namespace sdllm {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+
+constexpr int kKeyTile = 64;
+constexpr float kLog2eA = 1.4426950408889634f;
+constexpr float kNegBigA = -3.0e38f;
+
+struct AttnArgs {
+  const uint16_t* q_block; const uint16_t* q_suffix;
+  const uint16_t* k_cache; const uint16_t* v_cache;
+  const uint16_t* k_block; const uint16_t* v_block;
+  const uint16_t* k_suffix; const uint16_t* v_suffix;
+  const int32_t* keep_idx;
+  uint16_t* out;
+  float* ws_o;    // [group][virtual row][split][D]   unnormalised partial outputs
+  float* ws_ml;   // [group][virtual row][split][2]   (running max in log2 units, sum)
+  int B, Hq, Hkv, g, P, cap, K, S, n_keep, Nq, Nkv, Rtot;
+  int nsplit, tiles_per_split, key_tiles, q_tiles, n_units;
+  float scale_log2;
+};
+
+__device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  // round-to-nearest-even; inputs are probabilities in [0,1], no NaN handling needed
+  uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
+  a += 0x7fffu + ((a >> 16) & 1u);
+  b += 0x7fffu + ((b >> 16) & 1u);
+  return (a >> 16) | (b & 0xffff0000u);
+}
+
+template <int D, int RB>
+__global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
+  constexpr int LDK = D + 8;                       // padded LDS row, elements (row start shifts 4 banks)
+  constexpr int CPR = D / 8;                       // 16-byte chunks per row
+  constexpr int RPP = 256 / CPR;                   // rows loaded per pass of the workgroup
+  constexpr int NP = kKeyTile / RPP;               // passes per tile
+  constexpr int NS = D / 32;                       // 32-wide d slices (QK^T contraction steps)
+  constexpr int NDB = D / 16;                      // 16-wide d blocks of the output
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+  uint16_t (*Ks)[kKeyTile][LDK] = reinterpret_cast<uint16_t (*)[kKeyTile][LDK]>(lds);
+  uint16_t (*Vs)[kKeyTile][LDK] = reinterpret_cast<uint16_t (*)[kKeyTile][LDK]>(lds + 2 * kKeyTile * LDK);
+
+  // ---- which piece of work: workgroups that share K/V (query tiles of one unit) sit on one XCD
+  const int xcd = blockIdx.x % kNumXCDs, slot = blockIdx.x / kNumXCDs;
+  const int unit = (slot / a.q_tiles) * kNumXCDs + xcd;
+  const int qt = slot % a.q_tiles;
+  if (unit >= a.n_units) return;
+  const int grp = unit / a.nsplit, split = unit - grp * a.nsplit;
+  const int b = grp / a.Hkv, kvh = grp - b * a.Hkv;
+  const int t0 = split * a.tiles_per_split;
+  const int t1 = min(t0 + a.tiles_per_split, a.key_tiles);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, G = lane >> 4;
+
+  const long long bh = (long long)b * a.Hkv + kvh;
+  const uint16_t* kc = a.k_cache + bh * a.cap * D;
+  const uint16_t* vc = a.v_cache + bh * a.cap * D;
+  const uint16_t* kb = a.k_block + bh * a.K * D;
+  const uint16_t* vb = a.v_block + bh * a.K * D;
+  const uint16_t* ks = a.k_suffix + bh * a.S * D;
+  const uint16_t* vs = a.v_suffix + bh * a.S * D;
+
+  // ---- global -> register staging of one K/V tile (rows clamped into the valid range)
+  const int lrow = tid / CPR, lchunk = tid % CPR;
+  uint4 kreg[NP], vreg[NP];
+  auto load_tile = [&](int tile) {
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      int r = tile * kKeyTile + lrow + p * RPP;
+      r = min(r, a.Nkv - 1);
+      const uint16_t* kp; const uint16_t* vp; long long off;
+      if (r < a.P) { kp = kc; vp = vc; off = (long long)r * D; }
+      else if (r < a.P + a.K) { kp = kb; vp = vb; off = (long long)(r - a.P) * D; }
+      else { kp = ks; vp = vs; off = (long long)a.keep_idx[r - a.P - a.K] * D; }
+      off += lchunk * 8;
+      kreg[p] = *reinterpret_cast<const uint4*>(kp + off);
+      vreg[p] = *reinterpret_cast<const uint4*>(vp + off);
+    }
+  };
+  auto store_tile = [&](int stage) {
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      *reinterpret_cast<uint4*>(&Ks[stage][lrow + p * RPP][lchunk * 8]) = kreg[p];
+      *reinterpret_cast<uint4*>(&Vs[stage][lrow + p * RPP][lchunk * 8]) = vreg[p];
+    }
+  };
+
+  load_tile(t0);
+
+  // ---- query rows of this wave, as MFMA B operands (lane: row l16, d = 32*s + 8*G .. +7)
+  const int row_base = qt * (64 * RB) + wave * (16 * RB);
+  bf16x8 qreg[RB][NS];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    int R = min(row_base + rb * 16 + l16, a.Rtot - 1);
+    const int hl = R / a.Nq, qi = R - hl * a.Nq;
+    const long long qbh = (long long)b * a.Hq + (long long)kvh * a.g + hl;
+    const uint16_t* qp = (qi < a.K) ? a.q_block + (qbh * a.K + qi) * D
+                                    : a.q_suffix + (qbh * a.S + a.keep_idx[qi - a.K]) * D;
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+      qreg[rb][s] = *reinterpret_cast<const bf16x8*>(qp + 32 * s + 8 * G);
+  }
+
+  f32x4 o[RB][NDB];
+  float m[RB], lsum[RB];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    m[rb] = kNegBigA; lsum[rb] = 0.f;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) o[rb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  store_tile(0);
+  __syncthreads();
+
+  for (int t = t0; t < t1; ++t) {
+    const int stage = (t - t0) & 1;
+    if (t + 1 < t1) load_tile(t + 1);              // in flight while this tile is computed
+
+    // ---- S^T = K Q^T
+    f32x4 sacc[RB][4];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int kb4 = 0; kb4 < 4; ++kb4) sacc[rb][kb4] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kb4 = 0; kb4 < 4; ++kb4) {
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        const bf16x8 kop = *reinterpret_cast<const bf16x8*>(&Ks[stage][kb4 * 16 + l16][32 * s + 8 * G]);
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+          sacc[rb][kb4] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, qreg[rb][s], sacc[rb][kb4], 0, 0, 0);
+      }
+    }
+
+    // ---- online softmax (log2 domain); keys past Nkv only exist in the last tile
+    const int key0 = t * kKeyTile;
+    const bool ragged = key0 + kKeyTile > a.Nkv;
+    s16x8 pk[RB][2];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      float mx = kNegBigA;
+#pragma unroll
+      for (int kb4 = 0; kb4 < 4; ++kb4)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float v = sacc[rb][kb4][i] * a.scale_log2;
+          if (ragged && key0 + kb4 * 16 + 4 * G + i >= a.Nkv) v = kNegBigA;
+          sacc[rb][kb4][i] = v;
+          mx = fmaxf(mx, v);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m[rb], mx);
+      const float corr = exp2_fast(m[rb] - m_new);
+      m[rb] = m_new;
+      float ps = 0.f;
+#pragma unroll
+      for (int kb4 = 0; kb4 < 4; ++kb4)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float p = exp2_fast(sacc[rb][kb4][i] - m_new);
+          sacc[rb][kb4][i] = p;
+          ps += p;
+        }
+      lsum[rb] = lsum[rb] * corr + ps;
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) o[rb][db] *= corr;
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        union { uint32_t w[4]; s16x8 v; } cv;
+        cv.w[0] = pack_bf16x2(sacc[rb][2 * u][0], sacc[rb][2 * u][1]);
+        cv.w[1] = pack_bf16x2(sacc[rb][2 * u][2], sacc[rb][2 * u][3]);
+        cv.w[2] = pack_bf16x2(sacc[rb][2 * u + 1][0], sacc[rb][2 * u + 1][1]);
+        cv.w[3] = pack_bf16x2(sacc[rb][2 * u + 1][2], sacc[rb][2 * u + 1][3]);
+        pk[rb][u] = cv.v;
+      }
+    }
+
+    // ---- O^T += V^T P^T ; V^T operand through the LDS transpose read
+    const int e4 = l16 >> 2, c4 = l16 & 3;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) {
+        typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (lds_s16x4_ptr)(&Vs[stage][32 * u + 4 * G + e4][16 * db + 4 * c4]));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (lds_s16x4_ptr)(&Vs[stage][32 * u + 16 + 4 * G + e4][16 * db + 4 * c4]));
+        const s16x8 vop = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+          o[rb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vop),
+                                                               __builtin_bit_cast(bf16x8, pk[rb][u]),
+                                                               o[rb][db], 0, 0, 0);
+      }
+    }
+
+    if (t + 1 < t1) store_tile(stage ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    float l = lsum[rb];
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    const int R = row_base + rb * 16 + l16;
+    if (R >= a.Rtot) continue;
+    if (a.nsplit == 1) {
+      const float inv = 1.0f / l;
+      uint16_t* orow = a.out + (((long long)b * a.Hq + (long long)kvh * a.g) * a.Nq + R) * D;
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) {
+        uint2 w;
+        w.x = pack_bf16x2(o[rb][db][0] * inv, o[rb][db][1] * inv);
+        w.y = pack_bf16x2(o[rb][db][2] * inv, o[rb][db][3] * inv);
+        *reinterpret_cast<uint2*>(orow + 16 * db + 4 * G) = w;
+      }
+    } else {
+      const long long slot_i = ((long long)grp * a.Rtot + R) * a.nsplit + split;
+      float* wo = a.ws_o + slot_i * D;
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+        *reinterpret_cast<f32x4*>(wo + 16 * db + 4 * G) = o[rb][db];
+      if (G == 0) { a.ws_ml[slot_i * 2] = m[rb]; a.ws_ml[slot_i * 2 + 1] = l; }
+    }
+  }
+}
+
+// merge the key-range splits of every output row: fixed order, fp32
+template <int D>
+__global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a, long long total_rows) {
+  constexpr int TPR = D / 4;                       // threads per row
+  constexpr int RPB = 256 / TPR;                   // rows per workgroup
+  const long long row = (long long)blockIdx.x * RPB + threadIdx.x / TPR;   // = grp * Rtot + R
+  if (row >= total_rows) return;
+  const int d = (threadIdx.x % TPR) * 4;
+  const float* ml = a.ws_ml + row * a.nsplit * 2;
+  float M = kNegBigA;
+  for (int k = 0; k < a.nsplit; ++k) M = fmaxf(M, ml[2 * k]);
+  float L = 0.f;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int k = 0; k < a.nsplit; ++k) {
+    const float w = exp2_fast(ml[2 * k] - M);
+    L += w * ml[2 * k + 1];
+    const f32x4 ov = *reinterpret_cast<const f32x4*>(a.ws_o + (row * a.nsplit + k) * D + d);
+    acc += ov * w;
+  }
+  const float inv = 1.0f / L;
+  const long long grp = row / a.Rtot;
+  const int R = (int)(row - grp * a.Rtot);
+  const int b = (int)(grp / a.Hkv), kvh = (int)(grp - (long long)b * a.Hkv);
+  uint16_t* orow = a.out + (((long long)b * a.Hq + (long long)kvh * a.g) * a.Nq + R) * D;
+  uint2 w2;
+  w2.x = pack_bf16x2(acc[0] * inv, acc[1] * inv);
+  w2.y = pack_bf16x2(acc[2] * inv, acc[3] * inv);
+  *reinterpret_cast<uint2*>(orow + d) = w2;
+}
+
+AttnPlan plan_attention_bf16(const sdllm_attn_params& p) {
+  AttnPlan pl;
+  const int g = p.Hq / p.Hkv;
+  const long long Rtot = (long long)g * (p.K + p.n_keep);
+  const long long Nkv = (long long)p.prefix_len + p.K + p.n_keep;
+  pl.rb = Rtot > 64 ? 2 : 1;
+  const int rows_wg = 64 * pl.rb;
+  pl.q_tiles = (int)((Rtot + rows_wg - 1) / rows_wg);
+  pl.key_tiles = (int)((Nkv + kKeyTile - 1) / kKeyTile);
+  const long long base = (long long)p.B * p.Hkv * pl.q_tiles;
+  long long ns;
+  if (p.kv_splits > 0) {
+    ns = p.kv_splits;
+  } else {
+    ns = (2LL * kNumCUs + base - 1) / base;        // aim at two workgroups per CU
+    const long long cap2 = pl.key_tiles / 2;       // but at least two key tiles per split
+    if (ns > cap2) ns = cap2;
+  }
+  if (ns > pl.key_tiles) ns = pl.key_tiles;
+  if (ns > 64) ns = 64;
+  if (ns < 1) ns = 1;
+  pl.tiles_per_split = (int)((pl.key_tiles + ns - 1) / ns);
+  pl.kv_splits = (pl.key_tiles + pl.tiles_per_split - 1) / pl.tiles_per_split;   // no empty split
+  const long long units = (long long)p.B * p.Hkv * pl.kv_splits;
+  pl.workgroups = (int)(((units + kNumXCDs - 1) / kNumXCDs) * kNumXCDs * pl.q_tiles);
+  return pl;
+}
+
+size_t attention_bf16_workspace_bytes(const sdllm_attn_params& p, const AttnPlan& pl) {
+  if (pl.kv_splits <= 1) return 0;
+  const size_t rows = (size_t)p.B * p.Hq * (p.K + p.n_keep);
+  return rows * pl.kv_splits * (size_t)(p.D + 2) * sizeof(float);
+}
+
+template <int D, int RB>
+static hipError_t launch_main(const AttnArgs& a, const AttnPlan& pl, hipStream_t stream) {
+  constexpr size_t lds_bytes = 2ull * 2 * kKeyTile * (D + 8) * sizeof(uint16_t);
+  static bool attr_set = false;                     // benign race: the call is idempotent
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<D, RB>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((attn_bf16_kernel<D, RB>), dim3(pl.workgroups), dim3(256), lds_bytes, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_attention_bf16(const sdllm_attn_params& p, const AttnPlan& pl,
+                                 const void* q_block, const void* q_suffix,
+                                 const void* k_cache, const void* v_cache,
+                                 const void* k_block, const void* v_block,
+                                 const void* k_suffix, const void* v_suffix,
+                                 const int32_t* keep_idx, void* out, void* workspace, hipStream_t stream) {
+  AttnArgs a;
+  a.q_block = (const uint16_t*)q_block; a.q_suffix = (const uint16_t*)q_suffix;
+  a.k_cache = (const uint16_t*)k_cache; a.v_cache = (const uint16_t*)v_cache;
+  a.k_block = (const uint16_t*)k_block; a.v_block = (const uint16_t*)v_block;
+  a.k_suffix = (const uint16_t*)k_suffix; a.v_suffix = (const uint16_t*)v_suffix;
+  a.keep_idx = keep_idx; a.out = (uint16_t*)out;
+  a.B = p.B; a.Hq = p.Hq; a.Hkv = p.Hkv; a.g = p.Hq / p.Hkv;
+  a.P = p.prefix_len; a.cap = p.prefix_cap; a.K = p.K; a.S = p.S; a.n_keep = p.n_keep;
+  a.Nq = p.K + p.n_keep; a.Nkv = p.prefix_len + p.K + p.n_keep; a.Rtot = a.g * a.Nq;
+  a.nsplit = pl.kv_splits; a.tiles_per_split = pl.tiles_per_split; a.key_tiles = pl.key_tiles;
+  a.q_tiles = pl.q_tiles; a.n_units = p.B * p.Hkv * pl.kv_splits;
+  const float scale = p.scale > 0.f ? p.scale : 1.0f / sqrtf((float)p.D);
+  a.scale_log2 = scale * kLog2eA;
+  const size_t rows = (size_t)p.B * p.Hq * a.Nq;
+  a.ws_o = (float*)workspace;
+  a.ws_ml = a.ws_o ? a.ws_o + rows * pl.kv_splits * (size_t)p.D : nullptr;
+
+  hipError_t e;
+  if (p.D == 128) e = pl.rb == 2 ? launch_main<128, 2>(a, pl, stream) : launch_main<128, 1>(a, pl, stream);
+  else            e = pl.rb == 2 ? launch_main<64, 2>(a, pl, stream) : launch_main<64, 1>(a, pl, stream);
+  if (e != hipSuccess) return e;
+  if (pl.kv_splits > 1) {
+    const long long total_rows = (long long)rows;
+    if (p.D == 128) {
+      const int rpb = 256 / (128 / 4);
+      hipLaunchKernelGGL(attn_combine_kernel<128>, dim3((unsigned)((total_rows + rpb - 1) / rpb)), dim3(256), 0, stream, a, total_rows);
+    } else {
+      const int rpb = 256 / (64 / 4);
+      hipLaunchKernelGGL(attn_combine_kernel<64>, dim3((unsigned)((total_rows + rpb - 1) / rpb)), dim3(256), 0, stream, a, total_rows);
+    }
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+}  // namespace sdllm

