@@ -1,0 +1,302 @@
+#!/usr/bin/env python3
+"""Benchmark of one block-wise diffusion decode step on one MI355X.
+
+A step = one pass of the whole hot path over one batch of seeded synthetic input that is already
+resident in HBM: pruned-suffix attention for every layer of the workload, the confidence-aware
+unmask over the block's logits, and the append of the block's K/V to the prefix caches.
+Prints ONE JSON line (metric: committed tokens per second of decode-step time), with the roofline
+figures of the dominant kernel (HIP events inside the timed region) and the CPU oracle timed on
+this machine's host cores as a baseline.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import workloads as wl  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--workload", default="cfg2", choices=[k for k in wl.WORKLOADS if k != "small_bf16"])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="leave the per-kernel HIP events out of the timed region (roofline.achieved = null)")
+    ap.add_argument("--kv-splits", type=int, default=0, help="force the attention key-range split count")
+    return ap.parse_args()
+
+
+def to_dev(x):
+    import torch
+    if isinstance(x, np.ndarray):
+        if x.dtype == np.uint16:
+            return torch.from_numpy(x.view(np.int16)).view(torch.bfloat16).cuda()
+        return torch.from_numpy(x).cuda()
+    return x
+
+
+class Step:
+    """All device buffers of one workload, allocated before the timed region."""
+
+    def __init__(self, sd, w: wl.Workload, seed: int, n_states: int, kv_splits: int = 0):
+        import torch
+        self.sd, self.w = sd, w
+        self.layers = []
+        for layer in range(w.n_layers):
+            if w.n_layers > 1:
+                t = wl.make_attention_inputs_device(w, seed, layer)
+            else:
+                t = {k: to_dev(v) for k, v in wl.make_attention_inputs(w, seed, layer).items()}
+            self.layers.append(t)
+        dt = self.layers[0]["q_block"].dtype
+        self.out = torch.empty((w.B, w.Hq, w.Nq, w.D), dtype=dt, device="cuda")
+        self.attn_p = sd.attn_params(sd.FP32 if w.dtype == "fp32" else sd.BF16, w.B, w.Hq, w.Hkv, w.D, w.P, w.cap,
+                                     w.K, w.S, w.n_keep, 0.0, kv_splits)
+        self.attn_ws = torch.empty((max(sd.attention_workspace_bytes(self.attn_p), 16),), dtype=torch.uint8, device="cuda")
+        self.plan = sd.plan_attention(self.attn_p)
+        # unmask state: one private copy of (tokens, masked) per step, so that every step does the same work
+        u = wl.make_unmask_inputs(w, seed)
+        self.host_unmask = u
+        self.logits = to_dev(u["logits"])
+        self.tokens = to_dev(np.ascontiguousarray(np.broadcast_to(u["tokens"], (n_states,) + u["tokens"].shape)))
+        self.masked = to_dev(np.ascontiguousarray(np.broadcast_to(u["masked"], (n_states,) + u["masked"].shape)))
+        self.n_committed = torch.zeros((n_states, w.B), dtype=torch.int32, device="cuda")
+        self.block_done = torch.zeros((n_states, w.B), dtype=torch.uint8, device="cuda")
+        self.eos_seen = torch.zeros((w.B,), dtype=torch.uint8, device="cuda")
+        self.unmask_p = sd.unmask_params(sd.FP32 if w.dtype == "fp32" else sd.BF16, w.B, w.K, w.V, w.V, w.tau0, w.alpha)
+        self.unmask_ws = torch.empty((max(sd.unmask_workspace_bytes(self.unmask_p), 16),), dtype=torch.uint8, device="cuda")
+        # append: the block K/V of every layer into every layer's cache (one launch).  Single-layer workloads
+        # append into the layer's own cache; the stack keeps [L,...] tensors so that one launch covers all layers.
+        if w.n_layers > 1:
+            self.k_caches = torch.stack([t["k_cache"] for t in self.layers])
+            self.v_caches = torch.stack([t["v_cache"] for t in self.layers])
+            for l, t in enumerate(self.layers):          # attention reads the stacked storage: no second copy
+                t["k_cache"], t["v_cache"] = self.k_caches[l], self.v_caches[l]
+            self.k_blocks = torch.stack([t["k_block"] for t in self.layers])
+            self.v_blocks = torch.stack([t["v_block"] for t in self.layers])
+        else:
+            t = self.layers[0]
+            self.k_caches, self.v_caches = t["k_cache"][None], t["v_cache"][None]
+            self.k_blocks, self.v_blocks = t["k_block"][None], t["v_block"][None]
+
+        # marshal every call once: in the loop a call is one foreign-function call
+        nk = w.n_keep
+        self.attention = [sd.bind_block_attention(
+            t["q_block"], t["q_suffix"] if nk else None, t["k_cache"], t["v_cache"], t["k_block"], t["v_block"],
+            t["k_suffix"] if nk else None, t["v_suffix"] if nk else None, t["keep_idx"] if nk else None, w.P,
+            out=self.out, kv_splits=kv_splits, workspace=self.attn_ws) for t in self.layers]
+        self.unmask = [sd.bind_confidence_unmask(
+            self.logits, self.tokens[i], self.masked[i], w.tau0, w.alpha, n_committed=self.n_committed[i],
+            block_done=self.block_done[i], eos_seen=self.eos_seen, workspace=self.unmask_ws) for i in range(n_states)]
+        self.append = sd.bind_kv_append(self.k_caches, self.v_caches, self.k_blocks, self.v_blocks, w.P)
+        torch.cuda.synchronize()
+
+    def run(self, i: int, events=None):
+        if events is not None:
+            events[0].record()
+            self.attention[0]()
+            events[1].record()
+            for call in self.attention[1:]:
+                call()
+        else:
+            for call in self.attention:
+                call()
+        self.unmask[i]()
+        self.append()
+
+
+def time_kernel(fn, iters=50, warm=5):
+    import torch
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters     # ms per call, back-to-back launches
+
+
+def cpu_baseline(w: wl.Workload, seed: int):
+    """The oracle, as it stands, on this machine's host cores: one decode step (bounded sample for the
+    big workloads).  Returns the cpu_baseline object."""
+    from threadpoolctl import threadpool_info
+    import oracle
+    t = wl.make_attention_inputs(w, seed, 0) if w.n_layers == 1 and w.attn_flops() < 4e10 else None
+    note = []
+    # --- attention: all (batch, head) pairs when cheap, else a sample of pairs scaled up
+    n_pairs = w.B * w.Hq
+    per_pair_flops = 4 * w.Nq * w.Nkv * w.D
+    sample_pairs = max(1, min(n_pairs, int(2e10 // per_pair_flops)))
+    rng = np.random.default_rng(seed)
+
+    def rand(*shape):
+        return rng.standard_normal(shape)
+
+    g = w.Hq // w.Hkv
+    hq_s = min(w.Hq, max(g, sample_pairs))
+    hq_s -= hq_s % g
+    hkv_s = hq_s // g
+    b_s = max(1, min(w.B, sample_pairs // hq_s))
+    keep = wl.make_keep_idx(w)
+    if t is not None:      # the workload's own tensors (cheap to draw), restricted to the sampled pairs
+        f = {k: wl.to_f64(v) for k, v in t.items() if k != "keep_idx"}
+        args = (f["q_block"][:b_s, :hq_s], f["q_suffix"][:b_s, :hq_s], f["k_cache"][:b_s, :hkv_s], f["v_cache"][:b_s, :hkv_s],
+                f["k_block"][:b_s, :hkv_s], f["v_block"][:b_s, :hkv_s], f["k_suffix"][:b_s, :hkv_s], f["v_suffix"][:b_s, :hkv_s])
+    else:                  # same shapes and law drawn directly in fp64 (the oracle's time does not depend on values)
+        args = (rand(b_s, hq_s, w.K, w.D), rand(b_s, hq_s, w.S, w.D), rand(b_s, hkv_s, w.P, w.D), rand(b_s, hkv_s, w.P, w.D),
+                rand(b_s, hkv_s, w.K, w.D), rand(b_s, hkv_s, w.K, w.D), rand(b_s, hkv_s, w.S, w.D), rand(b_s, hkv_s, w.S, w.D))
+    t0 = time.perf_counter()
+    oracle.block_attention(*args, keep, w.P)
+    t_attn_sample = time.perf_counter() - t0
+    frac = (b_s * hq_s) / n_pairs
+    t_attn = t_attn_sample / frac * w.n_layers
+    note.append(f"attention: {b_s * hq_s} of {n_pairs} (batch, head) pairs of one layer"
+                + (f", scaled x{n_pairs / (b_s * hq_s):.0f} x {w.n_layers} layers" if frac < 1 or w.n_layers > 1 else ""))
+    # --- unmask: a bounded number of sequences, scaled
+    u = wl.make_unmask_inputs(w, seed)
+    masked_rows = int((u["masked"] != 0).sum())
+    b_u = w.B
+    while b_u > 1 and int((u["masked"][:b_u] != 0).sum()) * w.V > 4e7:
+        b_u //= 2
+    lg = wl.to_f64(u["logits"][:b_u])
+    t0 = time.perf_counter()
+    res = oracle.confidence_unmask(lg, u["tokens"][:b_u], u["masked"][:b_u], float(np.float32(w.tau0)), float(np.float32(w.alpha)))
+    t_unmask_sample = time.perf_counter() - t0
+    rows_s = int((u["masked"][:b_u] != 0).sum())
+    t_unmask = t_unmask_sample * masked_rows / max(rows_s, 1)
+    committed_s = int(res["n_committed"].sum())
+    note.append(f"unmask: {b_u} of {w.B} sequences ({rows_s} of {masked_rows} masked rows)" + (", scaled" if b_u < w.B else ""))
+    # --- append: one layer, scaled
+    a = wl.make_append_inputs(w.dtype, 1, w.B, w.Hkv, w.D, w.K, w.P + w.K, seed)
+    t0 = time.perf_counter()
+    oracle.kv_append(a["k_caches"], a["v_caches"], a["k_blocks"], a["v_blocks"], w.P)
+    t_append = (time.perf_counter() - t0) * w.n_layers
+    note.append("append: one layer" + (f" x {w.n_layers}" if w.n_layers > 1 else ""))
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {"t_step_s": t_attn + t_unmask + t_append, "t_attention_s": t_attn, "t_unmask_s": t_unmask,
+            "t_append_s": t_append, "cores": threads, "sample": "; ".join(note),
+            "committed_sample": committed_s, "b_u": b_u}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (every box has one; the path shards by batch / head without "
+              "communication, see DESIGN.md); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    import paper_2601_17917_amd as sd
+    sd.load_library()                     # raises if the HIP library is missing: no fallback
+    w = wl.WORKLOADS[args.workload]
+    K, W = args.steps, args.warmup
+    st = Step(sd, w, args.seed, K + W, args.kv_splits)
+
+    for i in range(W):
+        st.run(i)
+    torch.cuda.synchronize()
+    use_ev = not args.no_kernel_events
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)] if use_ev else None
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        st.run(W + i, evs[i] if use_ev else None)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+
+    committed = st.n_committed[W:].sum(dim=1).cpu().numpy()
+    assert (committed == committed[0]).all(), "every timed step must do the same work"
+    committed_per_step = int(committed[0])
+    value = committed_per_step / (ms_per_step * 1e-3)
+
+    # ---- dominant kernel: the attention call of layer 0 (main kernel + split merge), events inside the timed region
+    attn_ms_ev = float(np.mean([a.elapsed_time(b) for a, b in evs])) if use_ev else None
+    attn_bytes = w.attn_bytes()
+    attn_flops = w.attn_flops()
+    intensity = attn_flops / attn_bytes
+    bound = "mfma" if intensity > MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9) and w.dtype == "bf16" else "hbm"
+
+    # ---- per-kernel timings outside the timed region (back-to-back launches of one call)
+    t_attn = time_kernel(st.attention[0])
+    fresh = (st.tokens[0].clone(), st.masked[0].clone())
+
+    def unmask_fresh():                                 # restore the state slot, then unmask it again
+        st.tokens[1].copy_(fresh[0]); st.masked[1].copy_(fresh[1])
+        st.unmask[1]()
+
+    def restore_only():
+        st.tokens[1].copy_(fresh[0]); st.masked[1].copy_(fresh[1])
+
+    st.tokens[0].copy_(to_dev(st.host_unmask["tokens"])); st.masked[0].copy_(to_dev(st.host_unmask["masked"]))
+    fresh = (st.tokens[0].clone(), st.masked[0].clone())
+    t_unm = time_kernel(unmask_fresh) - time_kernel(restore_only)
+    t_app = time_kernel(st.append)
+    masked_rows = int((st.host_unmask["masked"] != 0).sum())
+    unmask_bytes = masked_rows * w.V * w.elem_bytes
+    append_bytes = 2 * 2 * w.n_layers * w.B * w.Hkv * w.K * w.D * w.elem_bytes
+    kernels = {
+        "attention_call": {"ms": t_attn, "tflops": attn_flops / t_attn / 1e9, "gbs": attn_bytes / t_attn / 1e6,
+                           "frac_mfma_peak": attn_flops / t_attn / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+                           "frac_hbm_peak": attn_bytes / t_attn / 1e6 / HBM_PEAK_GBS,
+                           "kv_splits": st.plan.kv_splits, "workgroups": st.plan.workgroups, "layers_per_step": w.n_layers},
+        "unmask_call": {"ms": t_unm, "gbs": unmask_bytes / t_unm / 1e6, "frac_hbm_peak": unmask_bytes / t_unm / 1e6 / HBM_PEAK_GBS,
+                        "masked_rows": masked_rows},
+        "append_call": {"ms": t_app, "gbs": append_bytes / t_app / 1e6, "frac_hbm_peak": append_bytes / t_app / 1e6 / HBM_PEAK_GBS},
+    }
+    dur = attn_ms_ev if use_ev else None
+    if bound == "hbm":
+        ach = attn_bytes / dur / 1e6 if dur else None
+        roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": ach / HBM_PEAK_GBS if ach else None, "traffic": None}
+    else:
+        ach = attn_flops / dur / 1e9 if dur else None
+        roof = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / MFMA_BF16_PEAK_TFLOPS if ach else None, "traffic": None}
+    roof.update({"kernel": "sdllm_block_attention (attn_bf16_kernel + attn_combine_kernel)" if w.dtype == "bf16"
+                 else "sdllm_block_attention (attention_f32_kernel)",
+                 "launch_ms": dur, "algorithmic_bytes": attn_bytes, "algorithmic_flops": attn_flops})
+
+    out = {
+        "metric": "committed tokens/sec per decode step", "value": value, "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={w.B} Hq/Hkv={w.Hq}/{w.Hkv} D={w.D} P={w.P} K={w.K} S={w.S} kept={w.n_keep} "
+                               f"V={w.V} layers={w.n_layers} tau0={w.tau0} alpha={w.alpha}",
+                   "committed_tokens_per_step": committed_per_step, "seed": args.seed},
+        "roofline": roof,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        cb = cpu_baseline(w, args.seed)
+        # committed tokens per step are the same on both sides (checked by the parity tests)
+        out["cpu_baseline"] = {"value": committed_per_step / cb["t_step_s"], "unit": "tokens/s", "cores": cb["cores"],
+                               "kind": "oracle", "sample": cb["sample"], "step_seconds": cb["t_step_s"],
+                               "attention_s": cb["t_attention_s"], "unmask_s": cb["t_unmask_s"], "append_s": cb["t_append_s"]}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -142,10 +142,33 @@ def plan_attention(p: AttnParams) -> AttnPlan:
     return plan
 
 
-def block_attention(q_block, q_suffix, k_cache, v_cache, k_block, v_block, k_suffix, v_suffix, keep_idx,
-                    prefix_len: int, out=None, scale: float = 0.0, kv_splits: int = 0, workspace=None, stream=None):
+class BoundCall:
+    """One C-ABI call with its arguments marshalled once; calling it enqueues the work again on the
+    stream it was bound to.  Keeps the tensors alive.  For tight loops where per-call Python
+    marshalling would cost more than the kernels."""
+
+    __slots__ = ("_fn", "_args", "_keep", "result")
+
+    def __init__(self, fn, args, keep, result):
+        self._fn, self._args, self._keep, self.result = fn, args, keep, result
+
+    def __call__(self):
+        rc = self._fn(*self._args)
+        if rc != SDLLM_OK:
+            _check(rc)
+        return self.result
+
+
+def block_attention(*args, **kw):
     """sdllm_block_attention.  Tensors in [B,H,T,D] layout; returns out [B,Hq,K+n_keep,D].
-    The cache tensors may be None when prefix_len == 0, the suffix tensors when keep_idx is empty."""
+    The cache tensors may be None when prefix_len == 0, the suffix tensors when keep_idx is empty.
+    Signature: see bind_block_attention."""
+    return bind_block_attention(*args, **kw)()
+
+
+def bind_block_attention(q_block, q_suffix, k_cache, v_cache, k_block, v_block, k_suffix, v_suffix, keep_idx,
+                         prefix_len: int, out=None, scale: float = 0.0, kv_splits: int = 0, workspace=None,
+                         stream=None) -> BoundCall:
     import torch
     B, Hq, K, D = q_block.shape
     Hkv = k_block.shape[1]
@@ -165,10 +188,10 @@ def block_attention(q_block, q_suffix, k_cache, v_cache, k_block, v_block, k_suf
         workspace = torch.empty((need,), dtype=torch.uint8, device=q_block.device)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     kidx = keep_idx if n_keep else None
-    _check(load_library().sdllm_block_attention(
-        ctypes.byref(p), _ptr(q_block), _ptr(q_suffix), _ptr(k_cache), _ptr(v_cache), _ptr(k_block), _ptr(v_block),
-        _ptr(k_suffix), _ptr(v_suffix), _ptr(kidx), _ptr(out), _ptr(workspace), ws_bytes, _stream(stream)))
-    return out
+    args = (ctypes.byref(p), _ptr(q_block), _ptr(q_suffix), _ptr(k_cache), _ptr(v_cache), _ptr(k_block), _ptr(v_block),
+            _ptr(k_suffix), _ptr(v_suffix), _ptr(kidx), _ptr(out), _ptr(workspace), ws_bytes, _stream(stream))
+    keep = (p, q_block, q_suffix, k_cache, v_cache, k_block, v_block, k_suffix, v_suffix, kidx, out, workspace)
+    return BoundCall(load_library().sdllm_block_attention, args, keep, out)
 
 
 # ---------------------------------------------------------------------------------------------
@@ -185,12 +208,16 @@ def unmask_workspace_bytes(p: UnmaskParams) -> int:
     return n
 
 
-def confidence_unmask(logits, tokens, masked, tau0: float, alpha: float, V: Optional[int] = None,
-                      confidence=None, n_committed=None, block_done=None, eos_seen=None, eos_id: int = -1,
-                      tau_eos: Optional[float] = None, r_extra_masked: int = 0, r_extra_total: int = 0,
-                      workspace=None, stream=None):
+def confidence_unmask(*args, **kw):
     """sdllm_confidence_unmask.  logits [B,K,ld]; tokens int32 [B,K] and masked uint8 [B,K] are updated
-    in place.  Returns (n_committed int32 [B], block_done uint8 [B])."""
+    in place.  Returns (n_committed int32 [B], block_done uint8 [B]).  Signature: see bind_confidence_unmask."""
+    return bind_confidence_unmask(*args, **kw)()
+
+
+def bind_confidence_unmask(logits, tokens, masked, tau0: float, alpha: float, V: Optional[int] = None,
+                           confidence=None, n_committed=None, block_done=None, eos_seen=None, eos_id: int = -1,
+                           tau_eos: Optional[float] = None, r_extra_masked: int = 0, r_extra_total: int = 0,
+                           workspace=None, stream=None) -> BoundCall:
     import torch
     B, K, ld = logits.shape
     V = ld if V is None else V
@@ -210,15 +237,20 @@ def confidence_unmask(logits, tokens, masked, tau0: float, alpha: float, V: Opti
     if workspace is None:
         workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=logits.device)
     ws_bytes = workspace.numel() * workspace.element_size()
-    _check(load_library().sdllm_confidence_unmask(
-        ctypes.byref(p), _ptr(logits), _ptr(tokens), _ptr(masked), _ptr(confidence), _ptr(n_committed),
-        _ptr(block_done), _ptr(eos_seen), _ptr(workspace), ws_bytes, _stream(stream)))
-    return n_committed, block_done
+    args = (ctypes.byref(p), _ptr(logits), _ptr(tokens), _ptr(masked), _ptr(confidence), _ptr(n_committed),
+            _ptr(block_done), _ptr(eos_seen), _ptr(workspace), ws_bytes, _stream(stream))
+    keep = (p, logits, tokens, masked, confidence, n_committed, block_done, eos_seen, workspace)
+    return BoundCall(load_library().sdllm_confidence_unmask, args, keep, (n_committed, block_done))
 
 
 # ---------------------------------------------------------------------------------------------
-def kv_append(k_caches, v_caches, k_blocks, v_blocks, prefix_len: int, do_append=None, stream=None):
-    """sdllm_kv_append.  caches [L,B,Hkv,cap,D] (updated in place), blocks [L,B,Hkv,K,D]."""
+def kv_append(*args, **kw):
+    """sdllm_kv_append.  caches [L,B,Hkv,cap,D] (updated in place), blocks [L,B,Hkv,K,D].
+    Signature: see bind_kv_append."""
+    return bind_kv_append(*args, **kw)()
+
+
+def bind_kv_append(k_caches, v_caches, k_blocks, v_blocks, prefix_len: int, do_append=None, stream=None) -> BoundCall:
     import torch
     L, B, Hkv, cap, D = k_caches.shape
     K = k_blocks.shape[3]
@@ -226,5 +258,7 @@ def kv_append(k_caches, v_caches, k_blocks, v_blocks, prefix_len: int, do_append
         _require(t, name, k_caches.dtype)
     _require(do_append, "do_append", torch.uint8)
     p = AppendParams(_dtype_code(k_caches), L, B, Hkv, D, K, prefix_len, cap, 0, 0)
-    _check(load_library().sdllm_kv_append(ctypes.byref(p), _ptr(k_caches), _ptr(v_caches), _ptr(k_blocks),
-                                          _ptr(v_blocks), _ptr(do_append), _stream(stream)))
+    args = (ctypes.byref(p), _ptr(k_caches), _ptr(v_caches), _ptr(k_blocks), _ptr(v_blocks), _ptr(do_append),
+            _stream(stream))
+    keep = (p, k_caches, v_caches, k_blocks, v_blocks, do_append)
+    return BoundCall(load_library().sdllm_kv_append, args, keep, None)

@@ -285,3 +285,29 @@ def make_append_inputs(dtype: str, n_layers: int, B: int, Hkv: int, D: int, K: i
         "k_blocks": _normal(seed, "k_blocks", 0, (n_layers, B, Hkv, K, D), 1.0, dtype),
         "v_blocks": _normal(seed, "v_blocks", 0, (n_layers, B, Hkv, K, D), 1.0, dtype),
     }
+
+
+def make_attention_inputs_device(w: Workload, seed: int = 0, layer: int = 0, device: str = "cuda"):
+    """Device-side generation for workloads too large to draw on the host in reasonable time
+    (the 32-layer long-context stack: ~11 GB of K/V).  Same shapes and N(0, qkv_std^2) law as
+    make_attention_inputs, drawn with torch's seeded device generator (seed + layer); parity
+    checks copy the needed slices back so that the oracle sees identical bits."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed((seed << 16) + layer)
+    dt = torch.float32 if w.dtype == "fp32" else torch.bfloat16
+    B, Hq, Hkv, D, K, S, cap = w.B, w.Hq, w.Hkv, w.D, w.K, w.S, w.cap
+
+    def draw(*shape):
+        x = torch.randn(shape, generator=g, device=device, dtype=torch.float32)
+        if w.qkv_std != 1.0:
+            x *= w.qkv_std
+        return x.to(dt)
+
+    return {
+        "q_block": draw(B, Hq, K, D), "q_suffix": draw(B, Hq, S, D),
+        "k_cache": draw(B, Hkv, cap, D), "v_cache": draw(B, Hkv, cap, D),
+        "k_block": draw(B, Hkv, K, D), "v_block": draw(B, Hkv, K, D),
+        "k_suffix": draw(B, Hkv, S, D), "v_suffix": draw(B, Hkv, S, D),
+        "keep_idx": torch.from_numpy(make_keep_idx(w)).to(device),
+    }
