@@ -25,6 +25,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 constexpr int kKeyTile = 64;
 constexpr float kLog2eA = 1.4426950408889634f;
@@ -46,17 +47,18 @@ struct AttnArgs {
 
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
 
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  // round-to-nearest-even; inputs are probabilities in [0,1], no NaN handling needed
-  uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
-  a += 0x7fffu + ((a >> 16) & 1u);
-  b += 0x7fffu + ((b >> 16) & 1u);
-  return (a >> 16) | (b & 0xffff0000u);
+  // one v_cvt_pk_bf16_f32 (round to nearest even)
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
 }
 
 template <int D, int RB>
-__global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
-  constexpr int LDK = D + 8;                       // padded LDS row, elements (row start shifts 4 banks)
+__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
+  constexpr int LDK = D + 8;                       // K rows: +16 B, so 16 rows x 16 B (one b128 read phase) cover all banks
+  constexpr int LDV = D + 16;                      // V rows: +32 B, so 8 rows x 32 B (one transpose-read phase) cover all banks
   constexpr int CPR = D / 8;                       // 16-byte chunks per row
   constexpr int RPP = 256 / CPR;                   // rows loaded per pass of the workgroup
   constexpr int NP = kKeyTile / RPP;               // passes per tile
@@ -64,7 +66,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
   constexpr int NDB = D / 16;                      // 16-wide d blocks of the output
   extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
   uint16_t (*Ks)[kKeyTile][LDK] = reinterpret_cast<uint16_t (*)[kKeyTile][LDK]>(lds);
-  uint16_t (*Vs)[kKeyTile][LDK] = reinterpret_cast<uint16_t (*)[kKeyTile][LDK]>(lds + 2 * kKeyTile * LDK);
+  uint16_t (*Vs)[kKeyTile][LDV] = reinterpret_cast<uint16_t (*)[kKeyTile][LDV]>(lds + 2 * kKeyTile * LDK);
 
   // ---- which piece of work: workgroups that share K/V (query tiles of one unit) sit on one XCD
   const int xcd = blockIdx.x % kNumXCDs, slot = blockIdx.x / kNumXCDs;
@@ -89,30 +91,34 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
 
   // ---- global -> register staging of one K/V tile (rows clamped into the valid range)
   const int lrow = tid / CPR, lchunk = tid % CPR;
-  uint4 kreg[NP], vreg[NP];
-  auto load_tile = [&](int tile) {
-#pragma unroll
-    for (int p = 0; p < NP; ++p) {
-      int r = tile * kKeyTile + lrow + p * RPP;
-      r = min(r, a.Nkv - 1);
-      const uint16_t* kp; const uint16_t* vp; long long off;
-      if (r < a.P) { kp = kc; vp = vc; off = (long long)r * D; }
-      else if (r < a.P + a.K) { kp = kb; vp = vb; off = (long long)(r - a.P) * D; }
-      else { kp = ks; vp = vs; off = (long long)a.keep_idx[r - a.P - a.K] * D; }
-      off += lchunk * 8;
-      kreg[p] = *reinterpret_cast<const uint4*>(kp + off);
-      vreg[p] = *reinterpret_cast<const uint4*>(vp + off);
-    }
-  };
-  auto store_tile = [&](int stage) {
-#pragma unroll
-    for (int p = 0; p < NP; ++p) {
-      *reinterpret_cast<uint4*>(&Ks[stage][lrow + p * RPP][lchunk * 8]) = kreg[p];
-      *reinterpret_cast<uint4*>(&Vs[stage][lrow + p * RPP][lchunk * 8]) = vreg[p];
-    }
-  };
+  u32x4 kreg[NP], vreg[NP];
+#define SDLLM_LOAD_TILE(tile)                                                                   \
+  if (((tile) + 1) * kKeyTile <= a.P) {          /* uniform: whole tile inside the prefix cache */ \
+    const long long off0 = ((long long)(tile) * kKeyTile + lrow) * D + lchunk * 8;              \
+    _Pragma("unroll") for (int p = 0; p < NP; ++p) {                                            \
+      kreg[p] = *reinterpret_cast<const u32x4*>(kc + off0 + (long long)p * RPP * D);            \
+      vreg[p] = *reinterpret_cast<const u32x4*>(vc + off0 + (long long)p * RPP * D);            \
+    }                                                                                           \
+  } else {                                                                                      \
+    _Pragma("unroll") for (int p = 0; p < NP; ++p) {                                            \
+      int r = (tile) * kKeyTile + lrow + p * RPP;                                               \
+      r = min(r, a.Nkv - 1);                                                                    \
+      const uint16_t* kp; const uint16_t* vp; long long off;                                    \
+      if (r < a.P) { kp = kc; vp = vc; off = (long long)r * D; }                                \
+      else if (r < a.P + a.K) { kp = kb; vp = vb; off = (long long)(r - a.P) * D; }             \
+      else { kp = ks; vp = vs; off = (long long)a.keep_idx[r - a.P - a.K] * D; }                \
+      off += lchunk * 8;                                                                        \
+      kreg[p] = *reinterpret_cast<const u32x4*>(kp + off);                                      \
+      vreg[p] = *reinterpret_cast<const u32x4*>(vp + off);                                      \
+    }                                                                                           \
+  }
+#define SDLLM_STORE_TILE(stage)                                                                 \
+  _Pragma("unroll") for (int p = 0; p < NP; ++p) {                                              \
+    *reinterpret_cast<u32x4*>(&Ks[stage][lrow + p * RPP][lchunk * 8]) = kreg[p];                \
+    *reinterpret_cast<u32x4*>(&Vs[stage][lrow + p * RPP][lchunk * 8]) = vreg[p];                \
+  }
 
-  load_tile(t0);
+  SDLLM_LOAD_TILE(t0)
 
   // ---- query rows of this wave, as MFMA B operands (lane: row l16, d = 32*s + 8*G .. +7)
   const int row_base = qt * (64 * RB) + wave * (16 * RB);
@@ -138,12 +144,14 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
     for (int db = 0; db < NDB; ++db) o[rb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  store_tile(0);
+  SDLLM_STORE_TILE(0)
   __syncthreads();
 
   for (int t = t0; t < t1; ++t) {
     const int stage = (t - t0) & 1;
-    if (t + 1 < t1) load_tile(t + 1);              // in flight while this tile is computed
+    // next tile in flight while this one is computed (the last iteration re-loads its own tile: harmless)
+    const int tn = min(t + 1, t1 - 1);
+    SDLLM_LOAD_TILE(tn)
 
     // ---- S^T = K Q^T
     f32x4 sacc[RB][4];
@@ -162,39 +170,48 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
       }
     }
 
-    // ---- online softmax (log2 domain); keys past Nkv only exist in the last tile
+    // ---- online softmax (log2 domain: p = exp2(s * scale_log2 - m)); keys past Nkv only exist in the last tile
     const int key0 = t * kKeyTile;
-    const bool ragged = key0 + kKeyTile > a.Nkv;
+    if (key0 + kKeyTile > a.Nkv) {                 // uniform branch
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int kb4 = 0; kb4 < 4; ++kb4)
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (key0 + kb4 * 16 + 4 * G + i >= a.Nkv) sacc[rb][kb4][i] = kNegBigA;
+    }
     s16x8 pk[RB][2];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      float mx = kNegBigA;
-#pragma unroll
-      for (int kb4 = 0; kb4 < 4; ++kb4)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          float v = sacc[rb][kb4][i] * a.scale_log2;
-          if (ragged && key0 + kb4 * 16 + 4 * G + i >= a.Nkv) v = kNegBigA;
-          sacc[rb][kb4][i] = v;
-          mx = fmaxf(mx, v);
-        }
+      float mx = fmaxf(fmaxf(sacc[rb][0][0], sacc[rb][0][1]), sacc[rb][0][2]);
+      mx = fmaxf(fmaxf(mx, sacc[rb][0][3]), sacc[rb][1][0]);
+      mx = fmaxf(fmaxf(mx, sacc[rb][1][1]), sacc[rb][1][2]);
+      mx = fmaxf(fmaxf(mx, sacc[rb][1][3]), sacc[rb][2][0]);
+      mx = fmaxf(fmaxf(mx, sacc[rb][2][1]), sacc[rb][2][2]);
+      mx = fmaxf(fmaxf(mx, sacc[rb][2][3]), sacc[rb][3][0]);
+      mx = fmaxf(fmaxf(mx, sacc[rb][3][1]), sacc[rb][3][2]);
+      mx = fmaxf(mx, sacc[rb][3][3]);
       mx = fmaxf(mx, __shfl_xor(mx, 16));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m[rb], mx);
-      const float corr = exp2_fast(m[rb] - m_new);
-      m[rb] = m_new;
+      const float m_new = fmaxf(m[rb], mx * a.scale_log2);     // scale_log2 > 0
+      if (__builtin_amdgcn_ballot_w64(m_new != m[rb]) != 0) {  // uniform: rescale only when some row's maximum moved
+        const float corr = exp2_fast(m[rb] - m_new);
+        lsum[rb] *= corr;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) o[rb][db] *= corr;
+        m[rb] = m_new;
+      }
       float ps = 0.f;
 #pragma unroll
       for (int kb4 = 0; kb4 < 4; ++kb4)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const float p = exp2_fast(sacc[rb][kb4][i] - m_new);
+          const float p = exp2_fast(fmaf(sacc[rb][kb4][i], a.scale_log2, -m_new));
           sacc[rb][kb4][i] = p;
           ps += p;
         }
-      lsum[rb] = lsum[rb] * corr + ps;
-#pragma unroll
-      for (int db = 0; db < NDB; ++db) o[rb][db] *= corr;
+      lsum[rb] += ps;
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         union { uint32_t w[4]; s16x8 v; } cv;
@@ -226,7 +243,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
       }
     }
 
-    if (t + 1 < t1) store_tile(stage ^ 1);
+    SDLLM_STORE_TILE(stage ^ 1)
     __syncthreads();
   }
 
@@ -258,6 +275,9 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
     }
   }
 }
+
+#undef SDLLM_LOAD_TILE
+#undef SDLLM_STORE_TILE
 
 // merge the key-range splits of every output row: fixed order, fp32
 template <int D>
@@ -325,7 +345,7 @@ size_t attention_bf16_workspace_bytes(const sdllm_attn_params& p, const AttnPlan
 
 template <int D, int RB>
 static hipError_t launch_main(const AttnArgs& a, const AttnPlan& pl, hipStream_t stream) {
-  constexpr size_t lds_bytes = 2ull * 2 * kKeyTile * (D + 8) * sizeof(uint16_t);
+  constexpr size_t lds_bytes = 2ull * kKeyTile * ((D + 8) + (D + 16)) * sizeof(uint16_t);
   static bool attr_set = false;                     // benign race: the call is idempotent
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<D, RB>),
