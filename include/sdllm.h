@@ -13,6 +13,8 @@
  *   - Every buffer is CALLER-ALLOCATED DEVICE memory unless said otherwise; the library
  *     never allocates, frees or keeps a pointer.  Scratch memory comes from a caller-provided
  *     device workspace whose size the *_workspace_bytes query returns (0 = none needed).
+ *     A workspace needs no initialisation and holds nothing between calls; two calls that
+ *     may run at the same time need different workspaces.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *     enqueue work: they never synchronise and never read device data on the host.  Results,
  *     including counters and flags, land in device memory.

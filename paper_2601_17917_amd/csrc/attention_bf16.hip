@@ -279,7 +279,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
 #undef SDLLM_LOAD_TILE
 #undef SDLLM_STORE_TILE
 
-// merge the key-range splits of every output row: fixed order, fp32
+// merge the key-range splits of every output row: fixed (index) order, fp32.  The loads of up to
+// four splits are issued together so that a row costs about one memory round trip.
 template <int D>
 __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a, long long total_rows) {
   constexpr int TPR = D / 4;                       // threads per row
@@ -288,15 +289,25 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a, long long
   if (row >= total_rows) return;
   const int d = (threadIdx.x % TPR) * 4;
   const float* ml = a.ws_ml + row * a.nsplit * 2;
+  const float* po = a.ws_o + row * a.nsplit * D + d;
   float M = kNegBigA;
   for (int k = 0; k < a.nsplit; ++k) M = fmaxf(M, ml[2 * k]);
   float L = 0.f;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  for (int k = 0; k < a.nsplit; ++k) {
-    const float w = exp2_fast(ml[2 * k] - M);
-    L += w * ml[2 * k + 1];
-    const f32x4 ov = *reinterpret_cast<const f32x4*>(a.ws_o + (row * a.nsplit + k) * D + d);
-    acc += ov * w;
+  for (int k0 = 0; k0 < a.nsplit; k0 += 4) {
+    f32x4 ov[4]; float mk[4], lk[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int k = min(k0 + u, a.nsplit - 1);
+      ov[u] = *reinterpret_cast<const f32x4*>(po + (long long)k * D);
+      mk[u] = ml[2 * k]; lk[u] = ml[2 * k + 1];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float w = (k0 + u < a.nsplit) ? exp2_fast(mk[u] - M) : 0.f;
+      L += w * lk[u];
+      acc += ov[u] * w;
+    }
   }
   const float inv = 1.0f / L;
   const long long grp = row / a.Rtot;
@@ -323,8 +334,10 @@ AttnPlan plan_attention_bf16(const sdllm_attn_params& p) {
   if (p.kv_splits > 0) {
     ns = p.kv_splits;
   } else {
-    ns = (2LL * kNumCUs + base - 1) / base;        // aim at two workgroups per CU
-    const long long cap2 = pl.key_tiles / 2;       // but at least two key tiles per split
+    ns = (2LL * kNumCUs + base - 1) / base;        // aim at two workgroups per CU ...
+    // ... but keep a split long enough to amortise its merge: 8 key tiles, or 2 when the
+    // launch would otherwise leave most of the chip idle
+    const long long cap2 = pl.key_tiles / (base >= kNumCUs / 2 ? 8 : 2);
     if (ns > cap2) ns = cap2;
   }
   if (ns > pl.key_tiles) ns = pl.key_tiles;

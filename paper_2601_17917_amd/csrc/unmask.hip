@@ -1,12 +1,15 @@
 // Confidence-aware unmasking (paper Eq. 4, 5, 9, 10; block termination; EOS early exit).
 //
-// Two launches:
+// Two launches on the caller's stream:
 //  1. unmask_rows: a bandwidth-bound streaming reduction.  Every masked row of logits is
 //     split over `nsplit` workgroups; each streams its vocabulary slice once with 16-byte
 //     loads and reduces it to a (max, sum of exp relative to that max, lowest argmax id)
 //     triple.  Rows of unmasked positions are never read.
-//  2. unmask_commit: one workgroup per sequence merges the triples in a fixed order,
+//  2. unmask_commit: one workgroup per sequence merges the triples in a fixed pattern,
 //     forms c_i = 1 / sum, evaluates the threshold, commits, and writes the flags.
+// (A single launch in which the last workgroup to arrive commits its sequence was measured
+// and dropped: the device-scope release/acquire fences it needs write back and invalidate
+// the L2 of an XCD on every workgroup and cost several times the second launch.)
 #include "common.h"
 
 namespace sdllm {
@@ -49,23 +52,25 @@ template <> struct Vec<float> {      // 4 per 16 bytes
   }
 };
 
-struct RowArgs {
+struct UnmaskArgs {
   const void* logits;
-  const uint8_t* masked;
   Partial* partials;       // [rows][nsplit]
+  int32_t* tokens; uint8_t* masked; float* confidence;
+  int32_t* n_committed; uint8_t* block_done; uint8_t* eos_seen;
   long long ld;            // elements
   int V;
   int nvec;                // 16-byte vectors covering V (last one may be partial)
   int vec_per_split;
   int nsplit;
+  int nsplit_p2;           // nsplit rounded up to a power of two (<= 64)
+  int K;
+  float tau0, alpha; int r_extra_masked, r_extra_total; int eos_id; float tau_eos;
 };
 
+// Streams vocabulary slice `split` of one row; the merged triple of the workgroup ends in thread 0.
 template <typename T>
-__global__ __launch_bounds__(kRowThreads) void unmask_rows_kernel(RowArgs a) {
+__device__ __forceinline__ Partial reduce_row_slice(const UnmaskArgs& a, int row, int split, Partial* red) {
   constexpr int N = Vec<T>::N;
-  const int row = blockIdx.x / a.nsplit;
-  const int split = blockIdx.x - row * a.nsplit;
-  if (a.masked[row] == 0) return;          // uniform per workgroup
   const u32x4* __restrict__ base = reinterpret_cast<const u32x4*>(reinterpret_cast<const T*>(a.logits) + (long long)row * a.ld);
   const int v_begin = split * a.vec_per_split;
   const int v_end = min(v_begin + a.vec_per_split, a.nvec);
@@ -132,57 +137,61 @@ __global__ __launch_bounds__(kRowThreads) void unmask_rows_kernel(RowArgs a) {
     for (int j = N - 1; j >= 0; --j) if (x[j] == m && mvec * N + j < a.V) idx = mvec * N + j;
   }
 
-  // wave reduction, then across the 4 waves through LDS
+  // wave reduction, then across the waves through LDS
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) {
     float m2 = __shfl_xor(m, off); float s2 = __shfl_xor(s, off); int i2 = __shfl_xor(idx, off);
     merge_partial(m, s, idx, m2, s2, i2);
   }
-  __shared__ Partial red[kRowThreads / 64];
   if ((tid & 63) == 0) red[tid >> 6] = Partial{m, s, idx};
   __syncthreads();
   if (tid == 0) {
 #pragma unroll
     for (int w = 1; w < kRowThreads / 64; ++w) merge_partial(m, s, idx, red[w].m, red[w].s, red[w].idx);
-    a.partials[(long long)row * a.nsplit + split] = Partial{m, s, idx};
   }
+  return Partial{m, s, idx};
 }
 
-struct CommitArgs {
-  const Partial* partials;
-  int32_t* tokens; uint8_t* masked; float* confidence;
-  int32_t* n_committed; uint8_t* block_done; uint8_t* eos_seen;
-  int K; int nsplit;
-  float tau0, alpha; int r_extra_masked, r_extra_total; int eos_id; float tau_eos;
-};
-
-constexpr int kCommitThreads = 256;
-
-__global__ __launch_bounds__(kCommitThreads) void unmask_commit_kernel(CommitArgs a) {
-  extern __shared__ float conf_s[];            // K confidences (0 for unmasked positions), then K predicted ids
-  int* xhat_s = reinterpret_cast<int*>(conf_s + a.K);
+// Threshold, selection, update and flags of sequence b (Eq. 10, 9, 5), run by one whole workgroup
+// once every triple of the sequence is visible.
+__device__ __forceinline__ void commit_sequence(const UnmaskArgs& a, int b, float* conf_s, int* xhat_s) {
   __shared__ int cnt_masked, cnt_thr, eos_hit;
-  __shared__ float best_c[kCommitThreads / 64];
-  __shared__ int best_i[kCommitThreads / 64];
-  const int b = blockIdx.x, tid = threadIdx.x, K = a.K;
+  __shared__ float best_c[kRowThreads / 64];
+  __shared__ int best_i[kRowThreads / 64];
+  const int tid = threadIdx.x, K = a.K;
   if (tid == 0) { cnt_masked = 0; cnt_thr = 0; eos_hit = 0; }
   __syncthreads();
 
-  // pass 1: per masked position merge the splits (fixed order), c = 1 / sum
+  // pass 1: nsplit_p2 adjacent lanes hold the triples of one position and merge them with a
+  // butterfly (fixed pattern); all loads of a pass are independent.
+  const int P2 = a.nsplit_p2;
+  const int pos_per_pass = kRowThreads / P2;
+  const int k = tid & (P2 - 1);
   int my_masked = 0;
-  for (int i = tid; i < K; i += kCommitThreads) {
-    const long long pos = (long long)b * K + i;
-    float c = 0.f;
-    if (a.masked[pos] != 0) {
-      const Partial* p = a.partials + pos * a.nsplit;
-      float m = p[0].m, s = p[0].s; int idx = p[0].idx;
-      for (int k = 1; k < a.nsplit; ++k) merge_partial(m, s, idx, p[k].m, p[k].s, p[k].idx);
-      c = 1.0f / s;
-      my_masked++;
-      if (a.confidence) a.confidence[pos] = c;
-      xhat_s[i] = idx;
+  for (int i0 = 0; i0 < K; i0 += pos_per_pass) {
+    const int i = i0 + tid / P2;
+    const bool in = i < K;
+    const long long pos = (long long)b * K + (in ? i : 0);
+    const bool is_masked = in && a.masked[pos] != 0;
+    float m = kNegBig, s = 0.f; int idx = 0x7fffffff;
+    if (is_masked && k < a.nsplit) {
+      const Partial p = a.partials[pos * a.nsplit + k];
+      m = p.m; s = p.s; idx = p.idx;
     }
-    conf_s[i] = c;
+    for (int off = P2 >> 1; off >= 1; off >>= 1) {
+      float m2 = __shfl_xor(m, off); float s2 = __shfl_xor(s, off); int i2 = __shfl_xor(idx, off);
+      merge_partial(m, s, idx, m2, s2, i2);
+    }
+    if (in && k == 0) {
+      float c = 0.f;
+      if (is_masked) {
+        c = 1.0f / s;
+        my_masked++;
+        if (a.confidence) a.confidence[pos] = c;
+        xhat_s[i] = idx;
+      }
+      conf_s[i] = c;
+    }
   }
   if (my_masked) atomicAdd(&cnt_masked, my_masked);
   __syncthreads();
@@ -197,7 +206,7 @@ __global__ __launch_bounds__(kCommitThreads) void unmask_commit_kernel(CommitArg
 
   // pass 2: threshold commits + candidates for the fallback
   float bc = -1.f; int bi = 0x7fffffff; int my_thr = 0;
-  for (int i = tid; i < K; i += kCommitThreads) {
+  for (int i = tid; i < K; i += kRowThreads) {
     const long long pos = (long long)b * K + i;
     if (a.masked[pos] == 0) continue;
     const float c = conf_s[i];
@@ -221,7 +230,7 @@ __global__ __launch_bounds__(kCommitThreads) void unmask_commit_kernel(CommitArg
   if (tid == 0) {
     int ncommit = cnt_thr;
     if (ncommit == 0) {                     // fallback: single most confident masked position
-      for (int w = 1; w < kCommitThreads / 64; ++w)
+      for (int w = 1; w < kRowThreads / 64; ++w)
         if (best_c[w] > bc || (best_c[w] == bc && best_i[w] < bi)) { bc = best_c[w]; bi = best_i[w]; }
       const long long pos = (long long)b * K + bi;
       const int xhat = xhat_s[bi];
@@ -234,6 +243,22 @@ __global__ __launch_bounds__(kCommitThreads) void unmask_commit_kernel(CommitArg
     a.block_done[b] = (m_b - ncommit == 0) ? 1 : 0;
     if (a.eos_seen && eos_hit) a.eos_seen[b] = 1;
   }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kRowThreads) void unmask_rows_kernel(UnmaskArgs a) {
+  __shared__ Partial red[kRowThreads / 64];
+  const int row = blockIdx.x / a.nsplit;
+  const int split = blockIdx.x - row * a.nsplit;
+  if (a.masked[row] == 0) return;            // uniform per workgroup
+  const Partial p = reduce_row_slice<T>(a, row, split, red);
+  if (threadIdx.x == 0) a.partials[(long long)row * a.nsplit + split] = p;
+}
+
+__global__ __launch_bounds__(kRowThreads) void unmask_commit_kernel(UnmaskArgs a) {
+  extern __shared__ float conf_s[];          // K confidences, then K predicted ids
+  int* xhat_s = reinterpret_cast<int*>(conf_s + a.K);
+  commit_sequence(a, blockIdx.x, conf_s, xhat_s);
 }
 
 int unmask_splits(const sdllm_unmask_params& p) {
@@ -258,25 +283,26 @@ hipError_t launch_unmask(const sdllm_unmask_params& p, const void* logits, int32
                          float* confidence, int32_t* n_committed, uint8_t* block_done, uint8_t* eos_seen,
                          void* workspace, hipStream_t stream) {
   const int N = p.dtype == SDLLM_FP32 ? 4 : 8;
-  RowArgs r;
-  r.logits = logits; r.masked = masked; r.partials = (Partial*)workspace;
-  r.ld = p.ld; r.V = p.V;
+  UnmaskArgs r;
+  r.logits = logits; r.masked = masked;
+  r.partials = (Partial*)workspace;
+  r.tokens = tokens; r.confidence = confidence;
+  r.n_committed = n_committed; r.block_done = block_done; r.eos_seen = eos_seen;
+  r.ld = p.ld; r.V = p.V; r.K = p.K;
   r.nvec = (p.V + N - 1) / N;
   r.nsplit = unmask_splits(p);
+  r.nsplit_p2 = 1;
+  while (r.nsplit_p2 < r.nsplit) r.nsplit_p2 <<= 1;
   r.vec_per_split = (r.nvec + r.nsplit - 1) / r.nsplit;
+  r.tau0 = p.tau0; r.alpha = p.alpha; r.r_extra_masked = p.r_extra_masked; r.r_extra_total = p.r_extra_total;
+  r.eos_id = p.eos_id; r.tau_eos = p.tau_eos;
   dim3 grid((unsigned)((long long)p.B * p.K * r.nsplit), 1, 1);
   if (p.dtype == SDLLM_FP32) hipLaunchKernelGGL(unmask_rows_kernel<float>, grid, dim3(kRowThreads), 0, stream, r);
   else hipLaunchKernelGGL(unmask_rows_kernel<uint16_t>, grid, dim3(kRowThreads), 0, stream, r);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  CommitArgs c;
-  c.partials = (const Partial*)workspace;
-  c.tokens = tokens; c.masked = masked; c.confidence = confidence;
-  c.n_committed = n_committed; c.block_done = block_done; c.eos_seen = eos_seen;
-  c.K = p.K; c.nsplit = r.nsplit;
-  c.tau0 = p.tau0; c.alpha = p.alpha; c.r_extra_masked = p.r_extra_masked; c.r_extra_total = p.r_extra_total;
-  c.eos_id = p.eos_id; c.tau_eos = p.tau_eos;
-  hipLaunchKernelGGL(unmask_commit_kernel, dim3(p.B), dim3(kCommitThreads), (size_t)p.K * (sizeof(float) + sizeof(int)), stream, c);
+  const size_t lds = (size_t)p.K * (sizeof(float) + sizeof(int));
+  hipLaunchKernelGGL(unmask_commit_kernel, dim3(p.B), dim3(kRowThreads), lds, stream, r);
   return hipGetLastError();
 }
 

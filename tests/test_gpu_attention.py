@@ -159,5 +159,29 @@ def test_attention_rejects_bad_arguments(gpu_lib):
     with pytest.raises(sd.SdllmError) as e:       # workspace too small for a forced split
         sd.block_attention(d["q_block"], d["q_suffix"], d["k_cache"], d["v_cache"], d["k_block"], d["v_block"],
                            d["k_suffix"], d["v_suffix"], d["keep_idx"], w.P, kv_splits=2,
-                           workspace=torch.empty(64, dtype=torch.uint8, device="cuda"))
+                           workspace=torch.zeros(64, dtype=torch.uint8, device="cuda"))
     assert e.value.status == sd.ERR_WORKSPACE
+
+
+def test_workspace_reuse_with_garbage(gpu_lib):
+    """A workspace needs no initialisation and carries nothing between calls: one buffer, filled with
+    garbage, serves attention and unmask calls of different shapes one after the other."""
+    from oracle import confidence_unmask as oracle_unmask
+    sd = gpu_lib
+    ws = torch.full((64 << 20,), 0xA5, dtype=torch.uint8, device="cuda")
+    for rep, (name, splits) in enumerate([("small_bf16", 3), ("small_bf16", 2), ("cfg2", 0), ("small_bf16", 4)]):
+        w = wl.WORKLOADS[name]
+        t = wl.make_attention_inputs(w, seed=rep)
+        d = attn_to_dev(t)
+        out = sd.block_attention(d["q_block"], d["q_suffix"], d["k_cache"], d["v_cache"], d["k_block"], d["v_block"],
+                                 d["k_suffix"], d["v_suffix"], d["keep_idx"], w.P, kv_splits=splits, workspace=ws)
+        torch.cuda.synchronize()
+        assert np.abs(to_f64_host(out) - oracle(t, w.P)).max() <= TOL["bf16"], (name, splits)
+        u = wl.make_unmask_inputs(wl.WORKLOADS["small_bf16"], seed=rep)
+        tk = torch.from_numpy(u["tokens"]).cuda()
+        mk = torch.from_numpy(u["masked"]).cuda()
+        lg = torch.from_numpy(u["logits"].view(np.int16)).view(torch.bfloat16).cuda()
+        sd.confidence_unmask(lg, tk, mk, 0.9, 0.3, workspace=ws)
+        torch.cuda.synchronize()
+        ref = oracle_unmask(wl.to_f64(u["logits"]), u["tokens"], u["masked"], float(np.float32(0.9)), float(np.float32(0.3)))
+        assert (tk.cpu().numpy() == ref["tokens"]).all() and (mk.cpu().numpy() == ref["masked"]).all()
