@@ -81,6 +81,9 @@ int check_append_params(const sdllm_append_params* p) {
     return fail(SDLLM_ERR_UNSUPPORTED, "kv_append: row size %d bytes must be a multiple of 16", p->D * elem);
   const long long dense_c = (long long)p->B * p->Hkv * p->prefix_cap * p->D;
   const long long dense_b = (long long)p->B * p->Hkv * p->K * p->D;
+  if ((long long)p->n_layers * p->B * p->Hkv * (((long long)p->K * p->D * elem / 16 + 1023) / 1024) > 0x7fffffffLL ||
+      (long long)p->K * p->D * elem / 16 > 0x7fffffffLL)
+    return fail(SDLLM_ERR_UNSUPPORTED, "kv_append: problem too large for one launch");
   if (p->cache_layer_stride != 0 && (p->cache_layer_stride < dense_c || (p->cache_layer_stride * elem) % 16 != 0))
     return fail(SDLLM_ERR_INVALID_ARG, "kv_append: cache_layer_stride too small or not 16-byte aligned");
   if (p->block_layer_stride != 0 && (p->block_layer_stride < dense_b || (p->block_layer_stride * elem) % 16 != 0))

@@ -14,45 +14,44 @@ struct AppendArgs {
   long long cache_layer_stride16;   // in 16-byte chunks
   long long block_layer_stride16;
   long long seq_cache16;            // Hkv * cap * row16
-  int run16;                        // K * row16: chunks per (layer, b, h) run
+  int run16;                        // K * row16: contiguous chunks per (layer, b, h) run
   int row16;                        // 16-byte chunks per row (D * elem / 16)
   int cap_rows; int P;
-  int Hkv; int B; int L;
-  long long total16;                // chunks per tensor (K or V): L*B*Hkv*run16
+  int Hkv; int B;
+  int parts;                        // workgroups per run
 };
 
 constexpr int kAppendUnroll = 4;
+constexpr int kAppendChunksPerWG = 256 * kAppendUnroll;
 
+// One workgroup moves up to 16 KiB of one (layer, batch, head) run.  The run is decoded once per
+// workgroup with scalar arithmetic; a lane only adds its offset.  Each access instruction of a
+// wave covers 1 KiB contiguous; all loads are issued before the stores.
 __global__ __launch_bounds__(256) void kv_append_kernel(AppendArgs a) {
-  // blockIdx.y selects K (0) or V (1); each thread moves kAppendUnroll chunks spaced by the
-  // block size so that every access instruction of a wave covers 1 KiB contiguous.
   const u32x4* __restrict__ src = blockIdx.y ? a.vb : a.kb;
   u32x4* __restrict__ dst = blockIdx.y ? a.vc : a.kc;
-  long long base = ((long long)blockIdx.x * kAppendUnroll) * 256 + threadIdx.x;
+  const unsigned run = blockIdx.x / (unsigned)a.parts;
+  const unsigned part = blockIdx.x - run * (unsigned)a.parts;
+  const unsigned h = run % (unsigned)a.Hkv;
+  const unsigned t = run / (unsigned)a.Hkv;
+  const unsigned b = t % (unsigned)a.B;
+  const unsigned l = t / (unsigned)a.B;
+  if (a.do_append != nullptr && a.do_append[b] == 0) return;   // uniform
+  const long long soff = (long long)l * a.block_layer_stride16 + ((long long)b * a.Hkv + h) * a.run16;
+  const long long doff = (long long)l * a.cache_layer_stride16 + (long long)b * a.seq_cache16 +
+                         ((long long)h * a.cap_rows + a.P) * a.row16;
+  const int c0 = (int)part * kAppendChunksPerWG + (int)threadIdx.x;
   u32x4 v[kAppendUnroll];
-  long long doff[kAppendUnroll];
-  bool ok[kAppendUnroll];
 #pragma unroll
   for (int u = 0; u < kAppendUnroll; ++u) {
-    long long i = base + (long long)u * 256;
-    ok[u] = i < a.total16;
-    long long ii = ok[u] ? i : 0;
-    // i -> (layer, b, h, chunk within run)
-    long long run = ii / a.run16;
-    int c = (int)(ii - run * a.run16);
-    int h = (int)(run % a.Hkv);
-    long long t = run / a.Hkv;
-    int b = (int)(t % a.B);
-    int l = (int)(t / a.B);
-    if (ok[u] && a.do_append != nullptr && a.do_append[b] == 0) ok[u] = false;
-    long long soff = (long long)l * a.block_layer_stride16 + ((long long)b * a.Hkv + h) * a.run16 + c;
-    doff[u] = (long long)l * a.cache_layer_stride16 + (long long)b * a.seq_cache16 +
-              ((long long)h * a.cap_rows + a.P) * a.row16 + c;
-    if (ok[u]) v[u] = __builtin_nontemporal_load(src + soff);
+    const int c = c0 + u * 256;
+    if (c < a.run16) v[u] = __builtin_nontemporal_load(src + soff + c);
   }
 #pragma unroll
-  for (int u = 0; u < kAppendUnroll; ++u)
-    if (ok[u]) __builtin_nontemporal_store(v[u], dst + doff[u]);
+  for (int u = 0; u < kAppendUnroll; ++u) {
+    const int c = c0 + u * 256;
+    if (c < a.run16) __builtin_nontemporal_store(v[u], dst + doff + c);
+  }
 }
 
 hipError_t launch_kv_append(const sdllm_append_params& p, void* k_caches, void* v_caches,
@@ -71,11 +70,9 @@ hipError_t launch_kv_append(const sdllm_append_params& p, void* k_caches, void* 
   a.block_layer_stride16 = bls * elem / 16;
   a.seq_cache16 = (long long)p.Hkv * p.prefix_cap * a.row16;
   a.cap_rows = p.prefix_cap; a.P = p.prefix_len;
-  a.Hkv = p.Hkv; a.B = p.B; a.L = p.n_layers;
-  a.total16 = (long long)p.n_layers * p.B * p.Hkv * a.run16;
-  const long long per_block = 256LL * kAppendUnroll;
-  long long blocks = (a.total16 + per_block - 1) / per_block;
-  if (blocks <= 0) return hipSuccess;
+  a.Hkv = p.Hkv; a.B = p.B;
+  a.parts = (a.run16 + kAppendChunksPerWG - 1) / kAppendChunksPerWG;
+  const long long blocks = (long long)p.n_layers * p.B * p.Hkv * a.parts;
   dim3 grid((unsigned)blocks, 2, 1);
   hipLaunchKernelGGL(kv_append_kernel, grid, dim3(256), 0, stream, a);
   return hipGetLastError();

@@ -11,6 +11,7 @@
 // and dropped: the device-scope release/acquire fences it needs write back and invalidate
 // the L2 of an XCD on every workgroup and cost several times the second launch.)
 #include "common.h"
+#include <cstdlib>
 
 namespace sdllm {
 
@@ -262,6 +263,9 @@ __global__ __launch_bounds__(kRowThreads) void unmask_commit_kernel(UnmaskArgs a
 }
 
 int unmask_splits(const sdllm_unmask_params& p) {
+  // tuning knob for sweeps: SDLLM_UNMASK_SPLITS=n forces the split count (read once)
+  static const int forced = [] { const char* e = getenv("SDLLM_UNMASK_SPLITS"); return e ? atoi(e) : 0; }();
+  if (forced >= 1 && forced <= 64) return forced;
   const int N = p.dtype == SDLLM_FP32 ? 4 : 8;
   const long long nvec = ((long long)p.V + N - 1) / N;
   // aim at >= 8 workgroups per CU over the rows, but keep >= 2 main-loop iterations per split
