@@ -6,9 +6,11 @@
 //             g*Nq query rows are treated as one list of "virtual rows" and tiled together.
 //   workgroup = (group, query tile of 64*RB rows, key-range split); 4 waves, wave w owns the
 //             16*RB rows  [w*16*RB, (w+1)*16*RB) of the tile for all keys of the split.
-//   K/V tiles of 64 keys are staged in LDS (two stages, one barrier per tile); rows come from
-//             three places (cache, block, suffix[keep_idx]) and are addressed per row, so the
-//             gather costs nothing extra: a row is 16 lanes x 16 B, fully coalesced.
+//   K/V tiles of 64 keys stream through an LDS ring of NST stages.  They are moved global -> LDS
+//             directly (global_load_lds_dwordx4: no register staging), NST-1 tiles ahead of the
+//             one being computed, one workgroup barrier per tile.  Rows come from three places
+//             (cache, block, suffix[keep_idx]) and are addressed per row, so the gather costs
+//             nothing extra: a row is 16 lanes x 16 B, fully coalesced.
 // Math (all MFMA v_mfma_f32_16x16x32_bf16, fp32 accumulate)
 //   S^T = K Q^T  : A = K rows from LDS, B = Q rows from registers.  The accumulator of lane
 //                  (q = lane%16, G = lane/16) holds keys 16*kb + 4*G + i of query row q, so a
@@ -18,6 +20,7 @@
 //   Online softmax in the log2 domain; a split writes (unnormalised O, m, l) and a second
 //   kernel merges the splits in a fixed order (deterministic, no atomics).
 #include "common.h"
+#include <cstdlib>
 
 namespace sdllm {
 
@@ -55,18 +58,47 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
 }
 
-template <int D, int RB>
+// One 16-byte-per-lane global -> LDS transfer (the data never passes through registers): lane i's
+// 16 bytes land at lds_addr + 16*i.  Issued through inline assembly so that the compiler's
+// wait-count insertion does not serialise a multi-stage pipeline; completion is tracked by hand
+// with s_waitcnt vmcnt(n) before the workgroup barrier (transfers complete in issue order).
+__device__ __forceinline__ void dma16_sbase(unsigned lds_addr, const void* sbase, unsigned voff) {
+  // the base is the same in every lane; say so, so that it is held in a scalar register pair
+  const unsigned long long p = reinterpret_cast<unsigned long long>(sbase);
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)p);
+  const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(p >> 32));
+  const unsigned long long pu = ((unsigned long long)hi << 32) | lo;
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(pu) : "memory", "m0");
+}
+__device__ __forceinline__ void dma16_vaddr(unsigned lds_addr, const void* vaddr) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+               :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(vaddr) : "memory", "m0");
+}
+// s_waitcnt vmcnt(n) only (expcnt / lgkmcnt fields left at "no wait")
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+template <int D, int RB, int NST>
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
-  constexpr int LDK = D + 8;                       // K rows: +16 B, so 16 rows x 16 B (one b128 read phase) cover all banks
-  constexpr int LDV = D + 16;                      // V rows: +32 B, so 8 rows x 32 B (one transpose-read phase) cover all banks
   constexpr int CPR = D / 8;                       // 16-byte chunks per row
-  constexpr int RPP = 256 / CPR;                   // rows loaded per pass of the workgroup
-  constexpr int NP = kKeyTile / RPP;               // passes per tile
+  constexpr int RPI = 64 / CPR;                    // rows covered by one wave-wide transfer
+  constexpr int IPT = 16 / RPI;                    // transfers per wave per tile per tensor (a wave loads 16 rows)
+  constexpr int LPT = 2 * IPT;                     // ... for K and V together
+  constexpr int R256 = 16 / CPR;                   // rows per 256 bytes of LDS
   constexpr int NS = D / 32;                       // 32-wide d slices (QK^T contraction steps)
   constexpr int NDB = D / 16;                      // 16-wide d blocks of the output
-  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
-  uint16_t (*Ks)[kKeyTile][LDK] = reinterpret_cast<uint16_t (*)[kKeyTile][LDK]>(lds);
-  uint16_t (*Vs)[kKeyTile][LDV] = reinterpret_cast<uint16_t (*)[kKeyTile][LDV]>(lds + 2 * kKeyTile * LDK);
+  constexpr int ROWB = D * 2;                      // bytes per row
+  constexpr int TILEB = kKeyTile * ROWB;           // bytes per tile per tensor
+  constexpr int STAGEB = 2 * TILEB;                // one stage: K tile, then V tile
+  // LDS rows are unpadded (a transfer writes 1 KiB contiguous); bank conflicts are avoided by
+  // storing chunk c of row r at position c ^ f(r):  f_K(r) = (r / R256) % CPR makes the 16 rows of
+  // one b128 read phase hit 16 different positions, f_V(r) = 2 * ((r / R256) % (CPR/2)) does the
+  // same for the 8 rows x 32 bytes of one transpose-read phase.
+  extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)lds;
 
   // ---- which piece of work: workgroups that share K/V (query tiles of one unit) sit on one XCD
   const int xcd = blockIdx.x % kNumXCDs, slot = blockIdx.x / kNumXCDs;
@@ -78,7 +110,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   const int t0 = split * a.tiles_per_split;
   const int t1 = min(t0 + a.tiles_per_split, a.key_tiles);
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l16 = lane & 15, G = lane >> 4;
 
   const long long bh = (long long)b * a.Hkv + kvh;
@@ -89,36 +122,70 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   const uint16_t* ks = a.k_suffix + bh * a.S * D;
   const uint16_t* vs = a.v_suffix + bh * a.S * D;
 
-  // ---- global -> register staging of one K/V tile (rows clamped into the valid range)
-  const int lrow = tid / CPR, lchunk = tid % CPR;
-  u32x4 kreg[NP], vreg[NP];
-#define SDLLM_LOAD_TILE(tile)                                                                   \
-  if (((tile) + 1) * kKeyTile <= a.P) {          /* uniform: whole tile inside the prefix cache */ \
-    const long long off0 = ((long long)(tile) * kKeyTile + lrow) * D + lchunk * 8;              \
-    _Pragma("unroll") for (int p = 0; p < NP; ++p) {                                            \
-      kreg[p] = *reinterpret_cast<const u32x4*>(kc + off0 + (long long)p * RPP * D);            \
-      vreg[p] = *reinterpret_cast<const u32x4*>(vc + off0 + (long long)p * RPP * D);            \
-    }                                                                                           \
-  } else {                                                                                      \
-    _Pragma("unroll") for (int p = 0; p < NP; ++p) {                                            \
-      int r = (tile) * kKeyTile + lrow + p * RPP;                                               \
-      r = min(r, a.Nkv - 1);                                                                    \
-      const uint16_t* kp; const uint16_t* vp; long long off;                                    \
-      if (r < a.P) { kp = kc; vp = vc; off = (long long)r * D; }                                \
-      else if (r < a.P + a.K) { kp = kb; vp = vb; off = (long long)(r - a.P) * D; }             \
-      else { kp = ks; vp = vs; off = (long long)a.keep_idx[r - a.P - a.K] * D; }                \
-      off += lchunk * 8;                                                                        \
-      kreg[p] = *reinterpret_cast<const u32x4*>(kp + off);                                      \
-      vreg[p] = *reinterpret_cast<const u32x4*>(vp + off);                                      \
-    }                                                                                           \
+  // keep_idx read through the constant address space: uniform indices become scalar loads, which
+  // do not touch the vector-memory counter that tracks the transfers in flight
+  typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+  const const_i32_ptr keep_c = (const_i32_ptr)(uintptr_t)a.keep_idx;
+
+  // ---- transfer map of this lane: row within the tile and (swizzled) source chunk per transfer
+  unsigned kgo[IPT], vgo[IPT];                     // byte offset of the lane's source chunk within a tile
+#pragma unroll
+  for (int j = 0; j < IPT; ++j) {
+    const int r = 16 * wave + RPI * j + lane / CPR, q = lane % CPR;
+    kgo[j] = r * ROWB + ((q ^ ((r / R256) % CPR)) << 4);
+    vgo[j] = r * ROWB + ((q ^ (2 * ((r / R256) % (CPR / 2)))) << 4);
   }
-#define SDLLM_STORE_TILE(stage)                                                                 \
-  _Pragma("unroll") for (int p = 0; p < NP; ++p) {                                              \
-    *reinterpret_cast<u32x4*>(&Ks[stage][lrow + p * RPP][lchunk * 8]) = kreg[p];                \
-    *reinterpret_cast<u32x4*>(&Vs[stage][lrow + p * RPP][lchunk * 8]) = vreg[p];                \
+#define SDLLM_ISSUE_TILE(tile, stage)                                                             \
+  {                                                                                               \
+    const unsigned sb = lds_base + (stage) * STAGEB + 16 * wave * ROWB;                           \
+    if (((tile) + 1) * kKeyTile <= a.P) {        /* uniform: whole tile inside the prefix cache */ \
+      const unsigned char* kt = reinterpret_cast<const unsigned char*>(kc) + (long long)(tile) * TILEB; \
+      const unsigned char* vt = reinterpret_cast<const unsigned char*>(vc) + (long long)(tile) * TILEB; \
+      _Pragma("unroll") for (int j = 0; j < IPT; ++j) dma16_sbase(sb + j * RPI * ROWB, kt, kgo[j]); \
+      _Pragma("unroll") for (int j = 0; j < IPT; ++j) dma16_sbase(sb + TILEB + j * RPI * ROWB, vt, vgo[j]); \
+    } else {   /* block / gathered suffix rows, ragged tail: no divergent branch, keep_idx through scalar loads */ \
+      const int r0 = (tile) * kKeyTile + 16 * wave;                       /* uniform */           \
+      const unsigned char* kpp[IPT]; const unsigned char* vpp[IPT];                               \
+      _Pragma("unroll") for (int j = 0; j < IPT; ++j) {                                           \
+        const int rl = RPI * j + lane / CPR;                                                      \
+        const int r = min(r0 + rl, a.Nkv - 1);                                                    \
+        int kidx = 0;                                                                             \
+        if (a.n_keep > 0) {                                                                       \
+          _Pragma("unroll") for (int q2 = 0; q2 < RPI; ++q2) {                                    \
+            const int si = min(max(r0 + RPI * j + q2 - a.P - a.K, 0), a.n_keep - 1);              \
+            const int v = keep_c[si];                                     /* uniform address */   \
+            kidx = (lane / CPR == q2) ? v : kidx;                                                 \
+          }                                                                                       \
+        }                                                                                         \
+        const bool in_c = r < a.P, in_b = r < a.P + a.K;                                          \
+        const uint16_t* kp = in_c ? kc : (in_b ? kb : ks);                                        \
+        const uint16_t* vp = in_c ? vc : (in_b ? vb : vs);                                        \
+        const long long off = (long long)(in_c ? r : (in_b ? r - a.P : kidx)) * D;                \
+        kpp[j] = reinterpret_cast<const unsigned char*>(kp + off) + (kgo[j] - (16 * wave + rl) * ROWB); \
+        vpp[j] = reinterpret_cast<const unsigned char*>(vp + off) + (vgo[j] - (16 * wave + rl) * ROWB); \
+      }                                                                                           \
+      _Pragma("unroll") for (int j = 0; j < IPT; ++j) dma16_vaddr(sb + j * RPI * ROWB, kpp[j]);   \
+      _Pragma("unroll") for (int j = 0; j < IPT; ++j) dma16_vaddr(sb + TILEB + j * RPI * ROWB, vpp[j]); \
+    }                                                                                             \
   }
 
-  SDLLM_LOAD_TILE(t0)
+  // ---- prologue: the first NST-1 tiles go in flight
+#pragma unroll
+  for (int i = 0; i < NST - 1; ++i)
+    if (t0 + i < t1) SDLLM_ISSUE_TILE(t0 + i, i)
+
+  // ---- LDS read offsets of this lane (bytes within a stage, before the compile-time row offsets)
+  unsigned kro[NS], vro[NDB];
+  {
+    const int fk = (D == 128) ? l16 : (l16 >> 1);
+#pragma unroll
+    for (int s2 = 0; s2 < NS; ++s2) kro[s2] = l16 * ROWB + (((4 * s2 + G) ^ fk) << 4);
+    const int e4 = l16 >> 2, c4 = l16 & 3;
+    const int fv = (D == 128) ? 2 * (4 * (G & 1) + e4) : 2 * (2 * (G & 1) + (e4 >> 1));
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+      vro[db] = TILEB + (4 * G + e4) * ROWB + (((2 * db + (c4 >> 1)) ^ fv) << 4) + ((c4 & 1) << 3);
+  }
 
   // ---- query rows of this wave, as MFMA B operands (lane: row l16, d = 32*s + 8*G .. +7)
   const int row_base = qt * (64 * RB) + wave * (16 * RB);
@@ -144,14 +211,23 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     for (int db = 0; db < NDB; ++db) o[rb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  SDLLM_STORE_TILE(0)
-  __syncthreads();
+  // the query rows (ordinary loads) are complete before the loop, so that the compiler places no
+  // vector-memory wait of its own inside it
+  wait_vmcnt<0>();
 
   for (int t = t0; t < t1; ++t) {
-    const int stage = (t - t0) & 1;
-    // next tile in flight while this one is computed (the last iteration re-loads its own tile: harmless)
-    const int tn = min(t + 1, t1 - 1);
-    SDLLM_LOAD_TILE(tn)
+    const int rel = t - t0;
+    const int stage = rel % NST;
+    // tile t has landed once at most the transfers of the newer tiles in flight are outstanding
+    {
+      const int newer = min(NST - 2, t1 - 1 - t);
+      if (NST >= 4 && newer >= 2) wait_vmcnt<(NST >= 4 ? 2 : 0) * LPT>();
+      else if (NST >= 3 && newer == 1) wait_vmcnt<(NST >= 3 ? 1 : 0) * LPT>();
+      else wait_vmcnt<0>();
+    }
+    __builtin_amdgcn_s_barrier();                  // every wave's part of tile t is in LDS; tile t-1 is consumed
+    if (t + NST - 1 < t1) SDLLM_ISSUE_TILE(t + NST - 1, (rel + NST - 1) % NST)
+    const unsigned char* st = lds + stage * STAGEB;
 
     // ---- S^T = K Q^T
     f32x4 sacc[RB][4];
@@ -163,7 +239,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     for (int kb4 = 0; kb4 < 4; ++kb4) {
 #pragma unroll
       for (int s = 0; s < NS; ++s) {
-        const bf16x8 kop = *reinterpret_cast<const bf16x8*>(&Ks[stage][kb4 * 16 + l16][32 * s + 8 * G]);
+        const bf16x8 kop = *reinterpret_cast<const bf16x8*>(st + kro[s] + kb4 * 16 * ROWB);
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
           sacc[rb][kb4] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, qreg[rb][s], sacc[rb][kb4], 0, 0, 0);
@@ -224,16 +300,15 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     }
 
     // ---- O^T += V^T P^T ; V^T operand through the LDS transpose read
-    const int e4 = l16 >> 2, c4 = l16 & 3;
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
 #pragma unroll
       for (int db = 0; db < NDB; ++db) {
         typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_s16x4_ptr)(&Vs[stage][32 * u + 4 * G + e4][16 * db + 4 * c4]));
+            (lds_s16x4_ptr)(st + vro[db] + (32 * u) * ROWB));
         const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_s16x4_ptr)(&Vs[stage][32 * u + 16 + 4 * G + e4][16 * db + 4 * c4]));
+            (lds_s16x4_ptr)(st + vro[db] + (32 * u + 16) * ROWB));
         const s16x8 vop = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
@@ -243,8 +318,6 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
       }
     }
 
-    SDLLM_STORE_TILE(stage ^ 1)
-    __syncthreads();
   }
 
   // ---- epilogue
@@ -276,8 +349,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   }
 }
 
-#undef SDLLM_LOAD_TILE
-#undef SDLLM_STORE_TILE
+#undef SDLLM_ISSUE_TILE
 
 // merge the key-range splits of every output row: fixed (index) order, fp32.  The loads of up to
 // four splits are issued together so that a row costs about one memory round trip.
@@ -325,7 +397,18 @@ AttnPlan plan_attention_bf16(const sdllm_attn_params& p) {
   const int g = p.Hq / p.Hkv;
   const long long Rtot = (long long)g * (p.K + p.n_keep);
   const long long Nkv = (long long)p.prefix_len + p.K + p.n_keep;
-  pl.rb = Rtot > 64 ? 2 : 1;
+  // tuning knobs for sweeps (read once): SDLLM_ATTN_RB = 1|2, SDLLM_ATTN_STAGES = 2|3|4
+  static const int env_rb = [] { const char* e = getenv("SDLLM_ATTN_RB"); return e ? atoi(e) : 0; }();
+  static const int env_st = [] { const char* e = getenv("SDLLM_ATTN_STAGES"); return e ? atoi(e) : 0; }();
+  // 32 query rows per wave (128 per workgroup) pay off only when many query rows share one K/V
+  // stream (dense suffix); measured: 1024 rows -> 1.4x faster, 448 rows (GQA 7:1) -> 8 % slower
+  pl.rb = Rtot >= 512 ? 2 : 1;
+  if (env_rb == 1 || env_rb == 2) pl.rb = env_rb;
+  // Two ring stages and two workgroups per CU.  Deeper rings (3, 4 stages: one workgroup per CU)
+  // were measured and are slower at every shape: with one wave per SIMD the per-tile latencies of
+  // the MFMA / softmax / LDS chain are exposed, and those, not the K/V stream, bound the loop.
+  pl.stages = 2;
+  if (env_st >= 2 && env_st <= 4) pl.stages = env_st;
   const int rows_wg = 64 * pl.rb;
   pl.q_tiles = (int)((Rtot + rows_wg - 1) / rows_wg);
   pl.key_tiles = (int)((Nkv + kKeyTile - 1) / kKeyTile);
@@ -335,9 +418,9 @@ AttnPlan plan_attention_bf16(const sdllm_attn_params& p) {
     ns = p.kv_splits;
   } else {
     ns = (2LL * kNumCUs + base - 1) / base;        // aim at two workgroups per CU ...
-    // ... but keep a split long enough to amortise its merge: 8 key tiles, or 2 when the
-    // launch would otherwise leave most of the chip idle
-    const long long cap2 = pl.key_tiles / (base >= kNumCUs / 2 ? 8 : 2);
+    // ... but keep a split long enough to amortise its merge: 16 key tiles, or 2 when the
+    // launch would otherwise leave most of the chip idle (sweeps: 17 tiles -> 1 split, 82 -> 2)
+    const long long cap2 = pl.key_tiles / (base >= kNumCUs / 2 ? 16 : 2);
     if (ns > cap2) ns = cap2;
   }
   if (ns > pl.key_tiles) ns = pl.key_tiles;
@@ -356,18 +439,30 @@ size_t attention_bf16_workspace_bytes(const sdllm_attn_params& p, const AttnPlan
   return rows * pl.kv_splits * (size_t)(p.D + 2) * sizeof(float);
 }
 
-template <int D, int RB>
+template <int D, int RB, int NST>
 static hipError_t launch_main(const AttnArgs& a, const AttnPlan& pl, hipStream_t stream) {
-  constexpr size_t lds_bytes = 2ull * kKeyTile * ((D + 8) + (D + 16)) * sizeof(uint16_t);
+  constexpr size_t lds_bytes = (size_t)NST * 2 * kKeyTile * D * sizeof(uint16_t);
   static bool attr_set = false;                     // benign race: the call is idempotent
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<D, RB>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<D, RB, NST>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((attn_bf16_kernel<D, RB>), dim3(pl.workgroups), dim3(256), lds_bytes, stream, a);
+  hipLaunchKernelGGL((attn_bf16_kernel<D, RB, NST>), dim3(pl.workgroups), dim3(256), lds_bytes, stream, a);
   return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_d(const AttnArgs& a, const AttnPlan& pl, hipStream_t stream) {
+  if (pl.rb == 2) {
+    if (pl.stages == 2) return launch_main<D, 2, 2>(a, pl, stream);
+    if (pl.stages == 3) return launch_main<D, 2, 3>(a, pl, stream);
+    return launch_main<D, 2, 4>(a, pl, stream);
+  }
+  if (pl.stages == 2) return launch_main<D, 1, 2>(a, pl, stream);
+  if (pl.stages == 3) return launch_main<D, 1, 3>(a, pl, stream);
+  return launch_main<D, 1, 4>(a, pl, stream);
 }
 
 hipError_t launch_attention_bf16(const sdllm_attn_params& p, const AttnPlan& pl,
@@ -394,8 +489,7 @@ hipError_t launch_attention_bf16(const sdllm_attn_params& p, const AttnPlan& pl,
   a.ws_ml = a.ws_o ? a.ws_o + rows * pl.kv_splits * (size_t)p.D : nullptr;
 
   hipError_t e;
-  if (p.D == 128) e = pl.rb == 2 ? launch_main<128, 2>(a, pl, stream) : launch_main<128, 1>(a, pl, stream);
-  else            e = pl.rb == 2 ? launch_main<64, 2>(a, pl, stream) : launch_main<64, 1>(a, pl, stream);
+  e = p.D == 128 ? launch_d<128>(a, pl, stream) : launch_d<64>(a, pl, stream);
   if (e != hipSuccess) return e;
   if (pl.kv_splits > 1) {
     const long long total_rows = (long long)rows;
