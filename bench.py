@@ -39,6 +39,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="leave the per-kernel HIP events out of the timed region (roofline.achieved = null)")
+    ap.add_argument("--event-every", type=int, default=8,
+                    help="bracket the dominant kernel with HIP events on every n-th timed step (an event pair costs "
+                         "about as much as a small kernel, so bracketing every step would distort the step time)")
     ap.add_argument("--kv-splits", type=int, default=0, help="force the attention key-range split count")
     return ap.parse_args()
 
@@ -218,11 +221,13 @@ def main():
         st.run(i)
     torch.cuda.synchronize()
     use_ev = not args.no_kernel_events
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)] if use_ev else None
+    every = max(1, args.event_every)
+    evs = {i: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for i in range(0, K, every)} if use_ev else {}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(K):
-        st.run(W + i, evs[i] if use_ev else None)
+        st.run(W + i, evs.get(i))
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / K
@@ -233,7 +238,7 @@ def main():
     value = committed_per_step / (ms_per_step * 1e-3)
 
     # ---- dominant kernel: the attention call of layer 0 (main kernel + split merge), events inside the timed region
-    attn_ms_ev = float(np.mean([a.elapsed_time(b) for a, b in evs])) if use_ev else None
+    attn_ms_ev = float(np.mean([a.elapsed_time(b) for a, b in evs.values()])) if use_ev else None
     attn_bytes = w.attn_bytes()
     attn_flops = w.attn_flops()
     intensity = attn_flops / attn_bytes
@@ -275,6 +280,16 @@ def main():
         ach = attn_flops / dur / 1e9 if dur else None
         roof = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": ach / MFMA_BF16_PEAK_TFLOPS if ach else None, "traffic": None}
+    # HBM traffic of the same call measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, scaled by what
+    # the counters read for the kv_append copy of known size); stored with its provenance under profiles/
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
+            tr = json.load(f)["workloads"].get(w.name)
+        if tr is not None:
+            roof["traffic"] = tr["attention_call_bytes"]
+            roof["traffic_unit"] = "bytes per launch (read + write, main kernel + split merge)"
+    except (OSError, KeyError, ValueError):
+        pass
     roof.update({"kernel": "sdllm_block_attention (attn_bf16_kernel + attn_combine_kernel)" if w.dtype == "bf16"
                  else "sdllm_block_attention (attention_f32_kernel)",
                  "launch_ms": dur, "algorithmic_bytes": attn_bytes, "algorithmic_flops": attn_flops})

@@ -128,27 +128,28 @@ __device__ __forceinline__ Partial reduce_row_slice(const UnmaskArgs& a, int row
     }
   }
 
-  // resolve this lane's argmax id: first element of vector mvec equal to m
-  int idx = 0x7fffffff;
-  if (mvec != 0x7fffffff) {
-    u32x4 r = base[mvec];
-    float x[N];
-    Vec<T>::unpack(r, x);
-#pragma unroll
-    for (int j = N - 1; j >= 0; --j) if (x[j] == m && mvec * N + j < a.V) idx = mvec * N + j;
-  }
-
-  // wave reduction, then across the waves through LDS
+  // merge (max, sum, first vector holding the max) across the wave, then across the waves through
+  // LDS.  Vectors cover disjoint, increasing id ranges, so the lowest vector index among equal
+  // maxima contains the lowest arg-max id; it is located at the end by ONE lane re-reading ONE
+  // vector (a per-lane re-read would add a scattered 64-byte fetch per lane to the stream).
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) {
-    float m2 = __shfl_xor(m, off); float s2 = __shfl_xor(s, off); int i2 = __shfl_xor(idx, off);
-    merge_partial(m, s, idx, m2, s2, i2);
+    float m2 = __shfl_xor(m, off); float s2 = __shfl_xor(s, off); int i2 = __shfl_xor(mvec, off);
+    merge_partial(m, s, mvec, m2, s2, i2);
   }
-  if ((tid & 63) == 0) red[tid >> 6] = Partial{m, s, idx};
+  if ((tid & 63) == 0) red[tid >> 6] = Partial{m, s, mvec};
   __syncthreads();
+  int idx = 0x7fffffff;
   if (tid == 0) {
 #pragma unroll
-    for (int w = 1; w < kRowThreads / 64; ++w) merge_partial(m, s, idx, red[w].m, red[w].s, red[w].idx);
+    for (int w = 1; w < kRowThreads / 64; ++w) merge_partial(m, s, mvec, red[w].m, red[w].s, red[w].idx);
+    if (mvec != 0x7fffffff) {
+      u32x4 r = base[mvec];
+      float x[N];
+      Vec<T>::unpack(r, x);
+#pragma unroll
+      for (int j = N - 1; j >= 0; --j) if (x[j] == m && mvec * N + j < a.V) idx = mvec * N + j;
+    }
   }
   return Partial{m, s, idx};
 }

@@ -185,3 +185,40 @@ def test_workspace_reuse_with_garbage(gpu_lib):
         torch.cuda.synchronize()
         ref = oracle_unmask(wl.to_f64(u["logits"]), u["tokens"], u["masked"], float(np.float32(0.9)), float(np.float32(0.3)))
         assert (tk.cpu().numpy() == ref["tokens"]).all() and (mk.cpu().numpy() == ref["masked"]).all()
+
+
+def test_attention_cfg5_layers_sampled(gpu_lib):
+    """Long-context stack shape (P = 5120, 64-row block, 64 kept of 960): inputs are drawn on the device
+    (seed + layer), the oracle sees the same bits copied back.  Layer 0: four (batch, head) pairs;
+    two more layers: one pair each."""
+    sd = gpu_lib
+    w = wl.WORKLOADS["cfg5"]
+    g = w.Hq // w.Hkv
+    worst = 0.0
+    for layer, pairs in [(0, [(0, 0), (3, 31), (1, 17), (2, 5)]), (13, [(2, 9)]), (31, [(3, 30)])]:
+        d = wl.make_attention_inputs_device(w, seed=0, layer=layer)
+        out = sd.block_attention(d["q_block"], d["q_suffix"], d["k_cache"], d["v_cache"], d["k_block"], d["v_block"],
+                                 d["k_suffix"], d["v_suffix"], d["keep_idx"], w.P)
+        torch.cuda.synchronize()
+        assert torch.isfinite(out.float()).all()
+        keep = d["keep_idx"].cpu().numpy()
+        for (b, hq) in pairs:
+            kv = hq // g
+            f = lambda t, h: t[b:b + 1, h:h + 1].double().cpu().numpy()
+            want = oracle_attention(f(d["q_block"], hq), f(d["q_suffix"], hq), f(d["k_cache"], kv), f(d["v_cache"], kv),
+                                    f(d["k_block"], kv), f(d["v_block"], kv), f(d["k_suffix"], kv), f(d["v_suffix"], kv),
+                                    keep, w.P)
+            worst = max(worst, np.abs(out[b, hq].double().cpu().numpy() - want[0, 0]).max())
+        del d, out
+    print(f"cfg5: sampled max-abs err {worst:.3e}")
+    assert worst <= TOL["bf16"]
+
+
+def test_attention_cfg2_relative_error(gpu_lib):
+    """cfg2 draws Q/K/V with std 1/sqrt(128), so outputs are ~0.01 and the absolute 2e-2 bar alone would
+    be loose: also require 2e-2 relative to the largest output magnitude."""
+    w = wl.WORKLOADS["cfg2"]
+    t = wl.make_attention_inputs(w, seed=1)
+    got = run_gpu(gpu_lib, t, w.P)
+    want = oracle(t, w.P)
+    assert np.abs(got - want).max() <= 2e-2 * np.abs(want).max()
