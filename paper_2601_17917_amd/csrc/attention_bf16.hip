@@ -6,8 +6,8 @@
 //             g*Nq query rows are treated as one list of "virtual rows" and tiled together.
 //   workgroup = (group, query tile of 64*RB rows, key-range split); 4 waves, wave w owns the
 //             16*RB rows  [w*16*RB, (w+1)*16*RB) of the tile for all keys of the split.
-//   K/V tiles of 64 keys stream through an LDS ring of NST stages.  They are moved global -> LDS
-//             directly (global_load_lds_dwordx4: no register staging), NST-1 tiles ahead of the
+//   K/V tiles of 64 keys stream through a two-stage LDS ring.  They are moved global -> LDS
+//             directly (global_load_lds_dwordx4: no register staging), one tile ahead of the
 //             one being computed, one workgroup barrier per tile.  Rows come from three places
 //             (cache, block, suffix[keep_idx]) and are addressed per row, so the gather costs
 //             nothing extra: a row is 16 lanes x 16 B, fully coalesced.
@@ -81,24 +81,208 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
-template <int D, int RB, int NST>
+// Compile-time shape constants shared by the helpers below
+template <int D> struct Shape {
+  static constexpr int CPR = D / 8;                // 16-byte chunks per row
+  static constexpr int RPI = 64 / CPR;             // rows covered by one wave-wide transfer
+  static constexpr int IPT = 16 / RPI;             // transfers per wave per tile per tensor (a wave loads 16 rows)
+  static constexpr int R256 = 16 / CPR;            // rows per 256 bytes of LDS
+  static constexpr int NS = D / 32;                // 32-wide d slices (QK^T contraction steps)
+  static constexpr int NDB = D / 16;               // 16-wide d blocks of the output
+  static constexpr int ROWB = D * 2;               // bytes per row
+  static constexpr int TILEB = kKeyTile * ROWB;    // bytes per tile per tensor
+  // LDS: [K stage 0][K stage 1][V stage 0][V stage 1]; a stage offset (TILEB) plus any row offset
+  // of a tile fits the 16-bit immediate of a DS instruction, so a lane needs one base register
+  // per d slice / d block and no address arithmetic inside the loop.
+  static constexpr int VBASE = 2 * TILEB;
+  static constexpr int LDS_BYTES = 4 * TILEB;
+};
+
+// Per-lane constants of the K/V stream
+template <int D> struct Lane {
+  unsigned kgo[Shape<D>::IPT], vgo[Shape<D>::IPT]; // byte offset of the lane's (swizzled) source chunk within a tile
+  unsigned kro[Shape<D>::NS], vro[Shape<D>::NDB];  // LDS read bases (bytes), before compile-time offsets
+  unsigned lds_base; int wave, lane, G;
+};
+
+// Puts key tile `tile` in flight into ring stage `stage`: 2 * IPT transfers per wave.
+template <int D>
+__device__ __forceinline__ void issue_tile(const AttnArgs& a, const Lane<D>& L, const uint16_t* kc, const uint16_t* vc,
+                                           const uint16_t* kb, const uint16_t* vb, const uint16_t* ks, const uint16_t* vs,
+                                           int tile, int stage) {
+  using S = Shape<D>;
+  typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+  const unsigned sk = L.lds_base + stage * S::TILEB + 16 * L.wave * S::ROWB;
+  const unsigned sv = sk + S::VBASE;
+  if ((tile + 1) * kKeyTile <= a.P) {              // uniform: whole tile inside the prefix cache
+    const unsigned char* kt = reinterpret_cast<const unsigned char*>(kc) + (long long)tile * S::TILEB;
+    const unsigned char* vt = reinterpret_cast<const unsigned char*>(vc) + (long long)tile * S::TILEB;
+#pragma unroll
+    for (int j = 0; j < S::IPT; ++j) dma16_sbase(sk + j * S::RPI * S::ROWB, kt, L.kgo[j]);
+#pragma unroll
+    for (int j = 0; j < S::IPT; ++j) dma16_sbase(sv + j * S::RPI * S::ROWB, vt, L.vgo[j]);
+  } else {
+    // block / gathered suffix rows, ragged tail: no divergent branch; keep_idx is read through the
+    // constant address space with uniform indices (scalar loads: they do not touch the
+    // vector-memory counter that tracks the transfers in flight)
+    const const_i32_ptr keep_c = (const_i32_ptr)(uintptr_t)a.keep_idx;
+    const int r0 = tile * kKeyTile + 16 * L.wave;  // uniform
+    const unsigned char* kpp[S::IPT]; const unsigned char* vpp[S::IPT];
+#pragma unroll
+    for (int j = 0; j < S::IPT; ++j) {
+      const int rl = S::RPI * j + L.lane / S::CPR;
+      const int r = min(r0 + rl, a.Nkv - 1);
+      int kidx = 0;
+      if (a.n_keep > 0) {
+#pragma unroll
+        for (int q2 = 0; q2 < S::RPI; ++q2) {
+          const int si = min(max(r0 + S::RPI * j + q2 - a.P - a.K, 0), a.n_keep - 1);
+          const int v = keep_c[si];
+          kidx = (L.lane / S::CPR == q2) ? v : kidx;
+        }
+      }
+      const bool in_c = r < a.P, in_b = r < a.P + a.K;
+      const uint16_t* kp = in_c ? kc : (in_b ? kb : ks);
+      const uint16_t* vp = in_c ? vc : (in_b ? vb : vs);
+      const long long off = (long long)(in_c ? r : (in_b ? r - a.P : kidx)) * D;
+      kpp[j] = reinterpret_cast<const unsigned char*>(kp + off) + (L.kgo[j] - (16 * L.wave + rl) * S::ROWB);
+      vpp[j] = reinterpret_cast<const unsigned char*>(vp + off) + (L.vgo[j] - (16 * L.wave + rl) * S::ROWB);
+    }
+#pragma unroll
+    for (int j = 0; j < S::IPT; ++j) dma16_vaddr(sk + j * S::RPI * S::ROWB, kpp[j]);
+#pragma unroll
+    for (int j = 0; j < S::IPT; ++j) dma16_vaddr(sv + j * S::RPI * S::ROWB, vpp[j]);
+  }
+}
+
+typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+
+// V^T operand (16 d x 32 keys) of d block `db`, key half `u`, through two LDS transpose reads
+template <int D, int STAGE>
+__device__ __forceinline__ s16x8 read_vt(const unsigned char* lds, const Lane<D>& L, int db, int u) {
+  using S = Shape<D>;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (lds_s16x4_ptr)(lds + L.vro[db] + STAGE * S::TILEB + (32 * u) * S::ROWB));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (lds_s16x4_ptr)(lds + L.vro[db] + STAGE * S::TILEB + (32 * u + 16) * S::ROWB));
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+// One key tile (ring stage STAGE, a compile-time constant so that every LDS address is base + immediate)
+template <int D, int RB, int STAGE>
+__device__ __forceinline__ void compute_tile(const AttnArgs& a, const Lane<D>& L, const unsigned char* lds, int t,
+                                             const bf16x8 (&qreg)[RB][Shape<D>::NS], f32x4 (&o)[RB][Shape<D>::NDB],
+                                             float (&m)[RB], float (&lsum)[RB]) {
+  using S = Shape<D>;
+  constexpr int NS = S::NS, NDB = S::NDB;
+  // ---- S^T = K Q^T
+  f32x4 sacc[RB][4];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int kb4 = 0; kb4 < 4; ++kb4) sacc[rb][kb4] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int kb4 = 0; kb4 < 4; ++kb4) {
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const bf16x8 kop = *reinterpret_cast<const bf16x8*>(lds + L.kro[s] + STAGE * S::TILEB + kb4 * 16 * S::ROWB);
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+        sacc[rb][kb4] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, qreg[rb][s], sacc[rb][kb4], 0, 0, 0);
+    }
+  }
+
+  // ---- V^T operands of the first key half go in flight now: they do not depend on the softmax, so
+  // their LDS latency hides behind it (with 16 query rows per wave there is room for both halves)
+  constexpr int NPRE = (RB == 1) ? 2 : 1;
+  s16x8 vpre[NPRE][NDB];
+#pragma unroll
+  for (int u = 0; u < NPRE; ++u)
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) vpre[u][db] = read_vt<D, STAGE>(lds, L, db, u);
+
+  // ---- online softmax (log2 domain: p = exp2(s * scale_log2 - m)); keys past Nkv only exist in the last tile
+  const int key0 = t * kKeyTile;
+  if (key0 + kKeyTile > a.Nkv) {                   // uniform branch
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int kb4 = 0; kb4 < 4; ++kb4)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (key0 + kb4 * 16 + 4 * L.G + i >= a.Nkv) sacc[rb][kb4][i] = kNegBigA;
+  }
+  s16x8 pk[RB][2];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    float mx = fmaxf(fmaxf(sacc[rb][0][0], sacc[rb][0][1]), sacc[rb][0][2]);
+    mx = fmaxf(fmaxf(mx, sacc[rb][0][3]), sacc[rb][1][0]);
+    mx = fmaxf(fmaxf(mx, sacc[rb][1][1]), sacc[rb][1][2]);
+    mx = fmaxf(fmaxf(mx, sacc[rb][1][3]), sacc[rb][2][0]);
+    mx = fmaxf(fmaxf(mx, sacc[rb][2][1]), sacc[rb][2][2]);
+    mx = fmaxf(fmaxf(mx, sacc[rb][2][3]), sacc[rb][3][0]);
+    mx = fmaxf(fmaxf(mx, sacc[rb][3][1]), sacc[rb][3][2]);
+    mx = fmaxf(mx, sacc[rb][3][3]);
+    // across the four 16-lane groups that hold the other keys of the same query row: VALU lane swaps
+    {
+      const auto s16 = __builtin_amdgcn_permlane16_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+      mx = fmaxf(__uint_as_float(s16[0]), __uint_as_float(s16[1]));
+      const auto s32 = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+      mx = fmaxf(__uint_as_float(s32[0]), __uint_as_float(s32[1]));
+    }
+    const float m_new = fmaxf(m[rb], mx * a.scale_log2);       // scale_log2 > 0
+    if (__builtin_amdgcn_ballot_w64(m_new != m[rb]) != 0) {    // uniform: rescale only when some row's maximum moved
+      const float corr = exp2_fast(m[rb] - m_new);
+      lsum[rb] *= corr;
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) o[rb][db] *= corr;
+      m[rb] = m_new;
+    }
+    float ps = 0.f;
+#pragma unroll
+    for (int kb4 = 0; kb4 < 4; ++kb4)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float p = exp2_fast(fmaf(sacc[rb][kb4][i], a.scale_log2, -m_new));
+        sacc[rb][kb4][i] = p;
+        ps += p;
+      }
+    lsum[rb] += ps;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      union { uint32_t w[4]; s16x8 v; } cv;
+      cv.w[0] = pack_bf16x2(sacc[rb][2 * u][0], sacc[rb][2 * u][1]);
+      cv.w[1] = pack_bf16x2(sacc[rb][2 * u][2], sacc[rb][2 * u][3]);
+      cv.w[2] = pack_bf16x2(sacc[rb][2 * u + 1][0], sacc[rb][2 * u + 1][1]);
+      cv.w[3] = pack_bf16x2(sacc[rb][2 * u + 1][2], sacc[rb][2 * u + 1][3]);
+      pk[rb][u] = cv.v;
+    }
+  }
+
+  // ---- O^T += V^T P^T
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) {
+      const s16x8 vop = (u < NPRE) ? vpre[u < NPRE ? u : 0][db] : read_vt<D, STAGE>(lds, L, db, u);
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+        o[rb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vop),
+                                                             __builtin_bit_cast(bf16x8, pk[rb][u]),
+                                                             o[rb][db], 0, 0, 0);
+    }
+  }
+}
+
+template <int D, int RB>
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
-  constexpr int CPR = D / 8;                       // 16-byte chunks per row
-  constexpr int RPI = 64 / CPR;                    // rows covered by one wave-wide transfer
-  constexpr int IPT = 16 / RPI;                    // transfers per wave per tile per tensor (a wave loads 16 rows)
-  constexpr int LPT = 2 * IPT;                     // ... for K and V together
-  constexpr int R256 = 16 / CPR;                   // rows per 256 bytes of LDS
-  constexpr int NS = D / 32;                       // 32-wide d slices (QK^T contraction steps)
-  constexpr int NDB = D / 16;                      // 16-wide d blocks of the output
-  constexpr int ROWB = D * 2;                      // bytes per row
-  constexpr int TILEB = kKeyTile * ROWB;           // bytes per tile per tensor
-  constexpr int STAGEB = 2 * TILEB;                // one stage: K tile, then V tile
+  using S = Shape<D>;
+  constexpr int CPR = S::CPR, RPI = S::RPI, IPT = S::IPT, R256 = S::R256, NS = S::NS, NDB = S::NDB, ROWB = S::ROWB;
   // LDS rows are unpadded (a transfer writes 1 KiB contiguous); bank conflicts are avoided by
   // storing chunk c of row r at position c ^ f(r):  f_K(r) = (r / R256) % CPR makes the 16 rows of
   // one b128 read phase hit 16 different positions, f_V(r) = 2 * ((r / R256) % (CPR/2)) does the
   // same for the 8 rows x 32 bytes of one transpose-read phase.
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
-  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)lds;
 
   // ---- which piece of work: workgroups that share K/V (query tiles of one unit) sit on one XCD
   const int xcd = blockIdx.x % kNumXCDs, slot = blockIdx.x / kNumXCDs;
@@ -114,78 +298,34 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l16 = lane & 15, G = lane >> 4;
 
+  Lane<D> L;
+  L.lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)lds;
+  L.wave = wave; L.lane = lane; L.G = G;
   const long long bh = (long long)b * a.Hkv + kvh;
-  const uint16_t* kc = a.k_cache + bh * a.cap * D;
-  const uint16_t* vc = a.v_cache + bh * a.cap * D;
-  const uint16_t* kb = a.k_block + bh * a.K * D;
-  const uint16_t* vb = a.v_block + bh * a.K * D;
-  const uint16_t* ks = a.k_suffix + bh * a.S * D;
-  const uint16_t* vs = a.v_suffix + bh * a.S * D;
-
-  // keep_idx read through the constant address space: uniform indices become scalar loads, which
-  // do not touch the vector-memory counter that tracks the transfers in flight
-  typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
-  const const_i32_ptr keep_c = (const_i32_ptr)(uintptr_t)a.keep_idx;
-
-  // ---- transfer map of this lane: row within the tile and (swizzled) source chunk per transfer
-  unsigned kgo[IPT], vgo[IPT];                     // byte offset of the lane's source chunk within a tile
+  // base pointers of this (batch, KV head); kept as separate values (in a struct the compiler turns
+  // the three-way source select of the gather path into a table lookup in scratch memory)
+  const uint16_t* kc = a.k_cache + bh * a.cap * D;  const uint16_t* vc = a.v_cache + bh * a.cap * D;
+  const uint16_t* kb = a.k_block + bh * a.K * D;    const uint16_t* vb = a.v_block + bh * a.K * D;
+  const uint16_t* ks = a.k_suffix + bh * a.S * D;   const uint16_t* vs = a.v_suffix + bh * a.S * D;
 #pragma unroll
   for (int j = 0; j < IPT; ++j) {
     const int r = 16 * wave + RPI * j + lane / CPR, q = lane % CPR;
-    kgo[j] = r * ROWB + ((q ^ ((r / R256) % CPR)) << 4);
-    vgo[j] = r * ROWB + ((q ^ (2 * ((r / R256) % (CPR / 2)))) << 4);
+    L.kgo[j] = r * ROWB + ((q ^ ((r / R256) % CPR)) << 4);
+    L.vgo[j] = r * ROWB + ((q ^ (2 * ((r / R256) % (CPR / 2)))) << 4);
   }
-#define SDLLM_ISSUE_TILE(tile, stage)                                                             \
-  {                                                                                               \
-    const unsigned sb = lds_base + (stage) * STAGEB + 16 * wave * ROWB;                           \
-    if (((tile) + 1) * kKeyTile <= a.P) {        /* uniform: whole tile inside the prefix cache */ \
-      const unsigned char* kt = reinterpret_cast<const unsigned char*>(kc) + (long long)(tile) * TILEB; \
-      const unsigned char* vt = reinterpret_cast<const unsigned char*>(vc) + (long long)(tile) * TILEB; \
-      _Pragma("unroll") for (int j = 0; j < IPT; ++j) dma16_sbase(sb + j * RPI * ROWB, kt, kgo[j]); \
-      _Pragma("unroll") for (int j = 0; j < IPT; ++j) dma16_sbase(sb + TILEB + j * RPI * ROWB, vt, vgo[j]); \
-    } else {   /* block / gathered suffix rows, ragged tail: no divergent branch, keep_idx through scalar loads */ \
-      const int r0 = (tile) * kKeyTile + 16 * wave;                       /* uniform */           \
-      const unsigned char* kpp[IPT]; const unsigned char* vpp[IPT];                               \
-      _Pragma("unroll") for (int j = 0; j < IPT; ++j) {                                           \
-        const int rl = RPI * j + lane / CPR;                                                      \
-        const int r = min(r0 + rl, a.Nkv - 1);                                                    \
-        int kidx = 0;                                                                             \
-        if (a.n_keep > 0) {                                                                       \
-          _Pragma("unroll") for (int q2 = 0; q2 < RPI; ++q2) {                                    \
-            const int si = min(max(r0 + RPI * j + q2 - a.P - a.K, 0), a.n_keep - 1);              \
-            const int v = keep_c[si];                                     /* uniform address */   \
-            kidx = (lane / CPR == q2) ? v : kidx;                                                 \
-          }                                                                                       \
-        }                                                                                         \
-        const bool in_c = r < a.P, in_b = r < a.P + a.K;                                          \
-        const uint16_t* kp = in_c ? kc : (in_b ? kb : ks);                                        \
-        const uint16_t* vp = in_c ? vc : (in_b ? vb : vs);                                        \
-        const long long off = (long long)(in_c ? r : (in_b ? r - a.P : kidx)) * D;                \
-        kpp[j] = reinterpret_cast<const unsigned char*>(kp + off) + (kgo[j] - (16 * wave + rl) * ROWB); \
-        vpp[j] = reinterpret_cast<const unsigned char*>(vp + off) + (vgo[j] - (16 * wave + rl) * ROWB); \
-      }                                                                                           \
-      _Pragma("unroll") for (int j = 0; j < IPT; ++j) dma16_vaddr(sb + j * RPI * ROWB, kpp[j]);   \
-      _Pragma("unroll") for (int j = 0; j < IPT; ++j) dma16_vaddr(sb + TILEB + j * RPI * ROWB, vpp[j]); \
-    }                                                                                             \
-  }
-
-  // ---- prologue: the first NST-1 tiles go in flight
-#pragma unroll
-  for (int i = 0; i < NST - 1; ++i)
-    if (t0 + i < t1) SDLLM_ISSUE_TILE(t0 + i, i)
-
-  // ---- LDS read offsets of this lane (bytes within a stage, before the compile-time row offsets)
-  unsigned kro[NS], vro[NDB];
   {
     const int fk = (D == 128) ? l16 : (l16 >> 1);
 #pragma unroll
-    for (int s2 = 0; s2 < NS; ++s2) kro[s2] = l16 * ROWB + (((4 * s2 + G) ^ fk) << 4);
+    for (int s2 = 0; s2 < NS; ++s2) L.kro[s2] = l16 * ROWB + (((4 * s2 + G) ^ fk) << 4);
     const int e4 = l16 >> 2, c4 = l16 & 3;
     const int fv = (D == 128) ? 2 * (4 * (G & 1) + e4) : 2 * (2 * (G & 1) + (e4 >> 1));
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
-      vro[db] = TILEB + (4 * G + e4) * ROWB + (((2 * db + (c4 >> 1)) ^ fv) << 4) + ((c4 & 1) << 3);
+      L.vro[db] = S::VBASE + (4 * G + e4) * ROWB + (((2 * db + (c4 >> 1)) ^ fv) << 4) + ((c4 & 1) << 3);
   }
+
+  // ---- the first tile goes in flight, then the query rows
+  issue_tile<D>(a, L, kc, vc, kb, vb, ks, vs, t0, 0);
 
   // ---- query rows of this wave, as MFMA B operands (lane: row l16, d = 32*s + 8*G .. +7)
   const int row_base = qt * (64 * RB) + wave * (16 * RB);
@@ -211,113 +351,21 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     for (int db = 0; db < NDB; ++db) o[rb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  // the query rows (ordinary loads) are complete before the loop, so that the compiler places no
-  // vector-memory wait of its own inside it
-  wait_vmcnt<0>();
-
-  for (int t = t0; t < t1; ++t) {
-    const int rel = t - t0;
-    const int stage = rel % NST;
-    // tile t has landed once at most the transfers of the newer tiles in flight are outstanding
-    {
-      const int newer = min(NST - 2, t1 - 1 - t);
-      if (NST >= 4 && newer >= 2) wait_vmcnt<(NST >= 4 ? 2 : 0) * LPT>();
-      else if (NST >= 3 && newer == 1) wait_vmcnt<(NST >= 3 ? 1 : 0) * LPT>();
-      else wait_vmcnt<0>();
-    }
-    __builtin_amdgcn_s_barrier();                  // every wave's part of tile t is in LDS; tile t-1 is consumed
-    if (t + NST - 1 < t1) SDLLM_ISSUE_TILE(t + NST - 1, (rel + NST - 1) % NST)
-    const unsigned char* st = lds + stage * STAGEB;
-
-    // ---- S^T = K Q^T
-    f32x4 sacc[RB][4];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-      for (int kb4 = 0; kb4 < 4; ++kb4) sacc[rb][kb4] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int kb4 = 0; kb4 < 4; ++kb4) {
-#pragma unroll
-      for (int s = 0; s < NS; ++s) {
-        const bf16x8 kop = *reinterpret_cast<const bf16x8*>(st + kro[s] + kb4 * 16 * ROWB);
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-          sacc[rb][kb4] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, qreg[rb][s], sacc[rb][kb4], 0, 0, 0);
-      }
-    }
-
-    // ---- online softmax (log2 domain: p = exp2(s * scale_log2 - m)); keys past Nkv only exist in the last tile
-    const int key0 = t * kKeyTile;
-    if (key0 + kKeyTile > a.Nkv) {                 // uniform branch
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int kb4 = 0; kb4 < 4; ++kb4)
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            if (key0 + kb4 * 16 + 4 * G + i >= a.Nkv) sacc[rb][kb4][i] = kNegBigA;
-    }
-    s16x8 pk[RB][2];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      float mx = fmaxf(fmaxf(sacc[rb][0][0], sacc[rb][0][1]), sacc[rb][0][2]);
-      mx = fmaxf(fmaxf(mx, sacc[rb][0][3]), sacc[rb][1][0]);
-      mx = fmaxf(fmaxf(mx, sacc[rb][1][1]), sacc[rb][1][2]);
-      mx = fmaxf(fmaxf(mx, sacc[rb][1][3]), sacc[rb][2][0]);
-      mx = fmaxf(fmaxf(mx, sacc[rb][2][1]), sacc[rb][2][2]);
-      mx = fmaxf(fmaxf(mx, sacc[rb][2][3]), sacc[rb][3][0]);
-      mx = fmaxf(fmaxf(mx, sacc[rb][3][1]), sacc[rb][3][2]);
-      mx = fmaxf(mx, sacc[rb][3][3]);
-      mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m[rb], mx * a.scale_log2);     // scale_log2 > 0
-      if (__builtin_amdgcn_ballot_w64(m_new != m[rb]) != 0) {  // uniform: rescale only when some row's maximum moved
-        const float corr = exp2_fast(m[rb] - m_new);
-        lsum[rb] *= corr;
-#pragma unroll
-        for (int db = 0; db < NDB; ++db) o[rb][db] *= corr;
-        m[rb] = m_new;
-      }
-      float ps = 0.f;
-#pragma unroll
-      for (int kb4 = 0; kb4 < 4; ++kb4)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float p = exp2_fast(fmaf(sacc[rb][kb4][i], a.scale_log2, -m_new));
-          sacc[rb][kb4][i] = p;
-          ps += p;
-        }
-      lsum[rb] += ps;
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        union { uint32_t w[4]; s16x8 v; } cv;
-        cv.w[0] = pack_bf16x2(sacc[rb][2 * u][0], sacc[rb][2 * u][1]);
-        cv.w[1] = pack_bf16x2(sacc[rb][2 * u][2], sacc[rb][2 * u][3]);
-        cv.w[2] = pack_bf16x2(sacc[rb][2 * u + 1][0], sacc[rb][2 * u + 1][1]);
-        cv.w[3] = pack_bf16x2(sacc[rb][2 * u + 1][2], sacc[rb][2 * u + 1][3]);
-        pk[rb][u] = cv.v;
-      }
-    }
-
-    // ---- O^T += V^T P^T ; V^T operand through the LDS transpose read
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-#pragma unroll
-      for (int db = 0; db < NDB; ++db) {
-        typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_s16x4_ptr)(st + vro[db] + (32 * u) * ROWB));
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_s16x4_ptr)(st + vro[db] + (32 * u + 16) * ROWB));
-        const s16x8 vop = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-          o[rb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vop),
-                                                               __builtin_bit_cast(bf16x8, pk[rb][u]),
-                                                               o[rb][db], 0, 0, 0);
-      }
-    }
-
+  // Two tiles per trip so that the ring stage is a compile-time constant.  Per tile: wait for its
+  // transfers (all of this wave's outstanding ones: only that tile is in flight), barrier (every
+  // wave's part has landed and the previous tile is consumed), put the next tile in flight into the
+  // stage just freed, compute.  The query-row loads are complete after the first wait, so the
+  // compiler places no vector-memory wait of its own inside the loop.
+  for (int t = t0; t < t1; t += 2) {
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    if (t + 1 < t1) issue_tile<D>(a, L, kc, vc, kb, vb, ks, vs, t + 1, 1);
+    compute_tile<D, RB, 0>(a, L, lds, t, qreg, o, m, lsum);
+    if (t + 1 >= t1) break;
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    if (t + 2 < t1) issue_tile<D>(a, L, kc, vc, kb, vb, ks, vs, t + 2, 0);
+    compute_tile<D, RB, 1>(a, L, lds, t + 1, qreg, o, m, lsum);
   }
 
   // ---- epilogue
@@ -348,8 +396,6 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     }
   }
 }
-
-#undef SDLLM_ISSUE_TILE
 
 // merge the key-range splits of every output row: fixed (index) order, fp32.  The loads of up to
 // four splits are issued together so that a row costs about one memory round trip.
@@ -397,18 +443,16 @@ AttnPlan plan_attention_bf16(const sdllm_attn_params& p) {
   const int g = p.Hq / p.Hkv;
   const long long Rtot = (long long)g * (p.K + p.n_keep);
   const long long Nkv = (long long)p.prefix_len + p.K + p.n_keep;
-  // tuning knobs for sweeps (read once): SDLLM_ATTN_RB = 1|2, SDLLM_ATTN_STAGES = 2|3|4
+  // tuning knob for sweeps (read once): SDLLM_ATTN_RB = 1|2
   static const int env_rb = [] { const char* e = getenv("SDLLM_ATTN_RB"); return e ? atoi(e) : 0; }();
-  static const int env_st = [] { const char* e = getenv("SDLLM_ATTN_STAGES"); return e ? atoi(e) : 0; }();
   // 32 query rows per wave (128 per workgroup) pay off only when many query rows share one K/V
   // stream (dense suffix); measured: 1024 rows -> 1.4x faster, 448 rows (GQA 7:1) -> 8 % slower
   pl.rb = Rtot >= 512 ? 2 : 1;
   if (env_rb == 1 || env_rb == 2) pl.rb = env_rb;
-  // Two ring stages and two workgroups per CU.  Deeper rings (3, 4 stages: one workgroup per CU)
-  // were measured and are slower at every shape: with one wave per SIMD the per-tile latencies of
-  // the MFMA / softmax / LDS chain are exposed, and those, not the K/V stream, bound the loop.
+  // Two ring stages, two workgroups per CU.  Deeper rings (3, 4 stages: one workgroup per CU) were
+  // measured and are slower at every shape: with one wave per SIMD the per-tile latencies of the
+  // MFMA / softmax / LDS chain are exposed, and those, not the K/V stream, bound the loop.
   pl.stages = 2;
-  if (env_st >= 2 && env_st <= 4) pl.stages = env_st;
   const int rows_wg = 64 * pl.rb;
   pl.q_tiles = (int)((Rtot + rows_wg - 1) / rows_wg);
   pl.key_tiles = (int)((Nkv + kKeyTile - 1) / kKeyTile);
@@ -439,30 +483,23 @@ size_t attention_bf16_workspace_bytes(const sdllm_attn_params& p, const AttnPlan
   return rows * pl.kv_splits * (size_t)(p.D + 2) * sizeof(float);
 }
 
-template <int D, int RB, int NST>
+template <int D, int RB>
 static hipError_t launch_main(const AttnArgs& a, const AttnPlan& pl, hipStream_t stream) {
-  constexpr size_t lds_bytes = (size_t)NST * 2 * kKeyTile * D * sizeof(uint16_t);
+  constexpr size_t lds_bytes = Shape<D>::LDS_BYTES;
   static bool attr_set = false;                     // benign race: the call is idempotent
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<D, RB, NST>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<D, RB>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((attn_bf16_kernel<D, RB, NST>), dim3(pl.workgroups), dim3(256), lds_bytes, stream, a);
+  hipLaunchKernelGGL((attn_bf16_kernel<D, RB>), dim3(pl.workgroups), dim3(256), lds_bytes, stream, a);
   return hipGetLastError();
 }
 
 template <int D>
 static hipError_t launch_d(const AttnArgs& a, const AttnPlan& pl, hipStream_t stream) {
-  if (pl.rb == 2) {
-    if (pl.stages == 2) return launch_main<D, 2, 2>(a, pl, stream);
-    if (pl.stages == 3) return launch_main<D, 2, 3>(a, pl, stream);
-    return launch_main<D, 2, 4>(a, pl, stream);
-  }
-  if (pl.stages == 2) return launch_main<D, 1, 2>(a, pl, stream);
-  if (pl.stages == 3) return launch_main<D, 1, 3>(a, pl, stream);
-  return launch_main<D, 1, 4>(a, pl, stream);
+  return pl.rb == 2 ? launch_main<D, 2>(a, pl, stream) : launch_main<D, 1>(a, pl, stream);
 }
 
 hipError_t launch_attention_bf16(const sdllm_attn_params& p, const AttnPlan& pl,
