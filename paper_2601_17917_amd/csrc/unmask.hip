@@ -175,11 +175,11 @@ __device__ __forceinline__ void commit_sequence(const UnmaskArgs& a, int b, floa
     const bool in = i < K;
     const long long pos = (long long)b * K + (in ? i : 0);
     const bool is_masked = in && a.masked[pos] != 0;
+    // the triple is loaded without waiting for the mask byte (its slot is valid memory either way;
+    // for an unmasked position it holds garbage that is discarded): one memory round trip, not two
+    const Partial pr = a.partials[pos * a.nsplit + min(k, a.nsplit - 1)];
     float m = kNegBig, s = 0.f; int idx = 0x7fffffff;
-    if (is_masked && k < a.nsplit) {
-      const Partial p = a.partials[pos * a.nsplit + k];
-      m = p.m; s = p.s; idx = p.idx;
-    }
+    if (is_masked && k < a.nsplit) { m = pr.m; s = pr.s; idx = pr.idx; }
     for (int off = P2 >> 1; off >= 1; off >>= 1) {
       float m2 = __shfl_xor(m, off); float s2 = __shfl_xor(s, off); int i2 = __shfl_xor(idx, off);
       merge_partial(m, s, idx, m2, s2, i2);
