@@ -175,6 +175,7 @@ __device__ __forceinline__ void compute_tile(const AttnArgs& a, const Lane<D>& L
                                              float (&m)[RB], float (&lsum)[RB]) {
   using S = Shape<D>;
   constexpr int NS = S::NS, NDB = S::NDB;
+  constexpr bool kMfmaRowSum = (RB == 1);
   // ---- S^T = K Q^T
   f32x4 sacc[RB][4];
 #pragma unroll
@@ -192,10 +193,10 @@ __device__ __forceinline__ void compute_tile(const AttnArgs& a, const Lane<D>& L
     }
   }
 
-  // ---- V^T operands of the first key half go in flight now: they do not depend on the softmax, so
-  // their LDS latency hides behind it (with 16 query rows per wave there is room for both halves)
-  constexpr int NPRE = (RB == 1) ? 2 : 1;
-  s16x8 vpre[NPRE][NDB];
+  // ---- with 16 query rows per wave the V^T operands go in flight now: they do not depend on the
+  // softmax, so their LDS latency hides behind it
+  constexpr int NPRE = (RB == 1) ? 2 : 0;           // 32 rows per wave: no registers to spare for it
+  s16x8 vpre[NPRE > 0 ? NPRE : 1][NDB];
 #pragma unroll
   for (int u = 0; u < NPRE; ++u)
 #pragma unroll
@@ -230,8 +231,13 @@ __device__ __forceinline__ void compute_tile(const AttnArgs& a, const Lane<D>& L
       const auto s32 = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
       mx = fmaxf(__uint_as_float(s32[0]), __uint_as_float(s32[1]));
     }
-    const float m_new = fmaxf(m[rb], mx * a.scale_log2);       // scale_log2 > 0
-    if (__builtin_amdgcn_ballot_w64(m_new != m[rb]) != 0) {    // uniform: rescale only when some row's maximum moved
+    // Lazy reference: the row's reference exponent only moves when the new maximum exceeds it by
+    // more than 8 (log2 units), so probabilities stay below 2^8 (exact in fp32 sums, same relative
+    // precision in bf16) and the accumulator rescale below runs in a handful of tiles instead of
+    // most of them.  The final O / l is unchanged: both carry the same reference.
+    const float cand = mx * a.scale_log2;                      // scale_log2 > 0
+    const float m_new = (cand > m[rb] + 8.0f) ? cand : m[rb];
+    if (__builtin_amdgcn_ballot_w64(m_new != m[rb]) != 0) {    // uniform branch
       const float corr = exp2_fast(m[rb] - m_new);
       lsum[rb] *= corr;
 #pragma unroll
@@ -245,9 +251,9 @@ __device__ __forceinline__ void compute_tile(const AttnArgs& a, const Lane<D>& L
       for (int i = 0; i < 4; ++i) {
         const float p = exp2_fast(fmaf(sacc[rb][kb4][i], a.scale_log2, -m_new));
         sacc[rb][kb4][i] = p;
-        ps += p;
+        if (!kMfmaRowSum) ps += p;
       }
-    lsum[rb] += ps;
+    if (!kMfmaRowSum) lsum[rb] += ps;              // per-lane partial sum, reduced across lanes in the epilogue
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       union { uint32_t w[4]; s16x8 v; } cv;
@@ -256,6 +262,23 @@ __device__ __forceinline__ void compute_tile(const AttnArgs& a, const Lane<D>& L
       cv.w[2] = pack_bf16x2(sacc[rb][2 * u + 1][0], sacc[rb][2 * u + 1][1]);
       cv.w[3] = pack_bf16x2(sacc[rb][2 * u + 1][2], sacc[rb][2 * u + 1][3]);
       pk[rb][u] = cv.v;
+    }
+  }
+
+  // ---- row sums on the matrix pipe (16 rows per wave; with 32 there are no registers to spare):
+  // ones^T P^T adds the (bf16-rounded) probabilities of all 32 keys of a half tile for every query
+  // row; each lane receives its row's complete sum
+  if (kMfmaRowSum) {
+    union { uint32_t w[4]; s16x8 v; } ones;
+    ones.w[0] = ones.w[1] = ones.w[2] = ones.w[3] = 0x3f803f80u;   // bf16 1.0 pairs
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      f32x4 ls = {lsum[rb], 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+        ls = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ones.v),
+                                                     __builtin_bit_cast(bf16x8, pk[rb][u]), ls, 0, 0, 0);
+      lsum[rb] = ls[0];
     }
   }
 
@@ -372,8 +395,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
     float l = lsum[rb];
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
+    if (RB != 1) {                                 // per-lane partial sums (see compute_tile): reduce across the row's lanes
+      l += __shfl_xor(l, 16);
+      l += __shfl_xor(l, 32);
+    }
     const int R = row_base + rb * 16 + l16;
     if (R >= a.Rtot) continue;
     if (a.nsplit == 1) {
