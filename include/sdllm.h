@@ -175,6 +175,20 @@ int sdllm_kv_append(const sdllm_append_params* p,
                     void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * Attenuation-guided suffix rule (paper Eq. 7 and Fig. 4): of the S mask positions after the
+ * active block keep the w nearest blocks (a sliding window of w_blocks * K positions) and, when
+ * keep_trailing != 0, the trailing position S-1, which carries the final length through its
+ * position id.  HOST helper (integer only, no HIP call): writes the kept positions, relative to
+ * the start of the suffix and strictly increasing, to the HOST array out_idx (capacity `cap`
+ * entries) and their number to *n_keep.  n_keep = min(w_blocks*K, S) (+1 if the trailing position
+ * is kept and lies outside the window).  The list is what sdllm_block_attention takes as
+ * keep_idx after a copy to the device.
+ * Errors: INVALID_ARG (NULL pointer, negative S / w_blocks, K < 1, cap too small).
+ * ------------------------------------------------------------------------------------- */
+int sdllm_suffix_keep_indices(int32_t S, int32_t K, int32_t w_blocks, int32_t keep_trailing,
+                              int32_t* out_idx, int32_t cap, int32_t* n_keep);
+
+/* ---------------------------------------------------------------------------------------
  * Diagnostics.  sdllm_plan_attention reports the launch plan the library would use (host
  * only, no HIP call): number of key-range splits, query rows per workgroup, workgroups.
  * Returns SDLLM_OK or the validation error.

@@ -15,3 +15,4 @@ closed-form values derived by hand from the paper's equations.
 from .attention import block_attention, compose_rows  # noqa: F401
 from .unmask import confidence_unmask, dynamic_threshold, row_confidence  # noqa: F401
 from .kv_append import kv_append  # noqa: F401
+from .suffix import suffix_keep_indices  # noqa: F401

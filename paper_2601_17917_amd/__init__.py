@@ -19,7 +19,7 @@ FP32, BF16 = 0, 1
 EXPORTED_SYMBOLS = (
     "sdllm_block_attention", "sdllm_attention_workspace_bytes", "sdllm_plan_attention",
     "sdllm_confidence_unmask", "sdllm_unmask_workspace_bytes",
-    "sdllm_kv_append",
+    "sdllm_kv_append", "sdllm_suffix_keep_indices",
     "sdllm_status_string", "sdllm_last_error", "sdllm_version",
 )
 
@@ -83,6 +83,9 @@ def load_library(path: Optional[str] = None):
     lib.sdllm_unmask_workspace_bytes.argtypes = [ctypes.POINTER(UnmaskParams)]
     lib.sdllm_confidence_unmask.restype = i32
     lib.sdllm_confidence_unmask.argtypes = [ctypes.POINTER(UnmaskParams)] + [vp] * 7 + [vp, sz, vp]
+    lib.sdllm_suffix_keep_indices.restype = i32
+    lib.sdllm_suffix_keep_indices.argtypes = [ctypes.c_int32] * 4 + [ctypes.POINTER(ctypes.c_int32), ctypes.c_int32,
+                                                                    ctypes.POINTER(ctypes.c_int32)]
     lib.sdllm_kv_append.restype = i32
     lib.sdllm_kv_append.argtypes = [ctypes.POINTER(AppendParams)] + [vp] * 5 + [vp]
     _lib = lib
@@ -262,3 +265,14 @@ def bind_kv_append(k_caches, v_caches, k_blocks, v_blocks, prefix_len: int, do_a
             _stream(stream))
     keep = (p, k_caches, v_caches, k_blocks, v_blocks, do_append)
     return BoundCall(load_library().sdllm_kv_append, args, keep, None)
+
+
+# ---------------------------------------------------------------------------------------------
+def suffix_keep_indices(S: int, K: int, w_blocks: int, keep_trailing: bool = True):
+    """sdllm_suffix_keep_indices (host helper, paper Eq. 7).  Returns a Python list of the kept suffix
+    positions (relative to the start of the suffix, strictly increasing)."""
+    cap = max(min(w_blocks * K, max(S, 0)) + 1, 1)
+    buf = (ctypes.c_int32 * cap)()
+    n = ctypes.c_int32(0)
+    _check(load_library().sdllm_suffix_keep_indices(S, K, w_blocks, 1 if keep_trailing else 0, buf, cap, ctypes.byref(n)))
+    return [buf[i] for i in range(n.value)]

@@ -167,6 +167,20 @@ int sdllm_block_attention(const sdllm_attn_params* p,
   return SDLLM_OK;
 }
 
+int sdllm_suffix_keep_indices(int32_t S, int32_t K, int32_t w_blocks, int32_t keep_trailing,
+                              int32_t* out_idx, int32_t cap, int32_t* n_keep) {
+  if (!out_idx || !n_keep) return fail(SDLLM_ERR_INVALID_ARG, "suffix_keep_indices: out_idx / n_keep is NULL");
+  if (S < 0 || w_blocks < 0 || K < 1) return fail(SDLLM_ERR_INVALID_ARG, "suffix_keep_indices: need S >= 0, w_blocks >= 0, K >= 1");
+  const long long window = (long long)w_blocks * K < S ? (long long)w_blocks * K : S;
+  const bool extra = keep_trailing && S > 0 && window < S;          // trailing position outside the window
+  const long long n = window + (extra ? 1 : 0);
+  if (n > cap) return fail(SDLLM_ERR_INVALID_ARG, "suffix_keep_indices: %lld indices do not fit the capacity %d", n, cap);
+  for (long long i = 0; i < window; ++i) out_idx[i] = (int32_t)i;
+  if (extra) out_idx[window] = S - 1;
+  *n_keep = (int32_t)n;
+  return SDLLM_OK;
+}
+
 size_t sdllm_unmask_workspace_bytes(const sdllm_unmask_params* p) {
   if (check_unmask_params(p) != SDLLM_OK) return (size_t)-1;
   return sdllm::unmask_workspace_bytes(*p);
