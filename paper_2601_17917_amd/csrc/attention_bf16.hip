@@ -105,46 +105,85 @@ template <int D> struct Lane {
   unsigned lds_base; int wave, lane, G;
 };
 
-// Puts key tile `tile` in flight into ring stage `stage`: 2 * IPT transfers per wave.
+typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;   // scalar (constant-cache) loads
+
+// keep_idx values of the first and the last of the 16 rows a wave moves for one key tile, loaded one
+// tile ahead (scalar loads that complete behind the tile being computed).  Indices are clamped, so
+// asking for a tile past the end is harmless.
+struct KeepAhead { int first, last; };
+
+__device__ __forceinline__ void load_keep_ahead(const AttnArgs& a, int wave, int tile, KeepAhead& ka) {
+  ka.first = 0; ka.last = 0;
+  if (a.n_keep > 0) {
+    const const_i32_ptr keep_c = (const_i32_ptr)(uintptr_t)a.keep_idx;
+    const int s0 = tile * kKeyTile + 16 * wave - a.P - a.K;
+    ka.first = keep_c[min(max(s0, 0), a.n_keep - 1)];
+    ka.last = keep_c[min(max(s0 + 15, 0), a.n_keep - 1)];
+  }
+}
+
+// Puts key tile `tile` in flight into ring stage `stage`: 2 * IPT transfers per wave, which moves
+// rows 16*wave .. 16*wave+15 of the tile.  `ka` holds the keep_idx bounds of these rows on entry and
+// those of the next tile on return.
 template <int D>
 __device__ __forceinline__ void issue_tile(const AttnArgs& a, const Lane<D>& L, const uint16_t* kc, const uint16_t* vc,
                                            const uint16_t* kb, const uint16_t* vb, const uint16_t* ks, const uint16_t* vs,
-                                           int tile, int stage) {
+                                           int tile, int stage, KeepAhead& ka) {
   using S = Shape<D>;
-  typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
   const unsigned sk = L.lds_base + stage * S::TILEB + 16 * L.wave * S::ROWB;
   const unsigned sv = sk + S::VBASE;
-  if ((tile + 1) * kKeyTile <= a.P) {              // uniform: whole tile inside the prefix cache
-    const unsigned char* kt = reinterpret_cast<const unsigned char*>(kc) + (long long)tile * S::TILEB;
-    const unsigned char* vt = reinterpret_cast<const unsigned char*>(vc) + (long long)tile * S::TILEB;
+  const int r0 = tile * kKeyTile + 16 * L.wave;    // uniform: first of the wave's 16 rows
+  const int r15 = r0 + 15;
+  // Uniform classification of the wave's rows.  Sixteen consecutive rows of one source tensor (the
+  // cache, the block, or a run of the suffix that keep_idx maps to consecutive rows: increasing
+  // indices whose ends differ by 15) are one contiguous 16-row slab: a scalar base plus the lane's
+  // constant offset, no per-lane address arithmetic.
+  const bool in_cache = r15 < a.P;
+  const bool in_block = r0 >= a.P && r15 < a.P + a.K;
+  const bool in_sfx = r0 >= a.P + a.K && r15 < a.Nkv && ka.last - ka.first == 15;
+  if (in_cache || in_block || in_sfx) {
+    const long long row0 = in_cache ? r0 : (in_block ? r0 - a.P : ka.first);
+    const uint16_t* kp = in_cache ? kc : (in_block ? kb : ks);
+    const uint16_t* vp = in_cache ? vc : (in_block ? vb : vs);
+    // the lane offsets kgo / vgo count rows from the start of the tile: step back by the wave's 16*wave rows
+    const unsigned char* kt = reinterpret_cast<const unsigned char*>(kp) + (row0 - 16 * L.wave) * S::ROWB;
+    const unsigned char* vt = reinterpret_cast<const unsigned char*>(vp) + (row0 - 16 * L.wave) * S::ROWB;
 #pragma unroll
     for (int j = 0; j < S::IPT; ++j) dma16_sbase(sk + j * S::RPI * S::ROWB, kt, L.kgo[j]);
 #pragma unroll
     for (int j = 0; j < S::IPT; ++j) dma16_sbase(sv + j * S::RPI * S::ROWB, vt, L.vgo[j]);
   } else {
-    // block / gathered suffix rows, ragged tail: no divergent branch; keep_idx is read through the
-    // constant address space with uniform indices (scalar loads: they do not touch the
-    // vector-memory counter that tracks the transfers in flight)
-    const const_i32_ptr keep_c = (const_i32_ptr)(uintptr_t)a.keep_idx;
-    const int r0 = tile * kKeyTile + 16 * L.wave;  // uniform
+    // rows from more than one place, a gap in keep_idx, the ragged tail: per-row addresses without a
+    // divergent branch.  keep_idx is read through the constant address space with uniform indices
+    // (scalar loads: they do not touch the vector-memory counter that tracks the transfers in flight);
+    // rows past the end repeat the last row (finite data; their scores are masked).
+    int kidx[S::IPT];
+#pragma unroll
+    for (int j = 0; j < S::IPT; ++j) kidx[j] = 0;
+    if (a.n_keep > 0) {
+      const const_i32_ptr keep_c = (const_i32_ptr)(uintptr_t)a.keep_idx;
+      // the lane's own row is picked with and/or masks (a select would let the compiler move each
+      // load under a branch of its own and wait for them one by one)
+      int pick[S::RPI];
+#pragma unroll
+      for (int q2 = 0; q2 < S::RPI; ++q2) pick[q2] = -(int)(L.lane / S::CPR == q2);
+#pragma unroll
+      for (int j = 0; j < S::IPT; ++j)
+#pragma unroll
+        for (int q2 = 0; q2 < S::RPI; ++q2) {
+          const int si = min(max(r0 + S::RPI * j + q2 - a.P - a.K, 0), a.n_keep - 1);
+          kidx[j] |= keep_c[si] & pick[q2];
+        }
+    }
     const unsigned char* kpp[S::IPT]; const unsigned char* vpp[S::IPT];
 #pragma unroll
     for (int j = 0; j < S::IPT; ++j) {
       const int rl = S::RPI * j + L.lane / S::CPR;
       const int r = min(r0 + rl, a.Nkv - 1);
-      int kidx = 0;
-      if (a.n_keep > 0) {
-#pragma unroll
-        for (int q2 = 0; q2 < S::RPI; ++q2) {
-          const int si = min(max(r0 + S::RPI * j + q2 - a.P - a.K, 0), a.n_keep - 1);
-          const int v = keep_c[si];
-          kidx = (L.lane / S::CPR == q2) ? v : kidx;
-        }
-      }
       const bool in_c = r < a.P, in_b = r < a.P + a.K;
       const uint16_t* kp = in_c ? kc : (in_b ? kb : ks);
       const uint16_t* vp = in_c ? vc : (in_b ? vb : vs);
-      const long long off = (long long)(in_c ? r : (in_b ? r - a.P : kidx)) * D;
+      const long long off = (long long)(in_c ? r : (in_b ? r - a.P : kidx[j])) * D;
       kpp[j] = reinterpret_cast<const unsigned char*>(kp + off) + (L.kgo[j] - (16 * L.wave + rl) * S::ROWB);
       vpp[j] = reinterpret_cast<const unsigned char*>(vp + off) + (L.vgo[j] - (16 * L.wave + rl) * S::ROWB);
     }
@@ -153,6 +192,7 @@ __device__ __forceinline__ void issue_tile(const AttnArgs& a, const Lane<D>& L, 
 #pragma unroll
     for (int j = 0; j < S::IPT; ++j) dma16_vaddr(sv + j * S::RPI * S::ROWB, vpp[j]);
   }
+  load_keep_ahead(a, L.wave, tile + 1, ka);
 }
 
 typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
@@ -348,7 +388,9 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   }
 
   // ---- the first tile goes in flight, then the query rows
-  issue_tile<D>(a, L, kc, vc, kb, vb, ks, vs, t0, 0);
+  KeepAhead ka;
+  load_keep_ahead(a, wave, t0, ka);
+  issue_tile<D>(a, L, kc, vc, kb, vb, ks, vs, t0, 0, ka);
 
   // ---- query rows of this wave, as MFMA B operands (lane: row l16, d = 32*s + 8*G .. +7)
   const int row_base = qt * (64 * RB) + wave * (16 * RB);
@@ -382,12 +424,12 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   for (int t = t0; t < t1; t += 2) {
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
-    if (t + 1 < t1) issue_tile<D>(a, L, kc, vc, kb, vb, ks, vs, t + 1, 1);
+    if (t + 1 < t1) issue_tile<D>(a, L, kc, vc, kb, vb, ks, vs, t + 1, 1, ka);
     compute_tile<D, RB, 0>(a, L, lds, t, qreg, o, m, lsum);
     if (t + 1 >= t1) break;
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
-    if (t + 2 < t1) issue_tile<D>(a, L, kc, vc, kb, vb, ks, vs, t + 2, 0);
+    if (t + 2 < t1) issue_tile<D>(a, L, kc, vc, kb, vb, ks, vs, t + 2, 0, ka);
     compute_tile<D, RB, 1>(a, L, lds, t + 1, qreg, o, m, lsum);
   }
 
