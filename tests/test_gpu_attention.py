@@ -84,6 +84,25 @@ def test_attention_bf16_shapes(gpu_lib, B, Hq, Hkv, D, P, cap, K, S, keep, split
     assert err <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,D,P,cap,K,S,keep,splits", [
+    # a wave moves 16-row slabs of a key tile; a slab that lies in one tensor and (for the suffix) maps to
+    # consecutive rows takes a scalar-base path, every other slab a per-row path: hit both and their borders
+    (1, 2, 2, 128, 48, 64, 32, 100, tuple(range(5, 53)) + (99,), 0),      # window not starting at 0, then a jump
+    (2, 2, 1, 128, 40, 40, 24, 90, tuple(range(0, 64)), 0),               # P, K off the slab grid: straddling slabs
+    (1, 1, 1, 128, 64, 64, 32, 64, tuple(range(0, 8)) + tuple(range(9, 17)) + tuple(range(17, 49)), 0),  # one gap inside a slab
+    (1, 2, 2, 64, 32, 48, 32, 300, tuple(range(100, 164)) + (299,), 2),   # D = 64, late window, split keys
+    (1, 4, 1, 128, 0, 0, 48, 200, tuple(range(200)), 3),                  # no cache: block slabs, then a long run
+    (1, 1, 1, 128, 16, 16, 16, 40, tuple(range(1, 40, 1)), 0),            # run ends 1 short of a slab
+])
+def test_attention_bf16_slab_paths(gpu_lib, B, Hq, Hkv, D, P, cap, K, S, keep, splits):
+    t = wl.make_custom_attention_inputs("bf16", B, Hq, Hkv, D, P, max(cap, 1), K, max(S, 1), keep, seed=3 * P + K + S)
+    got = run_gpu(gpu_lib, t, P, kv_splits=splits)
+    want = oracle(t, P)
+    err = np.abs(got - want).max()
+    print(f"bf16 slab-path err {err:.3e}")
+    assert err <= TOL["bf16"]
+
+
 def test_attention_bf16_keep_all_equals_full_context(gpu_lib):
     """Keeping every suffix row = dense attention over the concatenated sequence: feed the same rows
     through the cache operand instead and compare the two GPU results with each other and the oracle."""
