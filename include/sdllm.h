@@ -2,12 +2,14 @@
  * sdllm.h -- C ABI of the MI355X (gfx950) hot path of one Streaming-dLLM
  * block-wise diffusion decode step.
  *
- * Three operations, one call each:
+ * The operations, one call each:
  *   sdllm_block_attention    bidirectional attention of (active block + kept suffix)
  *                            queries over (prefix cache + active block + kept suffix) K/V
  *   sdllm_confidence_unmask  vocab softmax -> max-probability / argmax -> dynamic-threshold
  *                            commit -> block-done / EOS early-exit flags
  *   sdllm_kv_append          copy the finished block's K/V into the prefix cache
+ *   sdllm_rope_gathered      rotary embedding of the pruned rows with their original position ids
+ *   sdllm_suffix_keep_indices  (host) which suffix rows the attenuation-guided rule keeps
  *
  * Conventions common to all calls
  *   - Every buffer is CALLER-ALLOCATED DEVICE memory unless said otherwise; the library
@@ -187,6 +189,45 @@ int sdllm_kv_append(const sdllm_append_params* p,
  * ------------------------------------------------------------------------------------- */
 int sdllm_suffix_keep_indices(int32_t S, int32_t K, int32_t w_blocks, int32_t keep_trailing,
                               int32_t* out_idx, int32_t cap, int32_t* n_keep);
+
+/* ---------------------------------------------------------------------------------------
+ * Rotary position embedding of the pruned rows with their ORIGINAL position ids (paper section
+ * 3.3, the sentence before Eq. 7: the kept suffix tokens keep the logical order of the sequence
+ * through their RoPE position ids; the ablation on trailing positional information is about this
+ * id).  Applied to a query or a key tensor before sdllm_block_attention (once per tensor):
+ *     block row r           -> position pos0 + r
+ *     kept suffix row j     -> position pos0 + K + keep_idx[j]      (not pos0 + K + j)
+ * Rotation of each pair (x_a, x_b) by the angle position * theta_base^(-2i/D), i = 0..D/2-1:
+ *     x_a' = x_a cos - x_b sin,   x_b' = x_b cos + x_a sin,
+ * (a, b) = (i, i + D/2) when interleaved == 0, (2i, 2i + 1) otherwise.  cos / sin are evaluated
+ * in double precision, the products in fp32; bf16 results are rounded to nearest even.
+ *
+ *   dtype, B, H (heads of this tensor), D (multiple of 16, <= 512), K >= 1, S >= 0,
+ *   0 <= n_keep <= S, pos0 >= 0 (pos0 + K + S must fit int32), theta_base > 1.
+ * ------------------------------------------------------------------------------------- */
+typedef struct sdllm_rope_params {
+  int32_t dtype;
+  int32_t B, H, D;
+  int32_t K, S, n_keep;
+  int32_t pos0;
+  float theta_base;
+  int32_t interleaved;
+} sdllm_rope_params;
+
+/*
+ *   x_block  [B,H,K,D] read     out_block  [B,H,K,D] written entirely (may be x_block: in place)
+ *   x_suffix [B,H,S,D] read     out_suffix [B,H,S,D]: ONLY the kept rows are written, at their own
+ *            index keep_idx[j] (so the tensor is used with the same keep_idx afterwards); may be
+ *            x_suffix.  Both may be NULL iff n_keep == 0.
+ *   keep_idx [n_keep] int32 on the device; precondition as for sdllm_block_attention.
+ * Apart from exact in-place use the outputs must not overlap the inputs.  No workspace.
+ * Errors: INVALID_ARG, UNSUPPORTED, HIP.
+ */
+int sdllm_rope_gathered(const sdllm_rope_params* p,
+                        const void* x_block, const void* x_suffix,
+                        const int32_t* keep_idx,
+                        void* out_block, void* out_suffix,
+                        void* stream);
 
 /* ---------------------------------------------------------------------------------------
  * Diagnostics.  sdllm_plan_attention reports the launch plan the library would use (host

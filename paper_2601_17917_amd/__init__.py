@@ -19,7 +19,7 @@ FP32, BF16 = 0, 1
 EXPORTED_SYMBOLS = (
     "sdllm_block_attention", "sdllm_attention_workspace_bytes", "sdllm_plan_attention",
     "sdllm_confidence_unmask", "sdllm_unmask_workspace_bytes",
-    "sdllm_kv_append", "sdllm_suffix_keep_indices",
+    "sdllm_kv_append", "sdllm_suffix_keep_indices", "sdllm_rope_gathered",
     "sdllm_status_string", "sdllm_last_error", "sdllm_version",
 )
 
@@ -43,6 +43,12 @@ class AppendParams(ctypes.Structure):
                 ("Hkv", ctypes.c_int32), ("D", ctypes.c_int32), ("K", ctypes.c_int32),
                 ("prefix_len", ctypes.c_int32), ("prefix_cap", ctypes.c_int32),
                 ("cache_layer_stride", ctypes.c_int64), ("block_layer_stride", ctypes.c_int64)]
+
+
+class RopeParams(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("B", ctypes.c_int32), ("H", ctypes.c_int32), ("D", ctypes.c_int32),
+                ("K", ctypes.c_int32), ("S", ctypes.c_int32), ("n_keep", ctypes.c_int32),
+                ("pos0", ctypes.c_int32), ("theta_base", ctypes.c_float), ("interleaved", ctypes.c_int32)]
 
 
 class AttnPlan(ctypes.Structure):
@@ -88,6 +94,8 @@ def load_library(path: Optional[str] = None):
                                                                     ctypes.POINTER(ctypes.c_int32)]
     lib.sdllm_kv_append.restype = i32
     lib.sdllm_kv_append.argtypes = [ctypes.POINTER(AppendParams)] + [vp] * 5 + [vp]
+    lib.sdllm_rope_gathered.restype = i32
+    lib.sdllm_rope_gathered.argtypes = [ctypes.POINTER(RopeParams)] + [vp] * 5 + [vp]
     _lib = lib
     return lib
 
@@ -265,6 +273,35 @@ def bind_kv_append(k_caches, v_caches, k_blocks, v_blocks, prefix_len: int, do_a
             _stream(stream))
     keep = (p, k_caches, v_caches, k_blocks, v_blocks, do_append)
     return BoundCall(load_library().sdllm_kv_append, args, keep, None)
+
+
+# ---------------------------------------------------------------------------------------------
+def rope_gathered(*args, **kw):
+    """sdllm_rope_gathered: see include/sdllm.h.  Returns (out_block, out_suffix)."""
+    return bind_rope_gathered(*args, **kw)()
+
+
+def bind_rope_gathered(x_block, x_suffix, keep_idx, pos0: int, theta_base: float, interleaved: bool = False,
+                       out_block=None, out_suffix=None, stream=None) -> BoundCall:
+    """Marshal once, call many times.  out_* default to the inputs (in place)."""
+    import torch
+    B, H, K, D = x_block.shape
+    n_keep = 0 if keep_idx is None else int(keep_idx.shape[0])
+    S = 0 if x_suffix is None else int(x_suffix.shape[2])
+    out_block = x_block if out_block is None else out_block
+    out_suffix = x_suffix if out_suffix is None else out_suffix
+    for name, t in (("x_block", x_block), ("x_suffix", x_suffix), ("out_block", out_block), ("out_suffix", out_suffix)):
+        _require(t, name, x_block.dtype)
+    _require(keep_idx, "keep_idx", torch.int32)
+    if x_suffix is not None and tuple(x_suffix.shape) != (B, H, S, D):
+        raise SdllmError(ERR_INVALID_ARG, "x_suffix must be [B,H,S,D] with the B, H, D of x_block")
+    if tuple(out_block.shape) != (B, H, K, D) or (out_suffix is not None and tuple(out_suffix.shape) != (B, H, S, D)):
+        raise SdllmError(ERR_INVALID_ARG, "out_block / out_suffix must have the shapes of the inputs")
+    p = RopeParams(_dtype_code(x_block), B, H, D, K, S, n_keep, int(pos0), float(theta_base), int(bool(interleaved)))
+    args = (ctypes.byref(p), _ptr(x_block), _ptr(x_suffix), _ptr(keep_idx), _ptr(out_block), _ptr(out_suffix),
+            _stream(stream))
+    keep = (p, x_block, x_suffix, keep_idx, out_block, out_suffix)
+    return BoundCall(load_library().sdllm_rope_gathered, args, keep, (out_block, out_suffix))
 
 
 # ---------------------------------------------------------------------------------------------

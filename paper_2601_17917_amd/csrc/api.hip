@@ -91,6 +91,24 @@ int check_append_params(const sdllm_append_params* p) {
   return SDLLM_OK;
 }
 
+int check_rope_params(const sdllm_rope_params* p) {
+  if (!p) return fail(SDLLM_ERR_INVALID_ARG, "rope: params is NULL");
+  if (p->dtype != SDLLM_FP32 && p->dtype != SDLLM_BF16)
+    return fail(SDLLM_ERR_UNSUPPORTED, "rope: dtype %d not supported (fp32=0, bf16=1)", p->dtype);
+  if (p->B < 1 || p->H < 1 || p->K < 1) return fail(SDLLM_ERR_INVALID_ARG, "rope: B, H, K must be >= 1");
+  if (p->D < 16 || p->D % 16 != 0 || p->D > 512)
+    return fail(SDLLM_ERR_UNSUPPORTED, "rope: head_dim %d not supported (multiple of 16, <= 512)", p->D);
+  if (p->S < 0 || p->n_keep < 0 || p->n_keep > p->S)
+    return fail(SDLLM_ERR_INVALID_ARG, "rope: need 0 <= n_keep (%d) <= S (%d)", p->n_keep, p->S);
+  if (p->pos0 < 0 || (long long)p->pos0 + p->K + p->S > 0x7fffffffLL)
+    return fail(SDLLM_ERR_INVALID_ARG, "rope: need pos0 >= 0 and pos0 + K + S within int32");
+  if (!(p->theta_base > 1.0f) || std::isinf(p->theta_base))
+    return fail(SDLLM_ERR_INVALID_ARG, "rope: theta_base must be finite and > 1");
+  if ((long long)p->B * p->H > 0x7fffffffLL || p->K + p->n_keep > 0x7fffffff - 1)
+    return fail(SDLLM_ERR_UNSUPPORTED, "rope: problem too large");
+  return SDLLM_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -216,6 +234,21 @@ int sdllm_kv_append(const sdllm_append_params* p, void* k_caches, void* v_caches
     return fail(SDLLM_ERR_INVALID_ARG, "kv_append: a base pointer is not 16-byte aligned");
   hipError_t e = sdllm::launch_kv_append(*p, k_caches, v_caches, k_blocks, v_blocks, do_append, (hipStream_t)stream);
   if (e != hipSuccess) return fail(SDLLM_ERR_HIP, "kv_append: %s", hipGetErrorString(e));
+  return SDLLM_OK;
+}
+
+int sdllm_rope_gathered(const sdllm_rope_params* p, const void* x_block, const void* x_suffix,
+                        const int32_t* keep_idx, void* out_block, void* out_suffix, void* stream) {
+  int rc = check_rope_params(p);
+  if (rc != SDLLM_OK) return rc;
+  if (!x_block || !out_block) return fail(SDLLM_ERR_INVALID_ARG, "rope: x_block, out_block must not be NULL");
+  if (p->n_keep > 0 && (!x_suffix || !out_suffix || !keep_idx))
+    return fail(SDLLM_ERR_INVALID_ARG, "rope: x_suffix / out_suffix / keep_idx is NULL with n_keep > 0");
+  const void* ptrs[] = {x_block, x_suffix, out_block, out_suffix};
+  for (const void* q : ptrs)
+    if (q && !aligned16(q)) return fail(SDLLM_ERR_INVALID_ARG, "rope: a base pointer is not 16-byte aligned");
+  hipError_t e = sdllm::launch_rope(*p, x_block, x_suffix, keep_idx, out_block, out_suffix, (hipStream_t)stream);
+  if (e != hipSuccess) return fail(SDLLM_ERR_HIP, "rope: %s", hipGetErrorString(e));
   return SDLLM_OK;
 }
 

@@ -45,6 +45,10 @@ hipError_t launch_unmask(const sdllm_unmask_params& p, const void* logits, int32
                          float* confidence, int32_t* n_committed, uint8_t* block_done, uint8_t* eos_seen,
                          void* workspace, hipStream_t stream);
 
+// ---- rope ----
+hipError_t launch_rope(const sdllm_rope_params& p, const void* x_block, const void* x_suffix,
+                       const int32_t* keep_idx, void* out_block, void* out_suffix, hipStream_t stream);
+
 // ---- kv append ----
 hipError_t launch_kv_append(const sdllm_append_params& p, void* k_caches, void* v_caches,
                             const void* k_blocks, const void* v_blocks, const uint8_t* do_append,

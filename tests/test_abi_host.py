@@ -153,3 +153,36 @@ def test_binding_refuses_host_tensors(lib):
     x = torch.zeros((1, 1, 32, 128), dtype=torch.bfloat16)
     with pytest.raises(sd.SdllmError):
         sd.block_attention(x, None, None, None, x, x, None, None, None, 0)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(D=40), sd.ERR_UNSUPPORTED),
+    (dict(D=1024), sd.ERR_UNSUPPORTED),
+    (dict(dtype=5), sd.ERR_UNSUPPORTED),
+    (dict(n_keep=9, S=8), sd.ERR_INVALID_ARG),
+    (dict(pos0=-1), sd.ERR_INVALID_ARG),
+    (dict(pos0=2**31 - 10), sd.ERR_INVALID_ARG),
+    (dict(theta_base=1.0), sd.ERR_INVALID_ARG),
+    (dict(theta_base=float("nan")), sd.ERR_INVALID_ARG),
+    (dict(K=0), sd.ERR_INVALID_ARG),
+])
+def test_rope_validation(lib, kw, status):
+    base = dict(dtype=sd.BF16, B=1, H=2, D=128, K=32, S=64, n_keep=8, pos0=100, theta_base=10000.0, interleaved=0)
+    base.update(kw)
+    p = sd.RopeParams(**base)
+    vp = ctypes.c_void_p
+    assert lib.sdllm_rope_gathered(ctypes.byref(p), vp(4096), vp(4096), vp(4096), vp(4096), vp(4096), None) == status
+    assert lib.sdllm_last_error() != b""
+
+
+def test_rope_null_and_misaligned(lib):
+    vp = ctypes.c_void_p
+    p = sd.RopeParams(sd.FP32, 1, 2, 64, 4, 8, 2, 0, 10000.0, 0)
+    ok = [vp(4096)] * 5
+    for i in (0, 1, 2, 3, 4):
+        bad = list(ok); bad[i] = None
+        assert lib.sdllm_rope_gathered(ctypes.byref(p), *bad, None) == sd.ERR_INVALID_ARG
+    bad = list(ok); bad[3] = vp(4100)
+    assert lib.sdllm_rope_gathered(ctypes.byref(p), *bad, None) == sd.ERR_INVALID_ARG
+    assert lib.sdllm_rope_gathered(None, *ok, None) == sd.ERR_INVALID_ARG
+    assert ctypes.sizeof(sd.RopeParams) == 40

@@ -53,12 +53,12 @@ def test_relative_position_property():
     g = _rng(3)
     q, k = g.standard_normal((1, 32)), g.standard_normal((1, 32))
     for il in (False, True):
-        d0 = float(rope_rotate(q, [40], 10000.0, il) @ rope_rotate(k, [33], 10000.0, il).T)
+        d0 = (rope_rotate(q, [40], 10000.0, il) @ rope_rotate(k, [33], 10000.0, il).T).item()
         for shift in (1, 17, 1000):
-            d1 = float(rope_rotate(q, [40 + shift], 10000.0, il) @ rope_rotate(k, [33 + shift], 10000.0, il).T)
+            d1 = (rope_rotate(q, [40 + shift], 10000.0, il) @ rope_rotate(k, [33 + shift], 10000.0, il).T).item()
             assert abs(d0 - d1) < 1e-10
         # and it does change with m - n
-        d2 = float(rope_rotate(q, [41], 10000.0, il) @ rope_rotate(k, [33], 10000.0, il).T)
+        d2 = (rope_rotate(q, [41], 10000.0, il) @ rope_rotate(k, [33], 10000.0, il).T).item()
         assert abs(d0 - d2) > 1e-6
 
 
