@@ -259,6 +259,20 @@ def main():
     fresh = (st.tokens[0].clone(), st.masked[0].clone())
     t_unm = time_kernel(unmask_fresh) - time_kernel(restore_only)
     t_app = time_kernel(st.append)
+    # RoPE of the pruned q and k rows (the step before the attention call; NOT part of the timed step):
+    # in place on copies, q and k back to back
+    t0_ = st.layers[0]
+    nk = w.n_keep
+    rq = sd.bind_rope_gathered(t0_["q_block"].clone(), t0_["q_suffix"].clone() if nk else None,
+                               t0_["keep_idx"] if nk else None, w.P, 500000.0)
+    rk = sd.bind_rope_gathered(t0_["k_block"].clone(), t0_["k_suffix"].clone() if nk else None,
+                               t0_["keep_idx"] if nk else None, w.P, 500000.0)
+
+    def rope_qk():
+        rq(); rk()
+
+    t_rope = time_kernel(rope_qk)
+    rope_bytes = 2 * w.B * (w.Hq + w.Hkv) * w.Nq * w.D * w.elem_bytes      # rows read + rows written
     masked_rows = int((st.host_unmask["masked"] != 0).sum())
     unmask_bytes = masked_rows * w.V * w.elem_bytes
     append_bytes = 2 * 2 * w.n_layers * w.B * w.Hkv * w.K * w.D * w.elem_bytes
@@ -270,6 +284,8 @@ def main():
         "unmask_call": {"ms": t_unm, "gbs": unmask_bytes / t_unm / 1e6, "frac_hbm_peak": unmask_bytes / t_unm / 1e6 / HBM_PEAK_GBS,
                         "masked_rows": masked_rows},
         "append_call": {"ms": t_app, "gbs": append_bytes / t_app / 1e6, "frac_hbm_peak": append_bytes / t_app / 1e6 / HBM_PEAK_GBS},
+        "rope_q_and_k_calls": {"ms": t_rope, "gbs": rope_bytes / t_rope / 1e6, "frac_hbm_peak": rope_bytes / t_rope / 1e6 / HBM_PEAK_GBS,
+                               "in_timed_step": False},
     }
     dur = attn_ms_ev if use_ev else None
     if bound == "hbm":
