@@ -158,6 +158,7 @@ def _sampled_heads_check(sd, w, pairs, seed=0, kv_splits=0):
     ("cfg3A", [(0, 0), (3, 17), (7, 31), (5, 8)]),
     ("cfg3B", [(0, 0), (7, 31), (2, 13)]),
     ("cfg4", [(0, 0), (15, 27), (8, 6), (8, 7), (3, 20)]),
+    ("cfgBC", [(0, 0), (7, 31), (4, 11), (4, 12)]),         # block-causal topology: no suffix at all
 ])
 def test_attention_full_size_sampled(gpu_lib, name, pairs):
     """Full-size launch in the configuration the bench times; the oracle checks sampled (batch, head) pairs."""

@@ -202,7 +202,7 @@ def test_unmask_cfg2_full_size(gpu_lib):
     assert skip == 0
 
 
-@pytest.mark.parametrize("name", ["cfg3A", "cfg4", "cfg4boost", "cfg5"])
+@pytest.mark.parametrize("name", ["cfg3A", "cfg4", "cfg4boost", "cfg5", "cfgBC"])
 def test_unmask_full_size_configs(gpu_lib, name):
     w = wl.WORKLOADS[name]
     u = wl.make_unmask_inputs(w, seed=0)

@@ -159,6 +159,11 @@ WORKLOADS: Dict[str, Workload] = {
     # long-context 32-layer stack
     "cfg5": Workload("cfg5", "bf16", 4, 32, 32, 128, 4096, 2048, 64, 16, 64, "window+last", 126464,
                      1.0, 4.0, False, "all", 0.9, 0.3, n_layers=32),
+    # block-causal (next-block) topology of the paper's extension section: the active block is the last
+    # visible one, so there is no suffix at all (S = 0, nothing kept) and only the temporal rule applies;
+    # GQA 32/8, last block of a 256-token generation after a 1024-token prompt
+    "cfgBC": Workload("cfgBC", "bf16", 8, 32, 8, 128, 1024, 256, 32, 7, 0, "first", 152064,
+                      1.0, 4.0, True, "half", 0.9, 0.3),
     # small bf16 case the oracle finishes instantly; spans several 32-key tiles and a ragged tail
     "small_bf16": Workload("small_bf16", "bf16", 2, 4, 2, 128, 75, 160, 32, 1, 33, "window+last", 5000,
                            1.0, 4.0, True, "half", 0.9, 0.3),
