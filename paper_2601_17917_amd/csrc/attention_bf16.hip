@@ -529,9 +529,10 @@ AttnPlan plan_attention_bf16(const sdllm_attn_params& p) {
     ns = p.kv_splits;
   } else {
     ns = (2LL * kNumCUs + base - 1) / base;        // aim at two workgroups per CU ...
-    // ... but keep a split long enough to amortise its merge: 16 key tiles, or 2 when the
-    // launch would otherwise leave most of the chip idle (sweeps: 17 tiles -> 1 split, 82 -> 2)
-    const long long cap2 = pl.key_tiles / (base >= kNumCUs / 2 ? 16 : 2);
+    // ... but keep a split long enough to amortise its merge: 16 key tiles once there is a workgroup
+    // per CU without splitting, 8 with one per two CUs, 2 when the launch would otherwise leave most
+    // of the chip idle (sweeps: 256 workgroups x 17 tiles -> 1 split, x 82 -> 2; 128 x 20 -> 2; 32 x 11 -> 4)
+    const long long cap2 = pl.key_tiles / (base >= kNumCUs ? 16 : (base >= kNumCUs / 2 ? 8 : 2));
     if (ns > cap2) ns = cap2;
   }
   if (ns > pl.key_tiles) ns = pl.key_tiles;
