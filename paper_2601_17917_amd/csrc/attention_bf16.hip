@@ -71,9 +71,25 @@ __device__ __forceinline__ void dma16_sbase(unsigned lds_addr, const void* sbase
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
                :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(pu) : "memory", "m0");
 }
+// the same with the LDS address given as scalar base + compile-time offset (one scalar add into m0)
+template <int OFF>
+__device__ __forceinline__ void dma16_sbase_off(unsigned lds_base, const void* sbase, unsigned voff) {
+  asm volatile("s_add_u32 m0, %0, %3\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds_base), "v"(voff), "s"(sbase), "n"(OFF) : "memory", "m0", "scc");
+}
 __device__ __forceinline__ void dma16_vaddr(unsigned lds_addr, const void* vaddr) {
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
                :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(vaddr) : "memory", "m0");
+}
+// A pointer that is the same in every lane, moved into a scalar register pair (64-bit address
+// arithmetic with products is done on the vector ALU; everything derived from the result would
+// otherwise stay there too)
+template <typename T>
+__device__ __forceinline__ const T* uniform_ptr(const T* p) {
+  const unsigned long long v = reinterpret_cast<unsigned long long>(p);
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+  const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+  return reinterpret_cast<const T*>(((unsigned long long)hi << 32) | lo);
 }
 // s_waitcnt vmcnt(n) only (expcnt / lgkmcnt fields left at "no wait")
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
@@ -114,11 +130,48 @@ struct KeepAhead { int first, last; };
 
 __device__ __forceinline__ void load_keep_ahead(const AttnArgs& a, int wave, int tile, KeepAhead& ka) {
   ka.first = 0; ka.last = 0;
-  if (a.n_keep > 0) {
+  const int s0 = tile * kKeyTile + 16 * wave - a.P - a.K;
+  if (a.n_keep > 0 && s0 >= 0) {                   // only slabs that start in the suffix use the bounds
     const const_i32_ptr keep_c = (const_i32_ptr)(uintptr_t)a.keep_idx;
-    const int s0 = tile * kKeyTile + 16 * wave - a.P - a.K;
-    ka.first = keep_c[min(max(s0, 0), a.n_keep - 1)];
-    ka.last = keep_c[min(max(s0 + 15, 0), a.n_keep - 1)];
+    ka.first = keep_c[min(s0, a.n_keep - 1)];
+    ka.last = keep_c[min(s0 + 15, a.n_keep - 1)];
+  }
+}
+
+// Loop-invariant tile ranges of a wave's 16-row slab (rows 64 t + 16 w .. + 15 of key tile t): the slab
+// lies wholly in the cache for t <= tc, wholly in the block for tb0 <= t <= tb1, wholly in the kept
+// suffix for ts0 <= t <= ts1 (a range is empty when its bounds cross).
+struct SlabRanges { int tc, tb0, tb1, ts0, ts1; };
+
+__device__ __forceinline__ SlabRanges slab_ranges(const AttnArgs& a, int wave) {
+  SlabRanges r;
+  const int w16 = 16 * wave;                       // arithmetic shifts: floor division also below zero
+  r.tc = (a.P - w16 - 16) >> 6;
+  r.tb0 = (a.P - w16 + 63) >> 6;   r.tb1 = (a.P + a.K - w16 - 16) >> 6;
+  r.ts0 = (a.P + a.K - w16 + 63) >> 6;   r.ts1 = (a.Nkv - w16 - 16) >> 6;
+  return r;
+}
+
+// 16 consecutive rows of one source tensor starting at source row `row0`: scalar bases, the lane's
+// constant offsets, no per-lane address arithmetic.  The lane offsets kgo / vgo count rows from the
+// start of the tile, hence the step back by the wave's 16*wave rows.
+template <int D>
+__device__ __forceinline__ void issue_slab(const Lane<D>& L, unsigned sk, const uint16_t* kp, const uint16_t* vp, long long row0) {
+  using S = Shape<D>;
+  const unsigned char* kt = reinterpret_cast<const unsigned char*>(kp) + (row0 - 16 * L.wave) * S::ROWB;
+  const unsigned char* vt = reinterpret_cast<const unsigned char*>(vp) + (row0 - 16 * L.wave) * S::ROWB;
+  static_assert(S::IPT == 4 || S::IPT == 2, "transfers per slab");
+  dma16_sbase_off<0>(sk, kt, L.kgo[0]);
+  dma16_sbase_off<S::RPI * S::ROWB>(sk, kt, L.kgo[1]);
+  if (S::IPT == 4) {
+    dma16_sbase_off<2 * S::RPI * S::ROWB>(sk, kt, L.kgo[S::IPT == 4 ? 2 : 0]);
+    dma16_sbase_off<3 * S::RPI * S::ROWB>(sk, kt, L.kgo[S::IPT == 4 ? 3 : 0]);
+  }
+  dma16_sbase_off<S::VBASE>(sk, vt, L.vgo[0]);
+  dma16_sbase_off<S::VBASE + S::RPI * S::ROWB>(sk, vt, L.vgo[1]);
+  if (S::IPT == 4) {
+    dma16_sbase_off<S::VBASE + 2 * S::RPI * S::ROWB>(sk, vt, L.vgo[S::IPT == 4 ? 2 : 0]);
+    dma16_sbase_off<S::VBASE + 3 * S::RPI * S::ROWB>(sk, vt, L.vgo[S::IPT == 4 ? 3 : 0]);
   }
 }
 
@@ -126,32 +179,23 @@ __device__ __forceinline__ void load_keep_ahead(const AttnArgs& a, int wave, int
 // rows 16*wave .. 16*wave+15 of the tile.  `ka` holds the keep_idx bounds of these rows on entry and
 // those of the next tile on return.
 template <int D>
-__device__ __forceinline__ void issue_tile(const AttnArgs& a, const Lane<D>& L, const uint16_t* kc, const uint16_t* vc,
+__device__ __forceinline__ void issue_tile(const AttnArgs& a, const Lane<D>& L, const SlabRanges& R,
+                                           const uint16_t* kc, const uint16_t* vc,
                                            const uint16_t* kb, const uint16_t* vb, const uint16_t* ks, const uint16_t* vs,
                                            int tile, int stage, KeepAhead& ka) {
   using S = Shape<D>;
   const unsigned sk = L.lds_base + stage * S::TILEB + 16 * L.wave * S::ROWB;
   const unsigned sv = sk + S::VBASE;
   const int r0 = tile * kKeyTile + 16 * L.wave;    // uniform: first of the wave's 16 rows
-  const int r15 = r0 + 15;
-  // Uniform classification of the wave's rows.  Sixteen consecutive rows of one source tensor (the
+  // Uniform classification of the wave's slab.  Sixteen consecutive rows of one source tensor (the
   // cache, the block, or a run of the suffix that keep_idx maps to consecutive rows: increasing
-  // indices whose ends differ by 15) are one contiguous 16-row slab: a scalar base plus the lane's
-  // constant offset, no per-lane address arithmetic.
-  const bool in_cache = r15 < a.P;
-  const bool in_block = r0 >= a.P && r15 < a.P + a.K;
-  const bool in_sfx = r0 >= a.P + a.K && r15 < a.Nkv && ka.last - ka.first == 15;
-  if (in_cache || in_block || in_sfx) {
-    const long long row0 = in_cache ? r0 : (in_block ? r0 - a.P : ka.first);
-    const uint16_t* kp = in_cache ? kc : (in_block ? kb : ks);
-    const uint16_t* vp = in_cache ? vc : (in_block ? vb : vs);
-    // the lane offsets kgo / vgo count rows from the start of the tile: step back by the wave's 16*wave rows
-    const unsigned char* kt = reinterpret_cast<const unsigned char*>(kp) + (row0 - 16 * L.wave) * S::ROWB;
-    const unsigned char* vt = reinterpret_cast<const unsigned char*>(vp) + (row0 - 16 * L.wave) * S::ROWB;
-#pragma unroll
-    for (int j = 0; j < S::IPT; ++j) dma16_sbase(sk + j * S::RPI * S::ROWB, kt, L.kgo[j]);
-#pragma unroll
-    for (int j = 0; j < S::IPT; ++j) dma16_sbase(sv + j * S::RPI * S::ROWB, vt, L.vgo[j]);
+  // indices whose ends differ by 15) are one contiguous slab.
+  if (tile <= R.tc) {
+    issue_slab<D>(L, sk, kc, vc, r0);
+  } else if (tile >= R.tb0 && tile <= R.tb1) {
+    issue_slab<D>(L, sk, kb, vb, r0 - a.P);
+  } else if (tile >= R.ts0 && tile <= R.ts1 && ka.last - ka.first == 15) {
+    issue_slab<D>(L, sk, ks, vs, ka.first);
   } else {
     // rows from more than one place, a gap in keep_idx, the ragged tail: per-row addresses without a
     // divergent branch.  keep_idx is read through the constant address space with uniform indices
@@ -367,9 +411,9 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   const long long bh = (long long)b * a.Hkv + kvh;
   // base pointers of this (batch, KV head); kept as separate values (in a struct the compiler turns
   // the three-way source select of the gather path into a table lookup in scratch memory)
-  const uint16_t* kc = a.k_cache + bh * a.cap * D;  const uint16_t* vc = a.v_cache + bh * a.cap * D;
-  const uint16_t* kb = a.k_block + bh * a.K * D;    const uint16_t* vb = a.v_block + bh * a.K * D;
-  const uint16_t* ks = a.k_suffix + bh * a.S * D;   const uint16_t* vs = a.v_suffix + bh * a.S * D;
+  const uint16_t* kc = uniform_ptr(a.k_cache + bh * a.cap * D);  const uint16_t* vc = uniform_ptr(a.v_cache + bh * a.cap * D);
+  const uint16_t* kb = uniform_ptr(a.k_block + bh * a.K * D);    const uint16_t* vb = uniform_ptr(a.v_block + bh * a.K * D);
+  const uint16_t* ks = uniform_ptr(a.k_suffix + bh * a.S * D);   const uint16_t* vs = uniform_ptr(a.v_suffix + bh * a.S * D);
 #pragma unroll
   for (int j = 0; j < IPT; ++j) {
     const int r = 16 * wave + RPI * j + lane / CPR, q = lane % CPR;
@@ -388,9 +432,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   }
 
   // ---- the first tile goes in flight, then the query rows
+  const SlabRanges R = slab_ranges(a, wave);
   KeepAhead ka;
   load_keep_ahead(a, wave, t0, ka);
-  issue_tile<D>(a, L, kc, vc, kb, vb, ks, vs, t0, 0, ka);
+  issue_tile<D>(a, L, R, kc, vc, kb, vb, ks, vs, t0, 0, ka);
 
   // ---- query rows of this wave, as MFMA B operands (lane: row l16, d = 32*s + 8*G .. +7)
   const int row_base = qt * (64 * RB) + wave * (16 * RB);
@@ -424,12 +469,12 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   for (int t = t0; t < t1; t += 2) {
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
-    if (t + 1 < t1) issue_tile<D>(a, L, kc, vc, kb, vb, ks, vs, t + 1, 1, ka);
+    if (t + 1 < t1) issue_tile<D>(a, L, R, kc, vc, kb, vb, ks, vs, t + 1, 1, ka);
     compute_tile<D, RB, 0>(a, L, lds, t, qreg, o, m, lsum);
     if (t + 1 >= t1) break;
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
-    if (t + 2 < t1) issue_tile<D>(a, L, kc, vc, kb, vb, ks, vs, t + 2, 0, ka);
+    if (t + 2 < t1) issue_tile<D>(a, L, R, kc, vc, kb, vb, ks, vs, t + 2, 0, ka);
     compute_tile<D, RB, 1>(a, L, lds, t + 1, qreg, o, m, lsum);
   }
 
