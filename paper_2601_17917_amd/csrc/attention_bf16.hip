@@ -68,17 +68,32 @@ __device__ __forceinline__ void dma16_sbase(unsigned lds_addr, const void* sbase
   const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)p);
   const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(p >> 32));
   const unsigned long long pu = ((unsigned long long)hi << 32) | lo;
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(pu) : "memory", "m0");
 }
-// the same with the LDS address given as scalar base + compile-time offset (one scalar add into m0)
-template <int OFF>
-__device__ __forceinline__ void dma16_sbase_off(unsigned lds_base, const void* sbase, unsigned voff) {
-  asm volatile("s_add_u32 m0, %0, %3\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds_base), "v"(voff), "s"(sbase), "n"(OFF) : "memory", "m0", "scc");
+// One 16-row slab of one tensor: NT transfers of 1 KiB to consecutive KiB of LDS from one scalar
+// base.  m0 (the LDS base of a transfer) is written once: the instruction's immediate offset moves
+// the LDS address and the global address alike, so transfer j carries offset j KiB and its lane offset
+// voffj has those j KiB taken off beforehand.  One wait state separates the write of m0 from the
+// first transfer that reads it.
+template <int NT>
+__device__ __forceinline__ void dma_slab(unsigned lds_addr, const void* sbase, const unsigned (&voffj)[4]) {
+  static_assert(NT == 2 || NT == 4, "transfers per slab");
+  if (NT == 4)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %2, %1\n\t"
+                 "global_load_lds_dwordx4 %3, %1 offset:1024\n\t"
+                 "global_load_lds_dwordx4 %4, %1 offset:2048\n\t"
+                 "global_load_lds_dwordx4 %5, %1 offset:3072"
+                 :: "s"(lds_addr), "s"(sbase), "v"(voffj[0]), "v"(voffj[1]), "v"(voffj[2]), "v"(voffj[3]) : "memory", "m0");
+  else
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %2, %1\n\t"
+                 "global_load_lds_dwordx4 %3, %1 offset:1024"
+                 :: "s"(lds_addr), "s"(sbase), "v"(voffj[0]), "v"(voffj[1]) : "memory", "m0");
 }
 __device__ __forceinline__ void dma16_vaddr(unsigned lds_addr, const void* vaddr) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(vaddr) : "memory", "m0");
 }
 // A pointer that is the same in every lane, moved into a scalar register pair (64-bit address
@@ -117,6 +132,7 @@ template <int D> struct Shape {
 // Per-lane constants of the K/V stream
 template <int D> struct Lane {
   unsigned kgo[Shape<D>::IPT], vgo[Shape<D>::IPT]; // byte offset of the lane's (swizzled) source chunk within a tile
+  unsigned kgj[4], vgj[4];                         // the same minus j KiB (see dma_slab); entries past IPT unused
   unsigned kro[Shape<D>::NS], vro[Shape<D>::NDB];  // LDS read bases (bytes), before compile-time offsets
   unsigned lds_base; int wave, lane, G;
 };
@@ -160,19 +176,9 @@ __device__ __forceinline__ void issue_slab(const Lane<D>& L, unsigned sk, const 
   using S = Shape<D>;
   const unsigned char* kt = reinterpret_cast<const unsigned char*>(kp) + (row0 - 16 * L.wave) * S::ROWB;
   const unsigned char* vt = reinterpret_cast<const unsigned char*>(vp) + (row0 - 16 * L.wave) * S::ROWB;
-  static_assert(S::IPT == 4 || S::IPT == 2, "transfers per slab");
-  dma16_sbase_off<0>(sk, kt, L.kgo[0]);
-  dma16_sbase_off<S::RPI * S::ROWB>(sk, kt, L.kgo[1]);
-  if (S::IPT == 4) {
-    dma16_sbase_off<2 * S::RPI * S::ROWB>(sk, kt, L.kgo[S::IPT == 4 ? 2 : 0]);
-    dma16_sbase_off<3 * S::RPI * S::ROWB>(sk, kt, L.kgo[S::IPT == 4 ? 3 : 0]);
-  }
-  dma16_sbase_off<S::VBASE>(sk, vt, L.vgo[0]);
-  dma16_sbase_off<S::VBASE + S::RPI * S::ROWB>(sk, vt, L.vgo[1]);
-  if (S::IPT == 4) {
-    dma16_sbase_off<S::VBASE + 2 * S::RPI * S::ROWB>(sk, vt, L.vgo[S::IPT == 4 ? 2 : 0]);
-    dma16_sbase_off<S::VBASE + 3 * S::RPI * S::ROWB>(sk, vt, L.vgo[S::IPT == 4 ? 3 : 0]);
-  }
+  static_assert(S::RPI * S::ROWB == 1024, "a transfer moves 1 KiB");
+  dma_slab<S::IPT>(sk, kt, L.kgj);
+  dma_slab<S::IPT>(sk + S::VBASE, vt, L.vgj);
 }
 
 // Puts key tile `tile` in flight into ring stage `stage`: 2 * IPT transfers per wave, which moves
@@ -419,7 +425,11 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     const int r = 16 * wave + RPI * j + lane / CPR, q = lane % CPR;
     L.kgo[j] = r * ROWB + ((q ^ ((r / R256) % CPR)) << 4);
     L.vgo[j] = r * ROWB + ((q ^ (2 * ((r / R256) % (CPR / 2)))) << 4);
+    L.kgj[j] = L.kgo[j] - 1024 * j;                // r * ROWB >= j KiB: stays non-negative
+    L.vgj[j] = L.vgo[j] - 1024 * j;
   }
+#pragma unroll
+  for (int j = IPT; j < 4; ++j) { L.kgj[j] = 0; L.vgj[j] = 0; }
   {
     const int fk = (D == 128) ? l16 : (l16 >> 1);
 #pragma unroll
