@@ -45,7 +45,7 @@ struct AttnArgs {
   float* ws_ml;   // [group][virtual row][split][2]   (running max in log2 units, sum)
   int B, Hq, Hkv, g, P, cap, K, S, n_keep, Nq, Nkv, Rtot;
   int nsplit, tiles_per_split, key_tiles, q_tiles, n_units;
-  float scale_log2;
+  float scale_log2, inv_scale_log2;
 };
 
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -262,7 +262,7 @@ __device__ __forceinline__ s16x8 read_vt(const unsigned char* lds, const Lane<D>
 template <int D, int RB, int STAGE>
 __device__ __forceinline__ void compute_tile(const AttnArgs& a, const Lane<D>& L, const unsigned char* lds, int t,
                                              const bf16x8 (&qreg)[RB][Shape<D>::NS], f32x4 (&o)[RB][Shape<D>::NDB],
-                                             float (&m)[RB], float (&lsum)[RB]) {
+                                             float (&m)[RB], float (&thr)[RB], float (&lsum)[RB]) {
   using S = Shape<D>;
   constexpr int NS = S::NS, NDB = S::NDB;
   constexpr bool kMfmaRowSum = (RB == 1);
@@ -314,26 +314,30 @@ __device__ __forceinline__ void compute_tile(const AttnArgs& a, const Lane<D>& L
     mx = fmaxf(fmaxf(mx, sacc[rb][2][3]), sacc[rb][3][0]);
     mx = fmaxf(fmaxf(mx, sacc[rb][3][1]), sacc[rb][3][2]);
     mx = fmaxf(mx, sacc[rb][3][3]);
-    // across the four 16-lane groups that hold the other keys of the same query row: VALU lane swaps
-    {
-      const auto s16 = __builtin_amdgcn_permlane16_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-      mx = fmaxf(__uint_as_float(s16[0]), __uint_as_float(s16[1]));
-      const auto s32 = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-      mx = fmaxf(__uint_as_float(s32[0]), __uint_as_float(s32[1]));
-    }
     // Lazy reference: the row's reference exponent only moves when the new maximum exceeds it by
     // more than 8 (log2 units), so probabilities stay below 2^8 (exact in fp32 sums, same relative
     // precision in bf16) and the accumulator rescale below runs in a handful of tiles instead of
     // most of them.  The final O / l is unchanged: both carry the same reference.
-    const float cand = mx * a.scale_log2;                      // scale_log2 > 0
-    const float m_new = (cand > m[rb] + 8.0f) ? cand : m[rb];
-    if (__builtin_amdgcn_ballot_w64(m_new != m[rb]) != 0) {    // uniform branch
-      const float corr = exp2_fast(m[rb] - m_new);
+    // A row's maximum exceeds the reference by 8 iff the in-lane maximum of one of its four lanes
+    // does, so the common case needs no cross-lane reduction at all: one wave-wide test against
+    // thr = (m + 8) / scale_log2 (kept beside m; a rounding-sized miss of the test only lets a
+    // probability reach 2^8 (1 + eps), a spurious hit leaves m unchanged).
+    if (__builtin_amdgcn_ballot_w64(mx > thr[rb]) != 0) {      // uniform branch
+      // across the four 16-lane groups that hold the other keys of the same query row: VALU lane swaps
+      const auto s16 = __builtin_amdgcn_permlane16_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+      mx = fmaxf(__uint_as_float(s16[0]), __uint_as_float(s16[1]));
+      const auto s32 = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+      mx = fmaxf(__uint_as_float(s32[0]), __uint_as_float(s32[1]));
+      const float cand = mx * a.scale_log2;
+      const float m_up = (cand > m[rb] + 8.0f) ? cand : m[rb];
+      const float corr = exp2_fast(m[rb] - m_up);  // 1 for the rows that stay
       lsum[rb] *= corr;
 #pragma unroll
       for (int db = 0; db < NDB; ++db) o[rb][db] *= corr;
-      m[rb] = m_new;
+      m[rb] = m_up;
+      thr[rb] = (m_up + 8.0f) * a.inv_scale_log2;
     }
+    const float m_new = m[rb];
     float ps = 0.f;
 #pragma unroll
     for (int kb4 = 0; kb4 < 4; ++kb4)
@@ -463,10 +467,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   }
 
   f32x4 o[RB][NDB];
-  float m[RB], lsum[RB];
+  float m[RB], thr[RB], lsum[RB];
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
-    m[rb] = kNegBigA; lsum[rb] = 0.f;
+    m[rb] = kNegBigA; thr[rb] = kNegBigA; lsum[rb] = 0.f;
 #pragma unroll
     for (int db = 0; db < NDB; ++db) o[rb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
@@ -480,12 +484,12 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
     if (t + 1 < t1) issue_tile<D>(a, L, R, kc, vc, kb, vb, ks, vs, t + 1, 1, ka);
-    compute_tile<D, RB, 0>(a, L, lds, t, qreg, o, m, lsum);
+    compute_tile<D, RB, 0>(a, L, lds, t, qreg, o, m, thr, lsum);
     if (t + 1 >= t1) break;
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
     if (t + 2 < t1) issue_tile<D>(a, L, R, kc, vc, kb, vb, ks, vs, t + 2, 0, ka);
-    compute_tile<D, RB, 1>(a, L, lds, t + 1, qreg, o, m, lsum);
+    compute_tile<D, RB, 1>(a, L, lds, t + 1, qreg, o, m, thr, lsum);
   }
 
   // ---- epilogue
@@ -644,6 +648,7 @@ hipError_t launch_attention_bf16(const sdllm_attn_params& p, const AttnPlan& pl,
   a.q_tiles = pl.q_tiles; a.n_units = p.B * p.Hkv * pl.kv_splits;
   const float scale = p.scale > 0.f ? p.scale : 1.0f / sqrtf((float)p.D);
   a.scale_log2 = scale * kLog2eA;
+  a.inv_scale_log2 = 1.0f / a.scale_log2;
   const size_t rows = (size_t)p.B * p.Hq * a.Nq;
   a.ws_o = (float*)workspace;
   a.ws_ml = a.ws_o ? a.ws_o + rows * pl.kv_splits * (size_t)p.D : nullptr;
