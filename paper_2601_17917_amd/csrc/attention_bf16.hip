@@ -131,8 +131,9 @@ template <int D> struct Shape {
 
 // Per-lane constants of the K/V stream
 template <int D> struct Lane {
-  unsigned kgo[Shape<D>::IPT], vgo[Shape<D>::IPT]; // byte offset of the lane's (swizzled) source chunk within a tile
-  unsigned kgj[4], vgj[4];                         // the same minus j KiB (see dma_slab); entries past IPT unused
+  // byte offset of the lane's (swizzled) source chunk of transfer j within a tile, minus j KiB (see
+  // dma_slab); entries past IPT unused
+  unsigned kgj[4], vgj[4];
   unsigned kro[Shape<D>::NS], vro[Shape<D>::NDB];  // LDS read bases (bytes), before compile-time offsets
   unsigned lds_base; int wave, lane, G;
 };
@@ -169,7 +170,7 @@ __device__ __forceinline__ SlabRanges slab_ranges(const AttnArgs& a, int wave) {
 }
 
 // 16 consecutive rows of one source tensor starting at source row `row0`: scalar bases, the lane's
-// constant offsets, no per-lane address arithmetic.  The lane offsets kgo / vgo count rows from the
+// constant offsets, no per-lane address arithmetic.  The lane offsets kgj / vgj count rows from the
 // start of the tile, hence the step back by the wave's 16*wave rows.
 template <int D>
 __device__ __forceinline__ void issue_slab(const Lane<D>& L, unsigned sk, const uint16_t* kp, const uint16_t* vp, long long row0) {
@@ -234,8 +235,8 @@ __device__ __forceinline__ void issue_tile(const AttnArgs& a, const Lane<D>& L, 
       const uint16_t* kp = in_c ? kc : (in_b ? kb : ks);
       const uint16_t* vp = in_c ? vc : (in_b ? vb : vs);
       const long long off = (long long)(in_c ? r : (in_b ? r - a.P : kidx[j])) * D;
-      kpp[j] = reinterpret_cast<const unsigned char*>(kp + off) + (L.kgo[j] - (16 * L.wave + rl) * S::ROWB);
-      vpp[j] = reinterpret_cast<const unsigned char*>(vp + off) + (L.vgo[j] - (16 * L.wave + rl) * S::ROWB);
+      kpp[j] = reinterpret_cast<const unsigned char*>(kp + off) + (L.kgj[j] + 1024 * j - (16 * L.wave + rl) * S::ROWB);
+      vpp[j] = reinterpret_cast<const unsigned char*>(vp + off) + (L.vgj[j] + 1024 * j - (16 * L.wave + rl) * S::ROWB);
     }
 #pragma unroll
     for (int j = 0; j < S::IPT; ++j) dma16_vaddr(sk + j * S::RPI * S::ROWB, kpp[j]);
@@ -427,10 +428,9 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
   for (int j = 0; j < IPT; ++j) {
     const int r = 16 * wave + RPI * j + lane / CPR, q = lane % CPR;
-    L.kgo[j] = r * ROWB + ((q ^ ((r / R256) % CPR)) << 4);
-    L.vgo[j] = r * ROWB + ((q ^ (2 * ((r / R256) % (CPR / 2)))) << 4);
-    L.kgj[j] = L.kgo[j] - 1024 * j;                // r * ROWB >= j KiB: stays non-negative
-    L.vgj[j] = L.vgo[j] - 1024 * j;
+    // r * ROWB >= j KiB, so the offsets stay non-negative
+    L.kgj[j] = r * ROWB + ((q ^ ((r / R256) % CPR)) << 4) - 1024 * j;
+    L.vgj[j] = r * ROWB + ((q ^ (2 * ((r / R256) % (CPR / 2)))) << 4) - 1024 * j;
   }
 #pragma unroll
   for (int j = IPT; j < 4; ++j) { L.kgj[j] = 0; L.vgj[j] = 0; }

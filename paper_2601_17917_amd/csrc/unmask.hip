@@ -191,6 +191,9 @@ __device__ __forceinline__ void commit_sequence(const UnmaskArgs& a, int b, floa
         my_masked++;
         if (a.confidence) a.confidence[pos] = c;
         xhat_s[i] = idx;
+        // the selection below works on a strictly positive finite number: a row of NaN logits (garbage
+        // in) ranks last instead of leaving the fallback without a candidate
+        if (!(c > 0.f)) c = 1e-38f;
       }
       conf_s[i] = c;
     }
@@ -210,8 +213,10 @@ __device__ __forceinline__ void commit_sequence(const UnmaskArgs& a, int b, floa
   float bc = -1.f; int bi = 0x7fffffff; int my_thr = 0;
   for (int i = tid; i < K; i += kRowThreads) {
     const long long pos = (long long)b * K + i;
-    if (a.masked[pos] == 0) continue;
+    // pass 1 left 0 for an unmasked position and 1 / sum > 0 for a masked one: no second look at the
+    // mask bytes (one memory round trip less)
     const float c = conf_s[i];
+    if (c == 0.f) continue;
     if ((double)c >= tau) {
       const int xhat = xhat_s[i];
       a.tokens[pos] = xhat;

@@ -211,3 +211,29 @@ def test_unmask_full_size_configs(gpu_lib, name):
     print(f"{name}: gap<1e-3={n_gap} in-band={n_band} skipped_seqs={skip} committed={int(want['n_committed'].sum())} "
           f"done={int(want['block_done'].sum())}/{w.B}")
     assert skip <= w.B // 8
+
+
+def test_unmask_non_finite_logits_stay_in_bounds(gpu_lib):
+    """NaN / inf logits are outside the method's domain (the oracle defines nothing for them); the
+    kernel must still stay in bounds and keep its invariants: exactly the fallback's single commit per
+    sequence when nothing finite passes the threshold, a valid position, counters consistent."""
+    B, K, V = 3, 8, 777 + 7
+    g = np.random.Generator(np.random.Philox(key=77))
+    logits = g.standard_normal((B, K, V), dtype=np.float32) * 3
+    masked = np.ones((B, K), dtype=np.uint8)
+    masked[1, :3] = 0
+    logits[0] = np.nan                          # every row of sequence 0
+    logits[1, 4, 10] = np.inf                   # one +inf in one row of sequence 1
+    logits[2, :, ::2] = -np.inf                 # -inf is a legitimate "impossible token": finite results
+    tokens = np.full((B, K), wl.MASK_TOKEN, dtype=np.int32)
+    got = run_gpu(gpu_lib, logits, tokens, masked, 2.0, 0.0)      # tau0 > 1: only the fallback can commit
+    assert (got["n_committed"] == 1).all()
+    for b in range(B):
+        newly = (masked[b] != 0) & (got["masked"][b] == 0)
+        assert newly.sum() == 1
+        assert (got["masked"][b][masked[b] == 0] == 0).all()
+    assert got["masked"][0, 0] == 0             # all-NaN sequence: the lowest masked position is taken
+    assert (got["block_done"] == 0).all()
+    # the sequence with -inf entries is inside the domain: compare it with the oracle
+    want = oracle_unmask(wl.to_f64(logits[2:3]), tokens[2:3], masked[2:3], 2.0, 0.0)
+    assert (got["tokens"][2] == want["tokens"][0]).all() and (got["masked"][2] == want["masked"][0]).all()
