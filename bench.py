@@ -43,6 +43,10 @@ def parse_args():
                     help="bracket the dominant kernel with HIP events on every n-th timed step (an event pair costs "
                          "about as much as a small kernel, so bracketing every step would distort the step time)")
     ap.add_argument("--kv-splits", type=int, default=0, help="force the attention key-range split count")
+    ap.add_argument("--kv-copies", type=int, default=0,
+                    help="single-layer workloads: number of distinct K/V/Q sets the steps cycle through, so that a "
+                         "step reads its operands from HBM and not from the 256 MB last-level cache a previous step "
+                         "left them in (0 = as many as make the sets exceed 512 MB, at most 64)")
     return ap.parse_args()
 
 
@@ -58,7 +62,7 @@ def to_dev(x):
 class Step:
     """All device buffers of one workload, allocated before the timed region."""
 
-    def __init__(self, sd, w: wl.Workload, seed: int, n_states: int, kv_splits: int = 0):
+    def __init__(self, sd, w: wl.Workload, seed: int, n_states: int, kv_splits: int = 0, kv_copies: int = 0):
         import torch
         self.sd, self.w = sd, w
         self.layers = []
@@ -68,6 +72,14 @@ class Step:
             else:
                 t = {k: to_dev(v) for k, v in wl.make_attention_inputs(w, seed, layer).items()}
             self.layers.append(t)
+        # A real model walks through the caches of all its layers between two visits of the same one; a
+        # single-layer workload that re-read one set of operands every step would find them in the
+        # last-level cache.  Cycle through enough distinct sets (same shapes and law, drawn on the device).
+        self.copies = 1
+        if w.n_layers == 1 and w.dtype == "bf16":
+            self.copies = kv_copies if kv_copies > 0 else min(64, max(1, -(-(512 << 20) // w.attn_bytes())))
+            for c in range(1, self.copies):
+                self.layers.append(wl.make_attention_inputs_device(w, seed, 1000 + c))
         dt = self.layers[0]["q_block"].dtype
         self.out = torch.empty((w.B, w.Hq, w.Nq, w.D), dtype=dt, device="cuda")
         self.attn_p = sd.attn_params(sd.FP32 if w.dtype == "fp32" else sd.BF16, w.B, w.Hq, w.Hkv, w.D, w.P, w.cap,
@@ -95,7 +107,7 @@ class Step:
             self.k_blocks = torch.stack([t["k_block"] for t in self.layers])
             self.v_blocks = torch.stack([t["v_block"] for t in self.layers])
         else:
-            t = self.layers[0]
+            t = self.layers[0]                           # the append goes into the first set's cache
             self.k_caches, self.v_caches = t["k_cache"][None], t["v_cache"][None]
             self.k_blocks, self.v_blocks = t["k_block"][None], t["v_block"][None]
 
@@ -112,14 +124,18 @@ class Step:
         torch.cuda.synchronize()
 
     def run(self, i: int, events=None):
+        if self.w.n_layers == 1:
+            calls = (self.attention[i % self.copies],)
+        else:
+            calls = self.attention
         if events is not None:
             events[0].record()
-            self.attention[0]()
+            calls[0]()
             events[1].record()
-            for call in self.attention[1:]:
+            for call in calls[1:]:
                 call()
         else:
-            for call in self.attention:
+            for call in calls:
                 call()
         self.unmask[i]()
         self.append()
@@ -215,7 +231,7 @@ def main():
     sd.load_library()                     # raises if the HIP library is missing: no fallback
     w = wl.WORKLOADS[args.workload]
     K, W = args.steps, args.warmup
-    st = Step(sd, w, args.seed, K + W, args.kv_splits)
+    st = Step(sd, w, args.seed, K + W, args.kv_splits, args.kv_copies)
 
     for i in range(W):
         st.run(i)
@@ -245,7 +261,13 @@ def main():
     bound = "mfma" if intensity > MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9) and w.dtype == "bf16" else "hbm"
 
     # ---- per-kernel timings outside the timed region (back-to-back launches of one call)
-    t_attn = time_kernel(st.attention[0])
+    rot = [0]
+
+    def attention_rotating():                           # same rotation as the timed steps
+        st.attention[rot[0] % len(st.attention)]()
+        rot[0] += 1
+
+    t_attn = time_kernel(attention_rotating)
     fresh = (st.tokens[0].clone(), st.masked[0].clone())
 
     def unmask_fresh():                                 # restore the state slot, then unmask it again
@@ -280,7 +302,8 @@ def main():
         "attention_call": {"ms": t_attn, "tflops": attn_flops / t_attn / 1e9, "gbs": attn_bytes / t_attn / 1e6,
                            "frac_mfma_peak": attn_flops / t_attn / 1e9 / MFMA_BF16_PEAK_TFLOPS,
                            "frac_hbm_peak": attn_bytes / t_attn / 1e6 / HBM_PEAK_GBS,
-                           "kv_splits": st.plan.kv_splits, "workgroups": st.plan.workgroups, "layers_per_step": w.n_layers},
+                           "kv_splits": st.plan.kv_splits, "workgroups": st.plan.workgroups, "layers_per_step": w.n_layers,
+                           "operand_sets_cycled": len(st.attention)},
         "unmask_call": {"ms": t_unm, "gbs": unmask_bytes / t_unm / 1e6, "frac_hbm_peak": unmask_bytes / t_unm / 1e6 / HBM_PEAK_GBS,
                         "masked_rows": masked_rows},
         "append_call": {"ms": t_app, "gbs": append_bytes / t_app / 1e6, "frac_hbm_peak": append_bytes / t_app / 1e6 / HBM_PEAK_GBS},
