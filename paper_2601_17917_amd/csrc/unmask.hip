@@ -16,7 +16,9 @@
 namespace sdllm {
 
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kNegBig = -3.0e38f;   // finite stand-in for -inf: keeps (m - m) free of NaN
+// finite stand-in for -inf as the initial running maximum: keeps (m - m) and m * log2(e) free of NaN
+// and overflow (a lane or a vector whose logits are all -inf then contributes exp2(-inf) = 0)
+constexpr float kNegBig = -1.0e30f;
 constexpr int kRowThreads = 256;
 constexpr int kVecPerIter = 4;        // 16-byte vectors in flight per lane
 
@@ -68,10 +70,37 @@ struct UnmaskArgs {
   float tau0, alpha; int r_extra_masked, r_extra_total; int eos_id; float tau_eos;
 };
 
+// Folds kVecPerIter unpacked vectors per lane (vector indices v0, v0 + 256, ...) into the lane's running
+// (max, sum of exp2 relative to that max, first vector holding the max).  Elements that do not exist
+// hold -inf: they never win the maximum and add exp2(-inf) = 0.
+template <int N>
+__device__ __forceinline__ void accumulate_trip(const float (&x)[kVecPerIter][N], int v0, float& m, float& s, int& mvec) {
+  float bm = m;
+#pragma unroll
+  for (int u = 0; u < kVecPerIter; ++u) {
+    float c = x[u][0];
+#pragma unroll
+    for (int j = 1; j < N; ++j) c = fmaxf(c, x[u][j]);
+    const bool up = c > bm;                // strict: the earliest vector keeps the maximum
+    mvec = up ? v0 + u * kRowThreads : mvec;
+    bm = up ? c : bm;
+  }
+  s *= fast_exp2((m - bm) * kLog2e);
+  m = bm;
+  const float ml = m * kLog2e;
+#pragma unroll
+  for (int u = 0; u < kVecPerIter; ++u) {
+#pragma unroll
+    for (int j = 0; j < N; ++j) s += fast_exp2(fmaf(x[u][j], kLog2e, -ml));
+  }
+}
+
 // Streams vocabulary slice `split` of one row; the merged triple of the workgroup ends in thread 0.
 template <typename T>
 __device__ __forceinline__ Partial reduce_row_slice(const UnmaskArgs& a, int row, int split, Partial* red) {
   constexpr int N = Vec<T>::N;
+  constexpr int kStride = kRowThreads * kVecPerIter;
+  constexpr unsigned kNegInfWord = (N == 8) ? 0xff80ff80u : 0xff800000u;   // -inf: two bf16 / one fp32
   const u32x4* __restrict__ base = reinterpret_cast<const u32x4*>(reinterpret_cast<const T*>(a.logits) + (long long)row * a.ld);
   const int v_begin = split * a.vec_per_split;
   const int v_end = min(v_begin + a.vec_per_split, a.nvec);
@@ -80,52 +109,44 @@ __device__ __forceinline__ Partial reduce_row_slice(const UnmaskArgs& a, int row
   float m = kNegBig, s = 0.f;
   int mvec = 0x7fffffff;                   // vector index holding this lane's maximum (first one)
 
-  // main loop: kVecPerIter vectors per lane per iteration, all loads issued before use
-  for (int v0 = v_begin + tid; v0 < v_end; v0 += kRowThreads * kVecPerIter) {
+  // The arithmetic, not the stream, bounds this kernel (its loads hide behind it), so the trips that
+  // lie wholly inside the slice and hold only complete vectors run without any bounds handling:
+  // unconditional loads, unpack, max, exp2-sum.  What is left (less than one trip, and the row's last
+  // vector when V is not a multiple of the vector length) goes through one guarded trip.
+  const bool ragged_row_end = (v_end == a.nvec) && (a.V % N != 0);             // uniform
+  const int n_bulk = max((v_end - (ragged_row_end ? 1 : 0)) - v_begin, 0) / kStride;   // uniform
+  int v0 = v_begin + tid;
+  for (int t = 0; t < n_bulk; ++t, v0 += kStride) {
     u32x4 r[kVecPerIter];
-    bool ok[kVecPerIter];
+#pragma unroll
+    for (int u = 0; u < kVecPerIter; ++u) r[u] = __builtin_nontemporal_load(base + v0 + u * kRowThreads);
+    float x[kVecPerIter][N];
+#pragma unroll
+    for (int u = 0; u < kVecPerIter; ++u) Vec<T>::unpack(r[u], x[u]);
+    accumulate_trip<N>(x, v0, m, s, mvec);
+  }
+  if (v0 - tid < v_end) {                  // uniform: the guarded trip
+    u32x4 r[kVecPerIter];
 #pragma unroll
     for (int u = 0; u < kVecPerIter; ++u) {
-      int v = v0 + u * kRowThreads;
-      ok[u] = v < v_end;
-      r[u] = ok[u] ? __builtin_nontemporal_load(base + v) : u32x4{0u, 0u, 0u, 0u};
+      r[u] = u32x4{kNegInfWord, kNegInfWord, kNegInfWord, kNegInfWord};
+      const int v = v0 + u * kRowThreads;
+      if (v < v_end) r[u] = __builtin_nontemporal_load(base + v);
     }
     float x[kVecPerIter][N];
-    float cm[kVecPerIter];
 #pragma unroll
-    for (int u = 0; u < kVecPerIter; ++u) {
-      Vec<T>::unpack(r[u], x[u]);
-      int v = v0 + u * kRowThreads;
-      // the last vector of the row may run past V: neutralise the excess elements
-      if (ok[u] && (v + 1) * N > a.V) {
+    for (int u = 0; u < kVecPerIter; ++u) Vec<T>::unpack(r[u], x[u]);
+    if (ragged_row_end) {                  // uniform: the row's last vector runs past V
 #pragma unroll
-        for (int j = 0; j < N; ++j) if (v * N + j >= a.V) x[u][j] = kNegBig;
+      for (int u = 0; u < kVecPerIter; ++u) {
+        const int v = v0 + u * kRowThreads;
+        if (v == a.nvec - 1) {
+#pragma unroll
+          for (int j = 0; j < N; ++j) if (v * N + j >= a.V) x[u][j] = -INFINITY;
+        }
       }
-      if (!ok[u]) {
-#pragma unroll
-        for (int j = 0; j < N; ++j) x[u][j] = kNegBig;
-      }
-      float c = x[u][0];
-#pragma unroll
-      for (int j = 1; j < N; ++j) c = fmaxf(c, x[u][j]);
-      cm[u] = c;
     }
-    float bm = m;
-#pragma unroll
-    for (int u = 0; u < kVecPerIter; ++u) {
-      int v = v0 + u * kRowThreads;
-      bool up = cm[u] > bm;              // strict: the earliest vector keeps the maximum
-      mvec = up ? v : mvec;
-      bm = up ? cm[u] : bm;
-    }
-    s *= fast_exp2((m - bm) * kLog2e);
-    m = bm;
-    const float ml = m * kLog2e;
-#pragma unroll
-    for (int u = 0; u < kVecPerIter; ++u) {
-#pragma unroll
-      for (int j = 0; j < N; ++j) s += fast_exp2(fmaf(x[u][j], kLog2e, -ml));
-    }
+    if (v0 < v_end) accumulate_trip<N>(x, v0, m, s, mvec);   // lanes past the end have nothing to add
   }
 
   // merge (max, sum, first vector holding the max) across the wave, then across the waves through
