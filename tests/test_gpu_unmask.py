@@ -237,3 +237,24 @@ def test_unmask_non_finite_logits_stay_in_bounds(gpu_lib):
     # the sequence with -inf entries is inside the domain: compare it with the oracle
     want = oracle_unmask(wl.to_f64(logits[2:3]), tokens[2:3], masked[2:3], 2.0, 0.0)
     assert (got["tokens"][2] == want["tokens"][0]).all() and (got["masked"][2] == want["masked"][0]).all()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_unmask_fallback_tie_takes_lowest_position(gpu_lib, dtype):
+    """Identical logit rows give bit-identical confidences on the GPU as well (same reduction order for
+    equal data), so the fallback tie is exact and must go to the lower position."""
+    B, K, V = 2, 40, 3001
+    lg = wl.make_logits(dtype, B, K, V, 3.0, False, seed=5, ld=3008)
+    masked = np.zeros((B, K), dtype=np.uint8)
+    masked[0, [3, 17, 30]] = 1
+    masked[1, [0, 39]] = 1
+    lg[0, 30] = lg[0, 17]
+    lg[0, 3] = lg[0, 17]                       # three-way tie: position 3 wins
+    lg[1, 39] = lg[1, 0]
+    tokens = np.full((B, K), 5, dtype=np.int32)
+    tokens[masked != 0] = wl.MASK_TOKEN
+    got = run_gpu(gpu_lib, lg, tokens, masked, 1.5, 0.0, V=V)
+    want = oracle_unmask(wl.to_f64(lg), tokens, masked, 1.5, 0.0, V=V)
+    assert (got["masked"] == want["masked"]).all() and (got["tokens"] == want["tokens"]).all()
+    assert got["masked"][0, 3] == 0 and got["masked"][0, 17] == 1 and got["masked"][1, 0] == 0
+    assert (got["n_committed"] == 1).all()

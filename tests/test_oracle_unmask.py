@@ -165,6 +165,20 @@ def test_tau_above_one_commits_exactly_one_per_sequence():
         assert got["fallback"][b] == 1
 
 
+def test_fallback_tie_takes_the_lowest_position():
+    """Two masked positions with identical logit rows have identical confidence; when no position
+    reaches the threshold the single fallback commit goes to the lower one (a stated reading)."""
+    logits, tokens, masked = _state(B=1, K=6, V=9, seed=11)
+    masked[:] = 0
+    masked[0, [1, 2, 4]] = 1
+    logits[0, 4] = logits[0, 2]                     # positions 2 and 4 tie ...
+    logits[0, 1] = logits[0, 2] * 0.5               # ... and position 1 is flatter, hence less confident
+    got = confidence_unmask(logits, tokens, masked, 1.5, 0.0)
+    assert got["confidence"][0, 2] == got["confidence"][0, 4] > got["confidence"][0, 1]
+    assert got["n_committed"][0] == 1 and got["fallback"][0] == 1
+    assert got["masked"][0].tolist() == [0, 1, 0, 0, 1, 0]
+
+
 def test_committed_never_remask_and_unmasked_untouched():
     logits, tokens, masked = _state(seed=6)
     got = confidence_unmask(logits, tokens, masked, 0.6, 0.3)
