@@ -16,4 +16,5 @@ from .attention import block_attention, compose_rows  # noqa: F401
 from .unmask import confidence_unmask, dynamic_threshold, row_confidence  # noqa: F401
 from .kv_append import kv_append  # noqa: F401
 from .suffix import suffix_keep_indices  # noqa: F401
+from .lm_head import lm_head_logits, lm_head_unmask  # noqa: F401
 from .rope import pruned_positions, rope_gathered, rope_rotate  # noqa: F401

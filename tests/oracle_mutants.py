@@ -54,6 +54,13 @@ MUTANTS = {
     "rope_frequency": ("rope", "theta = float(base) ** (-2.0 * i / D)", "theta = float(base) ** (-1.0 * i / D)"),
     "rope_pair_layout": ("rope", "if interleaved else (i, i + D // 2)", "if not interleaved else (i, i + D // 2)"),
     "rope_positions_shift_with_pruning": ("rope", "pos0 + K + keep_idx])", "pos0 + K + np.arange(len(keep_idx))])"),
+    # vocabulary projection (last map of Eq. 3)
+    "lm_head_transposed_weight": ("lm_head", "z[:, v0:v0 + Wc.shape[0]] = h2 @ Wc.T",
+                                  "z[:, v0:v0 + Wc.shape[0]] = (h2 @ Wc) if Wc.shape[0] == Wc.shape[1] else (h2 @ Wc.T)"),
+    "lm_head_slice_misplaced": ("lm_head", "z[:, v0:v0 + Wc.shape[0]] = h2 @ Wc.T", "z[:, V - v0 - Wc.shape[0]:V - v0] = h2 @ Wc.T"),
+    "lm_head_projects_unmasked_rows_only": ("lm_head", "m = np.asarray(masked) != 0", "m = np.asarray(masked) == 0"),
+    "lm_head_logits_rounded_to_bf16_grid": ("lm_head", "logits[m] = lm_head_logits(hidden[m], weight)",
+                                            "logits[m] = np.round(lm_head_logits(hidden[m], weight) * 8.0) / 8.0"),
 }
 
 # the pin files that must notice a mistake in the given oracle submodule
@@ -63,6 +70,7 @@ PIN_FILES = {
     "kv_append": ["test_oracle_kv_append.py"],
     "suffix": ["test_suffix_rule.py"],
     "rope": ["test_oracle_rope.py"],
+    "lm_head": ["test_oracle_lm_head.py"],
 }
 
 

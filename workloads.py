@@ -18,6 +18,7 @@ Layouts (row-major, last dim contiguous):
   k_block / v_block [B,Hkv,K,D]    k_suffix / v_suffix [B,Hkv,S,D]
   keep_idx [s] int32, strictly increasing, values in [0,S)
   logits [B,K,ld] (first V of each row valid), tokens [B,K] int32, masked [B,K] uint8
+  hidden [B,K,Hd] final hidden states, lm_weight [V,Hd] vocabulary projection (Hd = Hq*D)
 
 bf16 tensors are returned as uint16 bit patterns (round-to-nearest-even from
 fp32, done once here); `to_f64` widens either dtype exactly to float64.
@@ -117,6 +118,11 @@ class Workload:
     @property
     def Nkv(self) -> int:
         return self.P + self.K + self.n_keep
+
+    @property
+    def Hd(self) -> int:
+        """Model width (Hq * D): 4096 for the LLaDA-8B-shaped workloads, 3584 for the Dream-7B-shaped one."""
+        return self.Hq * self.D
 
     @property
     def scale(self) -> float:
@@ -278,6 +284,67 @@ def make_unmask_inputs(w: Workload, seed: int = 0, step: int = 0, ld: Optional[i
         "masked": masked,
         "eos_seen": np.zeros((w.B,), dtype=np.uint8),
     }
+
+
+def make_lm_head_inputs(w: Workload, seed: int = 0, step: int = 0, V: Optional[int] = None,
+                        Hd: Optional[int] = None) -> Dict[str, np.ndarray]:
+    """Final hidden states [B,K,Hd] ~ N(0,1) and a vocabulary projection [V,Hd] ~ N(0, (logit_std/sqrt(Hd))^2),
+    so that a logit (a dot product over Hd) follows the N(0, logit_std^2) law of make_logits.  With `boost`,
+    one seeded random token per row is made to stand out with a logit of u ~ U(18, 26): its projection row
+    is replaced by u * h / |h|^2, h being that row's hidden state (the other rows see ~u/sqrt(Hd) there)."""
+    V = w.V if V is None else V
+    Hd = w.Hd if Hd is None else Hd
+    g = _rng(seed, "hidden", step)
+    h = g.standard_normal(size=(w.B, w.K, Hd), dtype=np.float32)
+    hb = f32_to_bf16_bits(h)
+    gw = _rng(seed, "lm_weight", 0)
+    W = gw.standard_normal(size=(V, Hd), dtype=np.float32)
+    W *= np.float32(w.logit_std / np.sqrt(Hd))
+    if w.boost:
+        gb = _rng(seed, "boost", step)
+        tok = gb.integers(0, V, size=(w.B, w.K))
+        val = gb.uniform(18.0, 26.0, size=(w.B, w.K)).astype(np.float32)
+        hr = bf16_bits_to_f32(hb)
+        for b in range(w.B):
+            for k in range(w.K):
+                W[tok[b, k]] = val[b, k] * hr[b, k] / np.float32(np.dot(hr[b, k], hr[b, k]))
+    masked = make_masked(w, seed)
+    gt = _rng(seed, "tokens", 0)
+    tokens = gt.integers(0, V, size=(w.B, w.K)).astype(np.int32)
+    tokens[masked != 0] = MASK_TOKEN
+    return {"hidden": hb, "lm_weight": f32_to_bf16_bits(W), "tokens": tokens, "masked": masked,
+            "eos_seen": np.zeros((w.B,), dtype=np.uint8)}
+
+
+def make_lm_head_inputs_device(w: Workload, seed: int = 0, device: str = "cuda"):
+    """Device-side draw of make_lm_head_inputs' tensors for the full-size projection (V x Hd ~ 0.5e9
+    elements); same laws, torch's seeded device generator.  Returns bf16 tensors `hidden`, `lm_weight`
+    and the host-drawn `tokens` / `masked` state; parity checks copy them back for the oracle."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed((seed << 16) + 0x1ead)
+    h = torch.randn((w.B, w.K, w.Hd), generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+    W = torch.empty((w.V, w.Hd), device=device, dtype=torch.bfloat16)
+    rows = 16384
+    for v0 in range(0, w.V, rows):                     # fp32 draws in slices: bounded temporary
+        n = min(rows, w.V - v0)
+        x = torch.randn((n, w.Hd), generator=g, device=device, dtype=torch.float32)
+        W[v0:v0 + n] = (x * (w.logit_std / float(np.sqrt(w.Hd)))).to(torch.bfloat16)
+    if w.boost:
+        gb = _rng(seed, "boost", 0)
+        tok = torch.from_numpy(gb.integers(0, w.V, size=(w.B, w.K))).to(device)
+        val = torch.from_numpy(gb.uniform(18.0, 26.0, size=(w.B, w.K)).astype(np.float32)).to(device)
+        hf = h.float()
+        add = val[..., None] * hf / (hf * hf).sum(-1, keepdim=True)
+        for b in range(w.B):
+            for k in range(w.K):
+                W[tok[b, k]] = add[b, k].to(torch.bfloat16)
+    masked = make_masked(w, seed)
+    gt = _rng(seed, "tokens", 0)
+    tokens = gt.integers(0, w.V, size=(w.B, w.K)).astype(np.int32)
+    tokens[masked != 0] = MASK_TOKEN
+    return {"hidden": h, "lm_weight": W, "tokens": tokens, "masked": masked,
+            "eos_seen": np.zeros((w.B,), dtype=np.uint8)}
 
 
 def make_append_inputs(dtype: str, n_layers: int, B: int, Hkv: int, D: int, K: int, cap: int,
