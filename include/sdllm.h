@@ -7,6 +7,8 @@
  *                            queries over (prefix cache + active block + kept suffix) K/V
  *   sdllm_confidence_unmask  vocab softmax -> max-probability / argmax -> dynamic-threshold
  *                            commit -> block-done / EOS early-exit flags
+ *   sdllm_lm_head_unmask     the same unmask fed by the vocabulary projection of the hidden
+ *                            states instead of stored logits (the logits never reach memory)
  *   sdllm_kv_append          copy the finished block's K/V into the prefix cache
  *   sdllm_rope_gathered      rotary embedding of the pruned rows with their original position ids
  *   sdllm_suffix_keep_indices  (host) which suffix rows the attenuation-guided rule keeps
@@ -146,6 +148,45 @@ int sdllm_confidence_unmask(const sdllm_unmask_params* p,
                             int32_t* n_committed, uint8_t* block_done,
                             uint8_t* eos_seen,
                             void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Vocabulary projection fused into the unmask.  Paper Eq. 3 produces the logits z = f_theta(x); the
+ * last map of f_theta is the projection of the final hidden state onto the vocabulary,
+ * z_i = W h_i, and Eq. 4 reads z_i for the masked positions of the active block only.  This call
+ * forms those logits on the matrix cores (bf16 operands, fp32 accumulation) and reduces them to
+ * (max, sum of exp, argmax) on the fly: they are never stored.  Everything after that -- Eq. 4's
+ * confidence, Eq. 10, Eq. 9 with its fallback, Eq. 5, the block-done and EOS flags -- is exactly
+ * sdllm_confidence_unmask (same tie rules, same outputs).  Hidden rows of unmasked positions are
+ * not read.
+ *
+ *   B, K (1..4096; B*K <= 65536), V >= 1, Hd = model width (multiple of 32)
+ *   ld_h, ld_w  row strides of hidden / weight in elements (>= Hd, multiples of 8; B*K*ld_h < 2^31)
+ *   tau0 ... tau_eos as in sdllm_unmask_params.  bf16 only.
+ * ------------------------------------------------------------------------------------- */
+typedef struct sdllm_lm_head_params {
+  int32_t B, K, V, Hd;
+  int64_t ld_h, ld_w;
+  float tau0, alpha;
+  int32_t r_extra_masked, r_extra_total;
+  int32_t eos_id;
+  float tau_eos;
+} sdllm_lm_head_params;
+
+size_t sdllm_lm_head_unmask_workspace_bytes(const sdllm_lm_head_params* p);
+
+/*
+ *   hidden  [B,K,ld_h] bf16, read only (rows of masked positions)
+ *   weight  [V,ld_w]   bf16, read only: row v is the projection vector of token id v (no bias)
+ *   tokens, masked, confidence, n_committed, block_done, eos_seen: as for sdllm_confidence_unmask
+ * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP.
+ */
+int sdllm_lm_head_unmask(const sdllm_lm_head_params* p,
+                         const void* hidden, const void* weight,
+                         int32_t* tokens, uint8_t* masked,
+                         float* confidence,
+                         int32_t* n_committed, uint8_t* block_done,
+                         uint8_t* eos_seen,
+                         void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
  * KV append: the prefix K/V is kept and reused instead of recomputed (paper section 3.3,

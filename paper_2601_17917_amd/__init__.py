@@ -19,6 +19,7 @@ FP32, BF16 = 0, 1
 EXPORTED_SYMBOLS = (
     "sdllm_block_attention", "sdllm_attention_workspace_bytes", "sdllm_plan_attention",
     "sdllm_confidence_unmask", "sdllm_unmask_workspace_bytes",
+    "sdllm_lm_head_unmask", "sdllm_lm_head_unmask_workspace_bytes",
     "sdllm_kv_append", "sdllm_suffix_keep_indices", "sdllm_rope_gathered",
     "sdllm_status_string", "sdllm_last_error", "sdllm_version",
 )
@@ -34,6 +35,13 @@ class AttnParams(ctypes.Structure):
 class UnmaskParams(ctypes.Structure):
     _fields_ = [("dtype", ctypes.c_int32), ("B", ctypes.c_int32), ("K", ctypes.c_int32), ("V", ctypes.c_int32),
                 ("ld", ctypes.c_int64), ("tau0", ctypes.c_float), ("alpha", ctypes.c_float),
+                ("r_extra_masked", ctypes.c_int32), ("r_extra_total", ctypes.c_int32),
+                ("eos_id", ctypes.c_int32), ("tau_eos", ctypes.c_float)]
+
+
+class LmHeadParams(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("K", ctypes.c_int32), ("V", ctypes.c_int32), ("Hd", ctypes.c_int32),
+                ("ld_h", ctypes.c_int64), ("ld_w", ctypes.c_int64), ("tau0", ctypes.c_float), ("alpha", ctypes.c_float),
                 ("r_extra_masked", ctypes.c_int32), ("r_extra_total", ctypes.c_int32),
                 ("eos_id", ctypes.c_int32), ("tau_eos", ctypes.c_float)]
 
@@ -89,6 +97,10 @@ def load_library(path: Optional[str] = None):
     lib.sdllm_unmask_workspace_bytes.argtypes = [ctypes.POINTER(UnmaskParams)]
     lib.sdllm_confidence_unmask.restype = i32
     lib.sdllm_confidence_unmask.argtypes = [ctypes.POINTER(UnmaskParams)] + [vp] * 7 + [vp, sz, vp]
+    lib.sdllm_lm_head_unmask_workspace_bytes.restype = sz
+    lib.sdllm_lm_head_unmask_workspace_bytes.argtypes = [ctypes.POINTER(LmHeadParams)]
+    lib.sdllm_lm_head_unmask.restype = i32
+    lib.sdllm_lm_head_unmask.argtypes = [ctypes.POINTER(LmHeadParams)] + [vp] * 8 + [vp, sz, vp]
     lib.sdllm_suffix_keep_indices.restype = i32
     lib.sdllm_suffix_keep_indices.argtypes = [ctypes.c_int32] * 4 + [ctypes.POINTER(ctypes.c_int32), ctypes.c_int32,
                                                                     ctypes.POINTER(ctypes.c_int32)]
@@ -252,6 +264,62 @@ def bind_confidence_unmask(logits, tokens, masked, tau0: float, alpha: float, V:
             _ptr(block_done), _ptr(eos_seen), _ptr(workspace), ws_bytes, _stream(stream))
     keep = (p, logits, tokens, masked, confidence, n_committed, block_done, eos_seen, workspace)
     return BoundCall(load_library().sdllm_confidence_unmask, args, keep, (n_committed, block_done))
+
+
+# ---------------------------------------------------------------------------------------------
+def lm_head_params(B, K, V, Hd, ld_h, ld_w, tau0, alpha, r_extra_masked=0, r_extra_total=0, eos_id=-1,
+                   tau_eos=None) -> LmHeadParams:
+    return LmHeadParams(B, K, V, Hd, ld_h, ld_w, tau0, alpha, r_extra_masked, r_extra_total, eos_id,
+                        tau0 if tau_eos is None else tau_eos)
+
+
+def lm_head_unmask_workspace_bytes(p: LmHeadParams) -> int:
+    n = load_library().sdllm_lm_head_unmask_workspace_bytes(ctypes.byref(p))
+    if n == ctypes.c_size_t(-1).value:
+        raise SdllmError(ERR_INVALID_ARG, load_library().sdllm_last_error().decode())
+    return n
+
+
+def lm_head_unmask(*args, **kw):
+    """sdllm_lm_head_unmask.  hidden bf16 [B,K,Hd] (row stride ld_h), weight bf16 [V,Hd] (row stride ld_w);
+    tokens int32 [B,K] and masked uint8 [B,K] are updated in place.  Returns (n_committed int32 [B],
+    block_done uint8 [B]).  Signature: see bind_lm_head_unmask."""
+    return bind_lm_head_unmask(*args, **kw)()
+
+
+def bind_lm_head_unmask(hidden, weight, tokens, masked, tau0: float, alpha: float, confidence=None,
+                        n_committed=None, block_done=None, eos_seen=None, eos_id: int = -1,
+                        tau_eos: Optional[float] = None, r_extra_masked: int = 0, r_extra_total: int = 0,
+                        workspace=None, stream=None) -> BoundCall:
+    import torch
+    B, K, Hd = hidden.shape
+    V = weight.shape[0]
+    if hidden.dtype != torch.bfloat16 or weight.dtype != torch.bfloat16:
+        raise TypeError("lm_head_unmask: hidden and weight must be bfloat16")
+    if weight.shape[1] != Hd or hidden.stride(2) != 1 or weight.stride(1) != 1 or hidden.stride(0) != K * hidden.stride(1):
+        raise ValueError("lm_head_unmask: need hidden [B,K,Hd] and weight [V,Hd] with contiguous last dimension")
+    if not hidden.is_cuda or not weight.is_cuda:
+        raise ValueError("lm_head_unmask: hidden and weight must be device tensors")
+    _require(tokens, "tokens", torch.int32)
+    _require(masked, "masked", torch.uint8)
+    _require(confidence, "confidence", torch.float32)
+    _require(eos_seen, "eos_seen", torch.uint8)
+    if n_committed is None:
+        n_committed = torch.empty((B,), dtype=torch.int32, device=hidden.device)
+    if block_done is None:
+        block_done = torch.empty((B,), dtype=torch.uint8, device=hidden.device)
+    _require(n_committed, "n_committed", torch.int32)
+    _require(block_done, "block_done", torch.uint8)
+    p = lm_head_params(B, K, V, Hd, hidden.stride(1), weight.stride(0), tau0, alpha, r_extra_masked, r_extra_total,
+                       eos_id, tau_eos)
+    need = lm_head_unmask_workspace_bytes(p)
+    if workspace is None:
+        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=hidden.device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    args = (ctypes.byref(p), _ptr(hidden), _ptr(weight), _ptr(tokens), _ptr(masked), _ptr(confidence),
+            _ptr(n_committed), _ptr(block_done), _ptr(eos_seen), _ptr(workspace), ws_bytes, _stream(stream))
+    keep = (p, hidden, weight, tokens, masked, confidence, n_committed, block_done, eos_seen, workspace)
+    return BoundCall(load_library().sdllm_lm_head_unmask, args, keep, (n_committed, block_done))
 
 
 # ---------------------------------------------------------------------------------------------

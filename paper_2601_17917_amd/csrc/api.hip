@@ -68,6 +68,27 @@ int check_unmask_params(const sdllm_unmask_params* p) {
   return SDLLM_OK;
 }
 
+int check_lm_head_params(const sdllm_lm_head_params* p) {
+  if (!p) return fail(SDLLM_ERR_INVALID_ARG, "lm_head_unmask: params is NULL");
+  if (p->B < 1 || p->K < 1 || p->V < 1 || p->Hd < 1)
+    return fail(SDLLM_ERR_INVALID_ARG, "lm_head_unmask: B, K, V, Hd must be >= 1");
+  if (p->K > 4096) return fail(SDLLM_ERR_UNSUPPORTED, "lm_head_unmask: K (%d) > 4096", p->K);
+  if ((long long)p->B * p->K > 65536) return fail(SDLLM_ERR_UNSUPPORTED, "lm_head_unmask: B*K > 65536");
+  if (p->Hd % 32 != 0) return fail(SDLLM_ERR_UNSUPPORTED, "lm_head_unmask: Hd (%d) must be a multiple of 32", p->Hd);
+  if (p->ld_h < p->Hd || p->ld_w < p->Hd)
+    return fail(SDLLM_ERR_INVALID_ARG, "lm_head_unmask: ld_h (%lld) and ld_w (%lld) must be >= Hd (%d)",
+                (long long)p->ld_h, (long long)p->ld_w, p->Hd);
+  if (p->ld_h % 8 != 0 || p->ld_w % 8 != 0)
+    return fail(SDLLM_ERR_INVALID_ARG, "lm_head_unmask: ld_h and ld_w must be multiples of 8 elements (16 bytes)");
+  if ((long long)p->B * p->K * p->ld_h >= (1LL << 31))
+    return fail(SDLLM_ERR_UNSUPPORTED, "lm_head_unmask: B*K*ld_h must be below 2^31");
+  if (p->r_extra_masked < 0 || p->r_extra_total < p->r_extra_masked)
+    return fail(SDLLM_ERR_INVALID_ARG, "lm_head_unmask: need 0 <= r_extra_masked <= r_extra_total");
+  if (!(p->tau0 == p->tau0) || !(p->alpha == p->alpha) || !(p->tau_eos == p->tau_eos))
+    return fail(SDLLM_ERR_INVALID_ARG, "lm_head_unmask: tau0 / alpha / tau_eos is NaN");
+  return SDLLM_OK;
+}
+
 int check_append_params(const sdllm_append_params* p) {
   if (!p) return fail(SDLLM_ERR_INVALID_ARG, "kv_append: params is NULL");
   if (p->dtype != SDLLM_FP32 && p->dtype != SDLLM_BF16)
@@ -221,6 +242,32 @@ int sdllm_confidence_unmask(const sdllm_unmask_params* p, const void* logits,
   hipError_t e = sdllm::launch_unmask(*p, logits, tokens, masked, confidence, n_committed, block_done, eos_seen,
                                       workspace, (hipStream_t)stream);
   if (e != hipSuccess) return fail(SDLLM_ERR_HIP, "unmask: %s", hipGetErrorString(e));
+  return SDLLM_OK;
+}
+
+size_t sdllm_lm_head_unmask_workspace_bytes(const sdllm_lm_head_params* p) {
+  if (check_lm_head_params(p) != SDLLM_OK) return (size_t)-1;
+  return sdllm::lm_head_workspace_bytes(*p);
+}
+
+int sdllm_lm_head_unmask(const sdllm_lm_head_params* p, const void* hidden, const void* weight,
+                         int32_t* tokens, uint8_t* masked, float* confidence,
+                         int32_t* n_committed, uint8_t* block_done, uint8_t* eos_seen,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_lm_head_params(p);
+  if (rc != SDLLM_OK) return rc;
+  if (!hidden || !weight || !tokens || !masked || !n_committed || !block_done)
+    return fail(SDLLM_ERR_INVALID_ARG, "lm_head_unmask: hidden, weight, tokens, masked, n_committed, block_done must not be NULL");
+  if (!aligned16(hidden) || !aligned16(weight))
+    return fail(SDLLM_ERR_INVALID_ARG, "lm_head_unmask: hidden / weight is not 16-byte aligned");
+  const size_t need = sdllm::lm_head_workspace_bytes(*p);
+  if (!workspace || workspace_bytes < need)
+    return fail(SDLLM_ERR_WORKSPACE, "lm_head_unmask: workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : (size_t)0);
+  if ((reinterpret_cast<uintptr_t>(workspace) & 3u) != 0)
+    return fail(SDLLM_ERR_INVALID_ARG, "lm_head_unmask: workspace is not 4-byte aligned");
+  hipError_t e = sdllm::launch_lm_head_unmask(*p, hidden, weight, tokens, masked, confidence, n_committed,
+                                              block_done, eos_seen, workspace, (hipStream_t)stream);
+  if (e != hipSuccess) return fail(SDLLM_ERR_HIP, "lm_head_unmask: %s", hipGetErrorString(e));
   return SDLLM_OK;
 }
 

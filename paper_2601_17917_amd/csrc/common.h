@@ -45,6 +45,13 @@ hipError_t launch_unmask(const sdllm_unmask_params& p, const void* logits, int32
                          float* confidence, int32_t* n_committed, uint8_t* block_done, uint8_t* eos_seen,
                          void* workspace, hipStream_t stream);
 
+// ---- vocabulary projection fused into the unmask ----
+int lm_head_tiles(const sdllm_lm_head_params& p);   // vocabulary tiles = triples per row
+size_t lm_head_workspace_bytes(const sdllm_lm_head_params& p);
+hipError_t launch_lm_head_unmask(const sdllm_lm_head_params& p, const void* hidden, const void* weight,
+                                 int32_t* tokens, uint8_t* masked, float* confidence, int32_t* n_committed,
+                                 uint8_t* block_done, uint8_t* eos_seen, void* workspace, hipStream_t stream);
+
 // ---- rope ----
 hipError_t launch_rope(const sdllm_rope_params& p, const void* x_block, const void* x_suffix,
                        const int32_t* keep_idx, void* out_block, void* out_suffix, hipStream_t stream);

@@ -1,0 +1,294 @@
+// Vocabulary projection fused into the confidence-aware unmask (paper Eq. 3 -> Eq. 4): the logits
+// z_i = W h_i of the masked positions are formed tile by tile on the matrix cores and reduced to
+// (max, sum of exp, lowest argmax id) triples in registers; they are never written to memory.
+// The triples go to the same commit kernel as those of the streaming reduction over stored logits.
+//
+// One workgroup = one vocabulary tile (BN rows of W) x one chunk of BM masked rows, the whole of Hd.
+//   * Masked rows are compacted inside the kernel (every workgroup scans the mask bytes), so the
+//     matrix cores only see rows that Eq. 4 asks for; a chunk beyond the masked count exits at once.
+//   * W is the streamed operand and has no reuse inside a workgroup: every wave owns WNB x 16
+//     vocabulary rows and loads its MFMA A operands straight from global memory into registers
+//     (16 bytes per lane = the operand layout itself), PF k-steps ahead; W never touches LDS.
+//   * The hidden rows are the shared operand: chunks of KC elements per row go through a two-stage
+//     LDS ring (registers -> LDS one chunk ahead, one barrier per chunk), XOR-swizzled so that the
+//     16-byte B-operand reads are bank-conflict free.
+//   * logits^T tile = W_tile h^T (v_mfma_f32_16x16x32_bf16, fp32 accumulate): a lane ends up with
+//     vocabulary ids 4 (lane / 16) + r of row lane % 16, so the row reduction is in-lane first, then two
+//     lane exchanges, then across the four waves through LDS.
+//   * Row chunks of one vocabulary tile get workgroup ids that are equal mod 8 and adjacent in
+//     dispatch order: same XCD, same L2, so W comes from HBM once.
+#include "common.h"
+#include "unmask_common.h"
+
+namespace sdllm {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr int kLmThreads = 256;
+constexpr int kLmWaves = kLmThreads / 64;
+constexpr int kLmStageBytes = 32768;      // one LDS stage of hidden rows
+
+struct LmHeadArgs {
+  const uint16_t* hidden;     // [rows_total][ld_h]
+  const uint16_t* weight;     // [V][ld_w]
+  const uint8_t* masked;      // [rows_total]
+  Partial* partials;          // [rows_total][ntile]
+  long long ld_h, ld_w;       // elements
+  int rows_total, V, Hd;
+  int ntile;                  // vocabulary tiles
+  int nchunk;                 // row chunks in the grid (upper bound of ceil(masked rows / BM))
+};
+
+template <int BM, int WNB>
+struct LmShape {
+  static constexpr int JB = BM / 16;                        // 16-row blocks (B operands) per chunk
+  static constexpr int BN = kLmWaves * WNB * 16;            // vocabulary rows per workgroup
+  static constexpr int KC = kLmStageBytes / 2 / BM;         // hidden elements per row and stage
+  static constexpr int KSTEPS = KC / 32;                    // MFMA k-steps per stage
+  static constexpr int PIECES = KC / 8;                     // 16-byte pieces per LDS row
+  static constexpr int PF = (16 / WNB) < KSTEPS ? (16 / WNB) : KSTEPS;   // k-steps of W in flight per wave
+  static constexpr int ROWS_PER_PASS = kLmThreads / PIECES; // rows one staging pass of the workgroup covers
+  static constexpr int NPASS = BM / ROWS_PER_PASS;          // 16-byte staging loads per thread and chunk
+  static constexpr int MIN_WAVES = BM <= 64 ? 2 : 1;         // waves per SIMD the register budget must allow
+  static_assert(PIECES >= 16 && kLmThreads % PIECES == 0 && KSTEPS % PF == 0, "shape");
+};
+
+template <int BM, int WNB>
+__global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB>::MIN_WAVES)) void lm_head_rows_kernel(LmHeadArgs a) {
+  using S = LmShape<BM, WNB>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  unsigned char* stage = lds_raw;                                     // 2 x kLmStageBytes
+  int* row_of = reinterpret_cast<int*>(lds_raw + 2 * kLmStageBytes);  // BM compacted row ids (-1 = none)
+  Partial* red = reinterpret_cast<Partial*>(row_of + BM);             // [waves][BM]
+  __shared__ int wsum[kLmWaves];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // ---- workgroup -> (vocabulary tile, row chunk): chunks of a tile share id mod 8 (the XCD)
+  const int slot = blockIdx.x >> 3;
+  const int tile = (slot / a.nchunk) * kNumXCDs + (blockIdx.x & 7);
+  const int chunk = slot % a.nchunk;
+  if (tile >= a.ntile) return;
+
+  // ---- compact the masked rows; this workgroup takes compacted rows [lo, lo + BM)
+  const int lo = chunk * BM;
+  int running = 0;
+  for (int base = 0; base < a.rows_total; base += kLmThreads) {
+    const int i = base + tid;
+    const bool f = i < a.rows_total && a.masked[i] != 0;
+    const unsigned long long bal = __ballot(f);
+    const int rank = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) wsum[wave] = __popcll(bal);
+    __syncthreads();
+    int pre = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kLmWaves; ++w) { const int c = wsum[w]; pre += (w < wave) ? c : 0; tot += c; }
+    const int ci = running + pre + rank - lo;
+    if (f && ci >= 0 && ci < BM) row_of[ci] = i;
+    running += tot;
+    __syncthreads();
+    if (running >= lo + BM) break;                 // uniform: the chunk is full
+  }
+  const int n_valid = min(running - lo, BM);       // uniform
+  if (n_valid <= 0) return;
+  if (tid < BM && tid >= n_valid) row_of[tid] = -1;
+  __syncthreads();
+
+  // ---- operand addressing
+  const int NK = a.Hd / 32;                                    // k-steps
+  const int NCH = (NK + S::KSTEPS - 1) / S::KSTEPS;            // LDS chunks
+  const int q = lane >> 4, l16 = lane & 15;
+  const uint16_t* wrow[WNB];
+#pragma unroll
+  for (int ib = 0; ib < WNB; ++ib) {
+    const int n = min(tile * S::BN + (wave * WNB + ib) * 16 + l16, a.V - 1);   // rows past V: any valid row
+    wrow[ib] = a.weight + (long long)n * a.ld_w + 8 * q;
+  }
+  // staging: this thread moves piece `pc` of rows srow0 + ROWS_PER_PASS * i
+  const int pc = tid % S::PIECES, srow0 = tid / S::PIECES;
+  unsigned hoff[S::NPASS];       // element offset of the thread's rows
+  unsigned soff[S::NPASS];       // byte offset inside a stage
+#pragma unroll
+  for (int i = 0; i < S::NPASS; ++i) {
+    const int r = srow0 + S::ROWS_PER_PASS * i;
+    hoff[i] = (unsigned)((long long)max(row_of[r], 0) * a.ld_h) + 8u * pc;
+    soff[i] = (unsigned)(r * S::KC * 2 + ((pc ^ (r & 15)) << 4));
+  }
+  // B-operand read offset of 16-row block jb, k-step s: row jb * 16 + l16, piece (4 s + q) ^ l16
+  const unsigned boff = (unsigned)(l16 * S::KC * 2);
+
+  f32x4 acc[WNB][S::JB];
+#pragma unroll
+  for (int ib = 0; ib < WNB; ++ib)
+#pragma unroll
+    for (int jb = 0; jb < S::JB; ++jb) acc[ib][jb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // ---- prologue: first W k-steps in flight, first hidden chunk into stage 0
+  bf16x8 abuf[S::PF][WNB];
+#pragma unroll
+  for (int s = 0; s < S::PF; ++s)
+#pragma unroll
+    for (int ib = 0; ib < WNB; ++ib)
+      abuf[s][ib] = *reinterpret_cast<const bf16x8*>(wrow[ib] + 32 * min(s, NK - 1));
+  // A chunk's pieces past Hd are staged as zeros and its k-steps past Hd are computed like the others
+  // (finite W times zero adds nothing): the loop body has no branch, so the compiler's wait counters
+  // see one straight line and keep the W loads PF steps ahead.
+  const unsigned klast = (unsigned)(a.Hd - 8);          // last whole piece of a row
+  {
+    const unsigned k = 8u * pc;
+#pragma unroll
+    for (int i = 0; i < S::NPASS; ++i) {
+      const u32x4 v = *reinterpret_cast<const u32x4*>(a.hidden + (hoff[i] - k + min(k, klast)));
+      *reinterpret_cast<u32x4*>(stage + soff[i]) = (k < (unsigned)a.Hd) ? v : u32x4{0u, 0u, 0u, 0u};
+    }
+  }
+  __syncthreads();
+
+  // ---- main loop over the chunks of Hd
+  for (int c = 0; c < NCH; ++c) {
+    const unsigned char* cur = stage + (c & 1) * kLmStageBytes;
+    unsigned char* nxt = stage + ((c + 1) & 1) * kLmStageBytes;
+    // next chunk of the hidden rows into registers (after the last chunk: a re-read nobody uses)
+    const unsigned k = (unsigned)((c + 1) * S::KC) + 8u * pc;
+    const unsigned kc = min(k, klast);
+    u32x4 hreg[S::NPASS];
+#pragma unroll
+    for (int i = 0; i < S::NPASS; ++i)
+      hreg[i] = *reinterpret_cast<const u32x4*>(a.hidden + (hoff[i] - 8u * pc + kc));
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int s = 0; s < S::KSTEPS; ++s) {
+      const int g = c * S::KSTEPS + s;
+      const int slot_a = s % S::PF;
+      bf16x8 aop[WNB];
+#pragma unroll
+      for (int ib = 0; ib < WNB; ++ib) aop[ib] = abuf[slot_a][ib];
+#pragma unroll
+      for (int ib = 0; ib < WNB; ++ib)
+        abuf[slot_a][ib] = *reinterpret_cast<const bf16x8*>(wrow[ib] + 32 * min(g + S::PF, NK - 1));
+#pragma unroll
+      for (int jb = 0; jb < S::JB; ++jb) {
+        const bf16x8 bop = *reinterpret_cast<const bf16x8*>(
+            cur + boff + jb * 16 * S::KC * 2 + ((unsigned)((4 * s + q) ^ l16) << 4));
+#pragma unroll
+        for (int ib = 0; ib < WNB; ++ib)
+          acc[ib][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[ib], bop, acc[ib][jb], 0, 0, 0);
+      }
+      // keep the k-steps in the written order: left alone, the scheduler gathers the W loads of a whole
+      // chunk at its end and the stream runs dry in between
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // pieces past Hd become zeros by masking, not by a select: a select would let the compiler turn the
+    // loads above into conditional ones and sink them down here, behind every W load of the chunk
+    const unsigned keep = (k < (unsigned)a.Hd) ? 0xffffffffu : 0u;
+#pragma unroll
+    for (int i = 0; i < S::NPASS; ++i)
+      *reinterpret_cast<u32x4*>(nxt + soff[i]) = hreg[i] & u32x4{keep, keep, keep, keep};
+    __syncthreads();
+  }
+
+  // ---- row reduction of the tile: in-lane over this lane's vocabulary ids (ascending), then over the
+  // four lane groups, then over the waves
+#pragma unroll
+  for (int jb = 0; jb < S::JB; ++jb) {
+    float m = kNegBig; int idx = 0x7fffffff;
+#pragma unroll
+    for (int ib = 0; ib < WNB; ++ib)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int n = tile * S::BN + (wave * WNB + ib) * 16 + 4 * q + r;
+        float v = acc[ib][jb][r];
+        if (n >= a.V) v = -INFINITY;
+        acc[ib][jb][r] = v;
+        if (v > m) { m = v; idx = n; }               // strict: the lowest id keeps a tie
+      }
+    const float ml = m * kLog2e;
+    float s = 0.f;
+#pragma unroll
+    for (int ib = 0; ib < WNB; ++ib)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) s += fast_exp2(fmaf(acc[ib][jb][r], kLog2e, -ml));
+#pragma unroll
+    for (int off = 16; off <= 32; off <<= 1) {
+      const float m2 = __shfl_xor(m, off); const float s2 = __shfl_xor(s, off); const int i2 = __shfl_xor(idx, off);
+      merge_partial(m, s, idx, m2, s2, i2);
+    }
+    if (q == 0) red[wave * BM + jb * 16 + l16] = Partial{m, s, idx};
+  }
+  __syncthreads();
+  if (tid < BM && row_of[tid] >= 0) {
+    Partial p = red[tid];
+#pragma unroll
+    for (int w = 1; w < kLmWaves; ++w) {
+      const Partial p2 = red[w * BM + tid];
+      merge_partial(p.m, p.s, p.idx, p2.m, p2.s, p2.idx);
+    }
+    a.partials[(long long)row_of[tid] * a.ntile + tile] = p;
+  }
+}
+
+// ---- host side ----
+struct LmPlan { int bm, wnb, bn, ntile, nchunk; };
+
+static LmPlan lm_plan(const sdllm_lm_head_params& p) {
+  const long long rows = (long long)p.B * p.K;
+  LmPlan pl;
+  if (rows <= 32) { pl.bm = 32; pl.wnb = 2; }
+  else if (rows <= 64) { pl.bm = 64; pl.wnb = 2; }
+  else { pl.bm = 128; pl.wnb = 4; }
+  pl.bn = kLmWaves * pl.wnb * 16;
+  pl.ntile = (p.V + pl.bn - 1) / pl.bn;
+  pl.nchunk = (int)((rows + pl.bm - 1) / pl.bm);
+  return pl;
+}
+
+int lm_head_tiles(const sdllm_lm_head_params& p) { return lm_plan(p).ntile; }
+
+size_t lm_head_workspace_bytes(const sdllm_lm_head_params& p) {
+  return (size_t)p.B * p.K * lm_plan(p).ntile * sizeof(Partial);
+}
+
+template <int BM, int WNB>
+static hipError_t launch_rows(const LmHeadArgs& r, unsigned grid, hipStream_t stream) {
+  const size_t lds = 2 * kLmStageBytes + BM * sizeof(int) + kLmWaves * BM * sizeof(Partial);
+  static bool attr_set = false;                     // > 64 KiB of dynamic LDS needs the opt-in, once
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_rows_kernel<BM, WNB>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((lm_head_rows_kernel<BM, WNB>), dim3(grid), dim3(kLmThreads), lds, stream, r);
+  return hipGetLastError();
+}
+
+hipError_t launch_lm_head_unmask(const sdllm_lm_head_params& p, const void* hidden, const void* weight,
+                                 int32_t* tokens, uint8_t* masked, float* confidence, int32_t* n_committed,
+                                 uint8_t* block_done, uint8_t* eos_seen, void* workspace, hipStream_t stream) {
+  const LmPlan pl = lm_plan(p);
+  LmHeadArgs r;
+  r.hidden = (const uint16_t*)hidden; r.weight = (const uint16_t*)weight; r.masked = masked;
+  r.partials = (Partial*)workspace;
+  r.ld_h = p.ld_h; r.ld_w = p.ld_w;
+  r.rows_total = p.B * p.K; r.V = p.V; r.Hd = p.Hd;
+  r.ntile = pl.ntile; r.nchunk = pl.nchunk;
+  const unsigned grid = (unsigned)(((pl.ntile + kNumXCDs - 1) / kNumXCDs) * pl.nchunk * kNumXCDs);
+  hipError_t e;
+  if (pl.bm == 32) e = launch_rows<32, 2>(r, grid, stream);
+  else if (pl.bm == 64) e = launch_rows<64, 2>(r, grid, stream);
+  else e = launch_rows<128, 4>(r, grid, stream);
+  if (e != hipSuccess) return e;
+
+  UnmaskArgs u;
+  u.logits = nullptr; u.partials = (Partial*)workspace;
+  u.tokens = tokens; u.masked = masked; u.confidence = confidence;
+  u.n_committed = n_committed; u.block_done = block_done; u.eos_seen = eos_seen;
+  u.ld = 0; u.V = p.V; u.nvec = 0; u.vec_per_split = 0;
+  u.nsplit = pl.ntile; u.nsplit_p2 = 1; u.K = p.K;
+  u.tau0 = p.tau0; u.alpha = p.alpha; u.r_extra_masked = p.r_extra_masked; u.r_extra_total = p.r_extra_total;
+  u.eos_id = p.eos_id; u.tau_eos = p.tau_eos;
+  return launch_unmask_commit(u, p.B, stream);
+}
+
+}  // namespace sdllm

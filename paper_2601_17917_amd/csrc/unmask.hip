@@ -11,31 +11,13 @@
 // and dropped: the device-scope release/acquire fences it needs write back and invalidate
 // the L2 of an XCD on every workgroup and cost several times the second launch.)
 #include "common.h"
+#include "unmask_common.h"
 #include <cstdlib>
 
 namespace sdllm {
 
-constexpr float kLog2e = 1.4426950408889634f;
-// finite stand-in for -inf as the initial running maximum: keeps (m - m) and m * log2(e) free of NaN
-// and overflow (a lane or a vector whose logits are all -inf then contributes exp2(-inf) = 0)
-constexpr float kNegBig = -1.0e30f;
 constexpr int kRowThreads = 256;
 constexpr int kVecPerIter = 4;        // 16-byte vectors in flight per lane
-
-struct Partial { float m; float s; int idx; };
-typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // native vector: usable with nontemporal builtins
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-// merge (m2,s2,i2) into (m,s,i); ties on the maximum keep the lower id
-__device__ __forceinline__ void merge_partial(float& m, float& s, int& i, float m2, float s2, int i2) {
-  float M = fmaxf(m, m2);
-  float a = fast_exp2((m - M) * kLog2e);
-  float b = fast_exp2((m2 - M) * kLog2e);
-  s = s * a + s2 * b;
-  i = (m2 > m) ? i2 : ((m2 == m) ? min(i, i2) : i);
-  m = M;
-}
 
 template <typename T> struct Vec;
 template <> struct Vec<uint16_t> {   // bf16 bit patterns, 8 per 16 bytes
@@ -53,21 +35,6 @@ template <> struct Vec<float> {      // 4 per 16 bytes
     x[0] = __uint_as_float(r.x); x[1] = __uint_as_float(r.y);
     x[2] = __uint_as_float(r.z); x[3] = __uint_as_float(r.w);
   }
-};
-
-struct UnmaskArgs {
-  const void* logits;
-  Partial* partials;       // [rows][nsplit]
-  int32_t* tokens; uint8_t* masked; float* confidence;
-  int32_t* n_committed; uint8_t* block_done; uint8_t* eos_seen;
-  long long ld;            // elements
-  int V;
-  int nvec;                // 16-byte vectors covering V (last one may be partial)
-  int vec_per_split;
-  int nsplit;
-  int nsplit_p2;           // nsplit rounded up to a power of two (<= 64)
-  int K;
-  float tau0, alpha; int r_extra_masked, r_extra_total; int eos_id; float tau_eos;
 };
 
 // Folds kVecPerIter unpacked vectors per lane (vector indices v0, v0 + 256, ...) into the lane's running
@@ -177,18 +144,20 @@ __device__ __forceinline__ Partial reduce_row_slice(const UnmaskArgs& a, int row
 
 // Threshold, selection, update and flags of sequence b (Eq. 10, 9, 5), run by one whole workgroup
 // once every triple of the sequence is visible.
+template <int THREADS>
 __device__ __forceinline__ void commit_sequence(const UnmaskArgs& a, int b, float* conf_s, int* xhat_s) {
   __shared__ int cnt_masked, cnt_thr, eos_hit;
-  __shared__ float best_c[kRowThreads / 64];
-  __shared__ int best_i[kRowThreads / 64];
+  __shared__ float best_c[THREADS / 64];
+  __shared__ int best_i[THREADS / 64];
   const int tid = threadIdx.x, K = a.K;
   if (tid == 0) { cnt_masked = 0; cnt_thr = 0; eos_hit = 0; }
   __syncthreads();
 
-  // pass 1: nsplit_p2 adjacent lanes hold the triples of one position and merge them with a
-  // butterfly (fixed pattern); all loads of a pass are independent.
+  // pass 1: P2 adjacent lanes (at most one wave) hold the triples of one position and merge them with a
+  // butterfly (fixed pattern); all loads of a pass are independent.  With more than 64 triples per
+  // position (the vocabulary projection writes one per vocabulary tile) a lane first folds every 64th.
   const int P2 = a.nsplit_p2;
-  const int pos_per_pass = kRowThreads / P2;
+  const int pos_per_pass = THREADS / P2;
   const int k = tid & (P2 - 1);
   int my_masked = 0;
   for (int i0 = 0; i0 < K; i0 += pos_per_pass) {
@@ -201,6 +170,17 @@ __device__ __forceinline__ void commit_sequence(const UnmaskArgs& a, int b, floa
     const Partial pr = a.partials[pos * a.nsplit + min(k, a.nsplit - 1)];
     float m = kNegBig, s = 0.f; int idx = 0x7fffffff;
     if (is_masked && k < a.nsplit) { m = pr.m; s = pr.s; idx = pr.idx; }
+    if (a.nsplit > P2 && is_masked) {
+      constexpr int kBatch = 8;                       // independent loads in flight per lane
+      for (int k0 = k + P2; k0 < a.nsplit; k0 += kBatch * P2) {
+        Partial q[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) q[u] = a.partials[pos * a.nsplit + min(k0 + u * P2, a.nsplit - 1)];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u)
+          if (k0 + u * P2 < a.nsplit) merge_partial(m, s, idx, q[u].m, q[u].s, q[u].idx);
+      }
+    }
     for (int off = P2 >> 1; off >= 1; off >>= 1) {
       float m2 = __shfl_xor(m, off); float s2 = __shfl_xor(s, off); int i2 = __shfl_xor(idx, off);
       merge_partial(m, s, idx, m2, s2, i2);
@@ -232,7 +212,7 @@ __device__ __forceinline__ void commit_sequence(const UnmaskArgs& a, int b, floa
 
   // pass 2: threshold commits + candidates for the fallback
   float bc = -1.f; int bi = 0x7fffffff; int my_thr = 0;
-  for (int i = tid; i < K; i += kRowThreads) {
+  for (int i = tid; i < K; i += THREADS) {
     const long long pos = (long long)b * K + i;
     // pass 1 left 0 for an unmasked position and 1 / sum > 0 for a masked one: no second look at the
     // mask bytes (one memory round trip less)
@@ -258,7 +238,7 @@ __device__ __forceinline__ void commit_sequence(const UnmaskArgs& a, int b, floa
   if (tid == 0) {
     int ncommit = cnt_thr;
     if (ncommit == 0) {                     // fallback: single most confident masked position
-      for (int w = 1; w < kRowThreads / 64; ++w)
+      for (int w = 1; w < THREADS / 64; ++w)
         if (best_c[w] > bc || (best_c[w] == bc && best_i[w] < bi)) { bc = best_c[w]; bi = best_i[w]; }
       const long long pos = (long long)b * K + bi;
       const int xhat = xhat_s[bi];
@@ -283,10 +263,22 @@ __global__ __launch_bounds__(kRowThreads) void unmask_rows_kernel(UnmaskArgs a) 
   if (threadIdx.x == 0) a.partials[(long long)row * a.nsplit + split] = p;
 }
 
-__global__ __launch_bounds__(kRowThreads) void unmask_commit_kernel(UnmaskArgs a) {
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void unmask_commit_kernel(UnmaskArgs a) {
   extern __shared__ float conf_s[];          // K confidences, then K predicted ids
   int* xhat_s = reinterpret_cast<int*>(conf_s + a.K);
-  commit_sequence(a, blockIdx.x, conf_s, xhat_s);
+  commit_sequence<THREADS>(a, blockIdx.x, conf_s, xhat_s);
+}
+
+hipError_t launch_unmask_commit(const UnmaskArgs& args, int B, hipStream_t stream) {
+  UnmaskArgs r = args;
+  r.nsplit_p2 = 1;
+  while (r.nsplit_p2 < r.nsplit && r.nsplit_p2 < 64) r.nsplit_p2 <<= 1;
+  const size_t lds = (size_t)r.K * (sizeof(float) + sizeof(int));
+  // many triples per position: a wave per position, 16 positions per pass
+  if (r.nsplit > 64) hipLaunchKernelGGL(unmask_commit_kernel<1024>, dim3(B), dim3(1024), lds, stream, r);
+  else hipLaunchKernelGGL(unmask_commit_kernel<kRowThreads>, dim3(B), dim3(kRowThreads), lds, stream, r);
+  return hipGetLastError();
 }
 
 int unmask_splits(const sdllm_unmask_params& p) {
@@ -323,7 +315,6 @@ hipError_t launch_unmask(const sdllm_unmask_params& p, const void* logits, int32
   r.nvec = (p.V + N - 1) / N;
   r.nsplit = unmask_splits(p);
   r.nsplit_p2 = 1;
-  while (r.nsplit_p2 < r.nsplit) r.nsplit_p2 <<= 1;
   r.vec_per_split = (r.nvec + r.nsplit - 1) / r.nsplit;
   r.tau0 = p.tau0; r.alpha = p.alpha; r.r_extra_masked = p.r_extra_masked; r.r_extra_total = p.r_extra_total;
   r.eos_id = p.eos_id; r.tau_eos = p.tau_eos;
@@ -332,9 +323,7 @@ hipError_t launch_unmask(const sdllm_unmask_params& p, const void* logits, int32
   else hipLaunchKernelGGL(unmask_rows_kernel<uint16_t>, grid, dim3(kRowThreads), 0, stream, r);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const size_t lds = (size_t)p.K * (sizeof(float) + sizeof(int));
-  hipLaunchKernelGGL(unmask_commit_kernel, dim3(p.B), dim3(kRowThreads), lds, stream, r);
-  return hipGetLastError();
+  return launch_unmask_commit(r, p.B, stream);
 }
 
 }  // namespace sdllm

@@ -36,6 +36,8 @@ def test_struct_layouts_match_header():
     assert ctypes.sizeof(sd.AppendParams) == 48
     assert sd.AppendParams.cache_layer_stride.offset == 32
     assert ctypes.sizeof(sd.AttnPlan) == 16
+    assert ctypes.sizeof(sd.LmHeadParams) == 56
+    assert sd.LmHeadParams.ld_h.offset == 16 and sd.LmHeadParams.tau0.offset == 32
 
 
 def test_status_strings(lib):
@@ -131,6 +133,44 @@ def test_unmask_null_and_workspace(lib):
     assert lib.sdllm_confidence_unmask(ctypes.byref(p), *args, None, need, None) == sd.ERR_WORKSPACE
     bad = list(args); bad[1] = None
     assert lib.sdllm_confidence_unmask(ctypes.byref(p), *bad, vp(4096), need, None) == sd.ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(V=0), sd.ERR_INVALID_ARG),
+    (dict(Hd=4100), sd.ERR_UNSUPPORTED),                     # not a multiple of 32
+    (dict(ld_h=4000), sd.ERR_INVALID_ARG),                   # row stride below the width
+    (dict(ld_w=4100), sd.ERR_INVALID_ARG),                   # row stride not a multiple of 16 bytes
+    (dict(K=5000), sd.ERR_UNSUPPORTED),
+    (dict(B=4096, K=32), sd.ERR_UNSUPPORTED),                # more than 65536 positions
+    (dict(r_extra_masked=5, r_extra_total=4), sd.ERR_INVALID_ARG),
+    (dict(tau0=float("nan")), sd.ERR_INVALID_ARG),
+])
+def test_lm_head_validation(lib, kw, status):
+    base = dict(B=2, K=32, V=126464, Hd=4096, ld_h=4096, ld_w=4096, tau0=0.9, alpha=0.3)
+    base.update(kw)
+    p = sd.lm_head_params(**base)
+    vp = ctypes.c_void_p
+    rc = lib.sdllm_lm_head_unmask(ctypes.byref(p), vp(4096), vp(4096), vp(4096), vp(4096), None, vp(4096), vp(4096),
+                                  None, vp(4096), 1 << 30, None)
+    assert rc == status
+    assert lib.sdllm_last_error() != b""
+    assert lib.sdllm_lm_head_unmask_workspace_bytes(ctypes.byref(p)) == ctypes.c_size_t(-1).value
+
+
+def test_lm_head_null_misaligned_and_workspace(lib):
+    vp = ctypes.c_void_p
+    p = sd.lm_head_params(1, 32, 126464, 4096, 4096, 4096, 0.9, 0.3)
+    need = sd.lm_head_unmask_workspace_bytes(p)
+    assert need > 0 and need % (32 * 12) == 0                 # one (max, sum, arg-max) triple per position and vocabulary tile
+    args = [vp(4096), vp(4096), vp(4096), vp(4096), None, vp(4096), vp(4096), None]
+    assert lib.sdllm_lm_head_unmask(ctypes.byref(p), *args, vp(4096), need - 1, None) == sd.ERR_WORKSPACE
+    assert lib.sdllm_lm_head_unmask(ctypes.byref(p), *args, None, need, None) == sd.ERR_WORKSPACE
+    for i in (0, 1, 2, 3, 5, 6):
+        bad = list(args); bad[i] = None
+        assert lib.sdllm_lm_head_unmask(ctypes.byref(p), *bad, vp(4096), need, None) == sd.ERR_INVALID_ARG
+    bad = list(args); bad[1] = vp(4104)
+    assert lib.sdllm_lm_head_unmask(ctypes.byref(p), *bad, vp(4096), need, None) == sd.ERR_INVALID_ARG
+    assert lib.sdllm_lm_head_unmask(None, *args, vp(4096), need, None) == sd.ERR_INVALID_ARG
 
 
 @pytest.mark.parametrize("kw,status", [
