@@ -9,14 +9,17 @@
 //   * W is the streamed operand and has no reuse inside a workgroup: every wave owns WNB x 16
 //     vocabulary rows and loads its MFMA A operands straight from global memory into registers
 //     (16 bytes per lane = the operand layout itself), PF k-steps ahead; W never touches LDS.
-//   * The hidden rows are the shared operand: chunks of KC elements per row go through a two-stage
-//     LDS ring (registers -> LDS one chunk ahead, one barrier per chunk), XOR-swizzled so that the
-//     16-byte B-operand reads are bank-conflict free.
+//   * The hidden rows are the shared operand: chunks of KC elements per row go through an LDS ring
+//     (registers -> LDS ahead of use, one barrier per chunk), XOR-swizzled so that the 16-byte
+//     B-operand reads are bank-conflict free.
 //   * logits^T tile = W_tile h^T (v_mfma_f32_16x16x32_bf16, fp32 accumulate): a lane ends up with
 //     vocabulary ids 4 (lane / 16) + r of row lane % 16, so the row reduction is in-lane first, then two
 //     lane exchanges, then across the four waves through LDS.
 //   * Row chunks of one vocabulary tile get workgroup ids that are equal mod 8 and adjacent in
 //     dispatch order: same XCD, same L2, so W comes from HBM once.
+//   * Shapes: up to 32 / 64 rows the kernel is a W stream (two workgroups per CU); up to 128 / 256 rows
+//     per chunk it is bound by the matrix pipe (one wave per SIMD, accumulators in the accumulation
+//     registers, B operands through a register ring fed across chunk boundaries).
 #include "common.h"
 #include "unmask_common.h"
 
@@ -40,27 +43,51 @@ struct LmHeadArgs {
   int nchunk;                 // row chunks in the grid (upper bound of ceil(masked rows / BM))
 };
 
-template <int BM, int WNB>
+template <int BM, int WNB, int PF_>
 struct LmShape {
   static constexpr int JB = BM / 16;                        // 16-row blocks (B operands) per chunk
   static constexpr int BN = kLmWaves * WNB * 16;            // vocabulary rows per workgroup
   static constexpr int KC = kLmStageBytes / 2 / BM;         // hidden elements per row and stage
   static constexpr int KSTEPS = KC / 32;                    // MFMA k-steps per stage
   static constexpr int PIECES = KC / 8;                     // 16-byte pieces per LDS row
-  static constexpr int PF = (16 / WNB) < KSTEPS ? (16 / WNB) : KSTEPS;   // k-steps of W in flight per wave
+  static constexpr int PF = PF_;                            // k-steps of W in flight per wave
+  static constexpr int U = PF > KSTEPS ? PF / KSTEPS : 1;   // chunks per unrolled loop body (static ring slots)
   static constexpr int ROWS_PER_PASS = kLmThreads / PIECES; // rows one staging pass of the workgroup covers
   static constexpr int NPASS = BM / ROWS_PER_PASS;          // 16-byte staging loads per thread and chunk
-  static constexpr int MIN_WAVES = BM <= 64 ? 2 : 1;         // waves per SIMD the register budget must allow
-  static_assert(PIECES >= 16 && kLmThreads % PIECES == 0 && KSTEPS % PF == 0, "shape");
+  static constexpr int MIN_WAVES = BM <= 64 ? 2 : 1;        // waves per SIMD the register budget must allow
+  // The wide shapes are bound by the matrix pipe with one wave per SIMD.  Their 128 / 256 accumulator
+  // registers sit in the accumulation half of the register file by construction (left to the register
+  // allocator they were shuffled between the halves inside the loop, or spilled), and their B operands
+  // run through a register ring DB deep that is fed across chunk boundaries, which takes a third LDS
+  // stage (a chunk is complete one barrier before it is first read).
+  static constexpr bool WIDE = BM >= 128;
+  static constexpr int NST = WIDE ? 3 : 2;
+  static constexpr int DB = 4;
+  static_assert((PIECES == 8 || PIECES % 16 == 0) && kLmThreads % PIECES == 0, "shape");
+  static_assert((KSTEPS * U) % PF == 0 && (U == 1 || U % 2 == 0), "ring");
+  // LDS rows are unpadded; piece p of row r sits at slot swz(r, p), chosen so that the 16 lanes of a
+  // B-operand read (rows r..r+15, same piece) fall into 16 different 16-byte bank groups
+  __device__ static __forceinline__ int swz(int r, int p) {
+    return PIECES == 8 ? (p ^ ((r >> 1) & 7)) : (p ^ (r & 15));
+  }
 };
 
-template <int BM, int WNB>
-__global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB>::MIN_WAVES)) void lm_head_rows_kernel(LmHeadArgs a) {
-  using S = LmShape<BM, WNB>;
+__device__ __forceinline__ bf16x8 load_w(const uint16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
+
+// acc += A B, with the accumulator either left to the compiler or pinned to the accumulation registers
+template <bool ACC_IN_AGPR>
+__device__ __forceinline__ void mfma_acc(f32x4& acc, const bf16x8& a, const bf16x8& b) {
+  if constexpr (ACC_IN_AGPR) asm("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+  else acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc, 0, 0, 0);
+}
+
+template <int BM, int WNB, int PF_>
+__global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB, PF_>::MIN_WAVES)) void lm_head_rows_kernel(LmHeadArgs a) {
+  using S = LmShape<BM, WNB, PF_>;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  unsigned char* stage = lds_raw;                                     // 2 x kLmStageBytes
-  int* row_of = reinterpret_cast<int*>(lds_raw + 2 * kLmStageBytes);  // BM compacted row ids (-1 = none)
-  Partial* red = reinterpret_cast<Partial*>(row_of + BM);             // [waves][BM]
+  unsigned char* stage = lds_raw;                                          // NST x kLmStageBytes
+  int* row_of = reinterpret_cast<int*>(lds_raw + S::NST * kLmStageBytes);  // BM compacted row ids (-1 = none)
+  Partial* red = reinterpret_cast<Partial*>(row_of + BM);                  // [waves][BM]
   __shared__ int wsum[kLmWaves];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -99,6 +126,15 @@ __global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB>::MIN_WAVES)) void lm_
   const int NK = a.Hd / 32;                                    // k-steps
   const int NCH = (NK + S::KSTEPS - 1) / S::KSTEPS;            // LDS chunks
   const int q = lane >> 4, l16 = lane & 15;
+  // every workgroup walks the chunks of Hd in its own rotation, so that the workgroups resident at one
+  // time do not all ask for the same columns of W at once
+  const int c0 = tile % NCH;
+  auto kstep_at = [&](int t) {                                 // k-step at position t of this workgroup's walk
+    const int cc = t / S::KSTEPS, ss = t - cc * S::KSTEPS;
+    const int ch = (cc + c0) % NCH;
+    return min(ch * S::KSTEPS + ss, NK - 1);
+  };
+  auto chunk_at = [&](int c) { int ch = c + c0; ch -= (ch >= NCH) ? NCH : 0; return ch; };   // c < NCH
   const uint16_t* wrow[WNB];
 #pragma unroll
   for (int ib = 0; ib < WNB; ++ib) {
@@ -112,10 +148,10 @@ __global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB>::MIN_WAVES)) void lm_
 #pragma unroll
   for (int i = 0; i < S::NPASS; ++i) {
     const int r = srow0 + S::ROWS_PER_PASS * i;
-    hoff[i] = (unsigned)((long long)max(row_of[r], 0) * a.ld_h) + 8u * pc;
-    soff[i] = (unsigned)(r * S::KC * 2 + ((pc ^ (r & 15)) << 4));
+    hoff[i] = (unsigned)((long long)max(row_of[r], 0) * a.ld_h);
+    soff[i] = (unsigned)(r * S::KC * 2 + (S::swz(r, pc) << 4));
   }
-  // B-operand read offset of 16-row block jb, k-step s: row jb * 16 + l16, piece (4 s + q) ^ l16
+  // B-operand read of 16-row block jb, k-step ks: row jb * 16 + l16, piece 4 ks + q
   const unsigned boff = (unsigned)(l16 * S::KC * 2);
 
   f32x4 acc[WNB][S::JB];
@@ -124,68 +160,127 @@ __global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB>::MIN_WAVES)) void lm_
 #pragma unroll
     for (int jb = 0; jb < S::JB; ++jb) acc[ib][jb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // ---- prologue: first W k-steps in flight, first hidden chunk into stage 0
+  // ---- prologue: first W k-steps in flight, first hidden chunk(s) into LDS
   bf16x8 abuf[S::PF][WNB];
 #pragma unroll
   for (int s = 0; s < S::PF; ++s)
 #pragma unroll
-    for (int ib = 0; ib < WNB; ++ib)
-      abuf[s][ib] = *reinterpret_cast<const bf16x8*>(wrow[ib] + 32 * min(s, NK - 1));
+    for (int ib = 0; ib < WNB; ++ib) abuf[s][ib] = load_w(wrow[ib] + 32 * kstep_at(s));
   // A chunk's pieces past Hd are staged as zeros and its k-steps past Hd are computed like the others
   // (finite W times zero adds nothing): the loop body has no branch, so the compiler's wait counters
   // see one straight line and keep the W loads PF steps ahead.
   const unsigned klast = (unsigned)(a.Hd - 8);          // last whole piece of a row
-  {
-    const unsigned k = 8u * pc;
+  auto stage_now = [&](int c, unsigned char* dst) {     // chunk at walk position c straight into LDS
+    const unsigned k = (unsigned)(chunk_at(c < NCH ? c : 0) * S::KC) + 8u * pc;
+    const bool keep = c < NCH && k < (unsigned)a.Hd;
 #pragma unroll
     for (int i = 0; i < S::NPASS; ++i) {
-      const u32x4 v = *reinterpret_cast<const u32x4*>(a.hidden + (hoff[i] - k + min(k, klast)));
-      *reinterpret_cast<u32x4*>(stage + soff[i]) = (k < (unsigned)a.Hd) ? v : u32x4{0u, 0u, 0u, 0u};
+      const u32x4 v = *reinterpret_cast<const u32x4*>(a.hidden + (hoff[i] + min(k, klast)));
+      *reinterpret_cast<u32x4*>(dst + soff[i]) = keep ? v : u32x4{0u, 0u, 0u, 0u};
     }
-  }
+  };
+  stage_now(0, stage);
+  if constexpr (S::WIDE) stage_now(1, stage + kLmStageBytes);
   __syncthreads();
 
-  // ---- main loop over the chunks of Hd
-  for (int c = 0; c < NCH; ++c) {
-    const unsigned char* cur = stage + (c & 1) * kLmStageBytes;
-    unsigned char* nxt = stage + ((c + 1) & 1) * kLmStageBytes;
-    // next chunk of the hidden rows into registers (after the last chunk: a re-read nobody uses)
-    const unsigned k = (unsigned)((c + 1) * S::KC) + 8u * pc;
-    const unsigned kc = min(k, klast);
-    u32x4 hreg[S::NPASS];
+  const int NCHU = (NCH + S::U - 1) / S::U * S::U;      // chunks past NCH see zeros
+  if constexpr (S::WIDE) {
+    // ---- main loop, wide shapes: three LDS stages (read c, already complete c + 1, being written c + 2)
+    constexpr int CH = S::KSTEPS * S::JB;               // B operands per chunk
+    static_assert(CH % S::DB == 0, "B ring");
+    unsigned pv[S::KSTEPS];                             // per-lane part of a B-operand address, by k-step
 #pragma unroll
-    for (int i = 0; i < S::NPASS; ++i)
-      hreg[i] = *reinterpret_cast<const u32x4*>(a.hidden + (hoff[i] - 8u * pc + kc));
-    __builtin_amdgcn_sched_barrier(0);
+    for (int ks = 0; ks < S::KSTEPS; ++ks) pv[ks] = boff + (unsigned)(S::swz(l16, 4 * ks + q) << 4);
+    auto read_b = [&](unsigned st_off, int ks, int jb) {
+      return *reinterpret_cast<const bf16x8*>(stage + st_off + pv[ks] + jb * 16 * S::KC * 2);
+    };
+    unsigned cur_off = 0, nxt_off = kLmStageBytes, wr_off = 2 * kLmStageBytes;    // uniform
+    bf16x8 bq[S::DB];
 #pragma unroll
-    for (int s = 0; s < S::KSTEPS; ++s) {
-      const int g = c * S::KSTEPS + s;
-      const int slot_a = s % S::PF;
-      bf16x8 aop[WNB];
+    for (int d = 0; d < S::DB; ++d) bq[d] = read_b(cur_off, d / S::JB, d % S::JB);
+    for (int cb = 0; cb < NCHU; cb += S::U) {
 #pragma unroll
-      for (int ib = 0; ib < WNB; ++ib) aop[ib] = abuf[slot_a][ib];
+      for (int uu = 0; uu < S::U; ++uu) {
+        const int c = cb + uu;
+        // the chunk after next into registers (past the end: a re-read that is masked to zeros)
+        const bool more = c + 2 < NCH;
+        const unsigned k = (unsigned)(chunk_at(more ? c + 2 : 0) * S::KC) + 8u * pc;
+        const unsigned kc = min(k, klast);
+        u32x4 hreg[S::NPASS];
 #pragma unroll
-      for (int ib = 0; ib < WNB; ++ib)
-        abuf[slot_a][ib] = *reinterpret_cast<const bf16x8*>(wrow[ib] + 32 * min(g + S::PF, NK - 1));
+        for (int i = 0; i < S::NPASS; ++i) hreg[i] = *reinterpret_cast<const u32x4*>(a.hidden + (hoff[i] + kc));
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int jb = 0; jb < S::JB; ++jb) {
-        const bf16x8 bop = *reinterpret_cast<const bf16x8*>(
-            cur + boff + jb * 16 * S::KC * 2 + ((unsigned)((4 * s + q) ^ l16) << 4));
+        for (int ks = 0; ks < S::KSTEPS; ++ks) {
+          const int g = c * S::KSTEPS + ks;
+          const int slot_a = (uu * S::KSTEPS + ks) % S::PF;
+          bf16x8 aop[WNB];
 #pragma unroll
-        for (int ib = 0; ib < WNB; ++ib)
-          acc[ib][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[ib], bop, acc[ib][jb], 0, 0, 0);
+          for (int ib = 0; ib < WNB; ++ib) aop[ib] = abuf[slot_a][ib];
+#pragma unroll
+          for (int ib = 0; ib < WNB; ++ib) abuf[slot_a][ib] = load_w(wrow[ib] + 32 * kstep_at(g + S::PF));
+#pragma unroll
+          for (int jb = 0; jb < S::JB; ++jb) {
+            const int t = ks * S::JB + jb, tn = t + S::DB;
+            const bf16x8 bop = bq[t % S::DB];
+            bq[t % S::DB] = tn < CH ? read_b(cur_off, tn / S::JB, tn % S::JB)
+                                    : read_b(nxt_off, (tn - CH) / S::JB, (tn - CH) % S::JB);
+#pragma unroll
+            for (int ib = 0; ib < WNB; ++ib) mfma_acc<true>(acc[ib][jb], aop[ib], bop);
+            __builtin_amdgcn_sched_barrier(0);          // keep the ring's distance as written
+          }
+        }
+        // pieces past Hd become zeros by masking, not by a select: a select would let the compiler turn the
+        // loads above into conditional ones and sink them down here, behind every W load of the chunk
+        const unsigned keep = (more && k < (unsigned)a.Hd) ? 0xffffffffu : 0u;
+#pragma unroll
+        for (int i = 0; i < S::NPASS; ++i)
+          *reinterpret_cast<u32x4*>(stage + wr_off + soff[i]) = hreg[i] & u32x4{keep, keep, keep, keep};
+        __syncthreads();
+        const unsigned tmp = cur_off; cur_off = nxt_off; nxt_off = wr_off; wr_off = tmp;
       }
-      // keep the k-steps in the written order: left alone, the scheduler gathers the W loads of a whole
-      // chunk at its end and the stream runs dry in between
-      __builtin_amdgcn_sched_barrier(0);
     }
-    // pieces past Hd become zeros by masking, not by a select: a select would let the compiler turn the
-    // loads above into conditional ones and sink them down here, behind every W load of the chunk
-    const unsigned keep = (k < (unsigned)a.Hd) ? 0xffffffffu : 0u;
+    // the accumulators written by the last matrix instructions are read by vector instructions next; the
+    // compiler does not see an MFMA inside the asm statement, so the required wait states are spelled out
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+  } else {
+    // ---- main loop, narrow shapes: two LDS stages, the kernel is a stream of W
+    for (int c = 0; c < NCHU; ++c) {
+      const unsigned char* cur = stage + (c & 1) * kLmStageBytes;
+      unsigned char* nxt = stage + ((c + 1) & 1) * kLmStageBytes;
+      const bool more = c + 1 < NCH;
+      const unsigned k = (unsigned)(chunk_at(more ? c + 1 : 0) * S::KC) + 8u * pc;
+      const unsigned kc = min(k, klast);
+      u32x4 hreg[S::NPASS];
 #pragma unroll
-    for (int i = 0; i < S::NPASS; ++i)
-      *reinterpret_cast<u32x4*>(nxt + soff[i]) = hreg[i] & u32x4{keep, keep, keep, keep};
-    __syncthreads();
+      for (int i = 0; i < S::NPASS; ++i) hreg[i] = *reinterpret_cast<const u32x4*>(a.hidden + (hoff[i] + kc));
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int ks = 0; ks < S::KSTEPS; ++ks) {
+        const int g = c * S::KSTEPS + ks;
+        const int slot_a = ks % S::PF;
+        bf16x8 aop[WNB];
+#pragma unroll
+        for (int ib = 0; ib < WNB; ++ib) aop[ib] = abuf[slot_a][ib];
+#pragma unroll
+        for (int ib = 0; ib < WNB; ++ib) abuf[slot_a][ib] = load_w(wrow[ib] + 32 * kstep_at(g + S::PF));
+#pragma unroll
+        for (int jb = 0; jb < S::JB; ++jb) {
+          const bf16x8 bop = *reinterpret_cast<const bf16x8*>(
+              cur + boff + jb * 16 * S::KC * 2 + (unsigned)(S::swz(l16, 4 * ks + q) << 4));
+#pragma unroll
+          for (int ib = 0; ib < WNB; ++ib) mfma_acc<false>(acc[ib][jb], aop[ib], bop);
+        }
+        // keep the k-steps in the written order: left alone, the scheduler gathers the W loads of a whole
+        // chunk at its end and the stream runs dry in between
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      const unsigned keep = (more && k < (unsigned)a.Hd) ? 0xffffffffu : 0u;
+#pragma unroll
+      for (int i = 0; i < S::NPASS; ++i)
+        *reinterpret_cast<u32x4*>(nxt + soff[i]) = hreg[i] & u32x4{keep, keep, keep, keep};
+      __syncthreads();
+    }
   }
 
   // ---- row reduction of the tile: in-lane over this lane's vocabulary ids (ascending), then over the
@@ -236,7 +331,8 @@ static LmPlan lm_plan(const sdllm_lm_head_params& p) {
   LmPlan pl;
   if (rows <= 32) { pl.bm = 32; pl.wnb = 2; }
   else if (rows <= 64) { pl.bm = 64; pl.wnb = 2; }
-  else { pl.bm = 128; pl.wnb = 4; }
+  else if (rows <= 128) { pl.bm = 128; pl.wnb = 4; }
+  else { pl.bm = 256; pl.wnb = 4; }
   pl.bn = kLmWaves * pl.wnb * 16;
   pl.ntile = (p.V + pl.bn - 1) / pl.bn;
   pl.nchunk = (int)((rows + pl.bm - 1) / pl.bm);
@@ -249,17 +345,17 @@ size_t lm_head_workspace_bytes(const sdllm_lm_head_params& p) {
   return (size_t)p.B * p.K * lm_plan(p).ntile * sizeof(Partial);
 }
 
-template <int BM, int WNB>
+template <int BM, int WNB, int PF>
 static hipError_t launch_rows(const LmHeadArgs& r, unsigned grid, hipStream_t stream) {
-  const size_t lds = 2 * kLmStageBytes + BM * sizeof(int) + kLmWaves * BM * sizeof(Partial);
+  const size_t lds = LmShape<BM, WNB, PF>::NST * kLmStageBytes + BM * sizeof(int) + kLmWaves * BM * sizeof(Partial);
   static bool attr_set = false;                     // > 64 KiB of dynamic LDS needs the opt-in, once
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_rows_kernel<BM, WNB>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_rows_kernel<BM, WNB, PF>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((lm_head_rows_kernel<BM, WNB>), dim3(grid), dim3(kLmThreads), lds, stream, r);
+  hipLaunchKernelGGL((lm_head_rows_kernel<BM, WNB, PF>), dim3(grid), dim3(kLmThreads), lds, stream, r);
   return hipGetLastError();
 }
 
@@ -275,9 +371,10 @@ hipError_t launch_lm_head_unmask(const sdllm_lm_head_params& p, const void* hidd
   r.ntile = pl.ntile; r.nchunk = pl.nchunk;
   const unsigned grid = (unsigned)(((pl.ntile + kNumXCDs - 1) / kNumXCDs) * pl.nchunk * kNumXCDs);
   hipError_t e;
-  if (pl.bm == 32) e = launch_rows<32, 2>(r, grid, stream);
-  else if (pl.bm == 64) e = launch_rows<64, 2>(r, grid, stream);
-  else e = launch_rows<128, 4>(r, grid, stream);
+  if (pl.bm == 32) e = launch_rows<32, 2, 8>(r, grid, stream);
+  else if (pl.bm == 64) e = launch_rows<64, 2, 8>(r, grid, stream);
+  else if (pl.bm == 128) e = launch_rows<128, 4, 8>(r, grid, stream);
+  else e = launch_rows<256, 4, 8>(r, grid, stream);
   if (e != hipSuccess) return e;
 
   UnmaskArgs u;
