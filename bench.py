@@ -42,6 +42,9 @@ def parse_args():
     ap.add_argument("--event-every", type=int, default=8,
                     help="bracket the dominant kernel with HIP events on every n-th timed step (an event pair costs "
                          "about as much as a small kernel, so bracketing every step would distort the step time)")
+    ap.add_argument("--no-lm-head", action="store_true",
+                    help="skip the per-kernel figure of the fused vocabulary projection + unmask (it draws the "
+                         "V x Hd projection, about 1 GB, on the device)")
     ap.add_argument("--kv-splits", type=int, default=0, help="force the attention key-range split count")
     ap.add_argument("--kv-copies", type=int, default=0,
                     help="single-layer workloads: number of distinct K/V/Q sets the steps cycle through, so that a "
@@ -310,6 +313,31 @@ def main():
         "rope_q_and_k_calls": {"ms": t_rope, "gbs": rope_bytes / t_rope / 1e6, "frac_hbm_peak": rope_bytes / t_rope / 1e6 / HBM_PEAK_GBS,
                                "in_timed_step": False},
     }
+    if w.dtype == "bf16" and not args.no_lm_head:
+        # the unmask fed by the vocabulary projection of the hidden states instead of stored logits (the step on
+        # the other side of Eq. 4; NOT part of the timed step, whose logits are inputs).  W (V x Hd) is larger
+        # than the last-level cache, so every call streams it from HBM.
+        lm = wl.make_lm_head_inputs_device(w, args.seed)
+        tok0 = torch.from_numpy(lm["tokens"]).cuda(); msk0 = torch.from_numpy(lm["masked"]).cuda()
+        tok, msk = tok0.clone(), msk0.clone()
+        lm_call = sd.bind_lm_head_unmask(lm["hidden"], lm["lm_weight"], tok, msk, w.tau0, w.alpha)
+
+        def lm_fresh():
+            tok.copy_(tok0); msk.copy_(msk0)
+            lm_call()
+
+        def lm_restore():
+            tok.copy_(tok0); msk.copy_(msk0)
+
+        t_lm = time_kernel(lm_fresh, iters=20) - time_kernel(lm_restore, iters=20)
+        lm_rows = int((lm["masked"] != 0).sum())
+        lm_bytes = w.V * w.Hd * 2 + lm_rows * w.Hd * 2
+        lm_flops = 2.0 * lm_rows * w.V * w.Hd
+        kernels["lm_head_unmask_call"] = {
+            "ms": t_lm, "gbs": lm_bytes / t_lm / 1e6, "frac_hbm_peak": lm_bytes / t_lm / 1e6 / HBM_PEAK_GBS,
+            "tflops": lm_flops / t_lm / 1e9, "frac_mfma_peak": lm_flops / t_lm / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+            "masked_rows": lm_rows, "hidden": w.Hd, "in_timed_step": False}
+        del lm, lm_call
     dur = attn_ms_ev if use_ev else None
     if bound == "hbm":
         ach = attn_bytes / dur / 1e6 if dur else None

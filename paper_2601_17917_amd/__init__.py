@@ -78,6 +78,9 @@ def load_library(path: Optional[str] = None):
     global _lib
     if _lib is not None:
         return _lib
+    # PyTorch brings its own copy of the HIP runtime: it has to be the one already in the process when
+    # libsdllm.so resolves its runtime symbols, or kernels are launched through a second, uninitialised copy
+    import torch  # noqa: F401
     path = path or LIB_PATH
     if not os.path.exists(path):
         raise RuntimeError(f"{path} not found: build it with `python -m paper_2601_17917_amd.build`")

@@ -22,6 +22,7 @@
 //     registers, B operands through a register ring fed across chunk boundaries).
 #include "common.h"
 #include "unmask_common.h"
+#include <cstdlib>
 
 namespace sdllm {
 
@@ -63,8 +64,9 @@ struct LmShape {
   static constexpr bool WIDE = BM >= 128;
   static constexpr int NST = WIDE ? 3 : 2;
   static constexpr int DB = 4;
+  static constexpr int HDEPTH = KSTEPS >= 4 ? 1 : 4 / KSTEPS;   // chunks a hidden chunk waits in registers (wide)
   static_assert((PIECES == 8 || PIECES % 16 == 0) && kLmThreads % PIECES == 0, "shape");
-  static_assert((KSTEPS * U) % PF == 0 && (U == 1 || U % 2 == 0), "ring");
+  static_assert((KSTEPS * U) % PF == 0 && (U == 1 || U % 2 == 0) && (!WIDE || U % HDEPTH == 0), "ring");
   // LDS rows are unpadded; piece p of row r sits at slot swz(r, p), chosen so that the 16 lanes of a
   // B-operand read (rows r..r+15, same piece) fall into 16 different 16-byte bank groups
   __device__ static __forceinline__ int swz(int r, int p) {
@@ -198,17 +200,30 @@ __global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB, PF_>::MIN_WAVES)) voi
     bf16x8 bq[S::DB];
 #pragma unroll
     for (int d = 0; d < S::DB; ++d) bq[d] = read_b(cur_off, d / S::JB, d % S::JB);
+    // Loads return in issue order, so waiting for a young load also waits for every older one: a hidden
+    // chunk that is consumed at the end of the chunk it was asked for in would drain the W ring down to
+    // the loads of that chunk, however far ahead the ring runs.  The hidden chunks therefore travel HD
+    // chunks ahead in registers, so that nothing younger than about PF k-steps is ever waited for.
+    constexpr int HD = S::HDEPTH;                       // chunks a hidden chunk waits in registers
+    u32x4 hreg[HD][S::NPASS];
+    auto load_hidden = [&](int c, u32x4 (&dst)[S::NPASS]) {      // chunk at walk position c (zeros past the end)
+      const unsigned k = (unsigned)(chunk_at(c < NCH ? c : 0) * S::KC) + 8u * pc;
+      const unsigned kc = min(k, klast);
+#pragma unroll
+      for (int i = 0; i < S::NPASS; ++i) dst[i] = *reinterpret_cast<const u32x4*>(a.hidden + (hoff[i] + kc));
+    };
+    auto keep_mask = [&](int c) -> unsigned {
+      const unsigned k = (unsigned)(chunk_at(c < NCH ? c : 0) * S::KC) + 8u * pc;
+      return (c < NCH && k < (unsigned)a.Hd) ? 0xffffffffu : 0u;
+    };
+#pragma unroll
+    for (int d = 1; d < HD; ++d) load_hidden(1 + d, hreg[d % HD]);     // chunks 2 .. HD: as if asked for earlier
     for (int cb = 0; cb < NCHU; cb += S::U) {
 #pragma unroll
       for (int uu = 0; uu < S::U; ++uu) {
         const int c = cb + uu;
-        // the chunk after next into registers (past the end: a re-read that is masked to zeros)
-        const bool more = c + 2 < NCH;
-        const unsigned k = (unsigned)(chunk_at(more ? c + 2 : 0) * S::KC) + 8u * pc;
-        const unsigned kc = min(k, klast);
-        u32x4 hreg[S::NPASS];
-#pragma unroll
-        for (int i = 0; i < S::NPASS; ++i) hreg[i] = *reinterpret_cast<const u32x4*>(a.hidden + (hoff[i] + kc));
+        // asked for now: chunk c + 1 + HD; written to LDS at the end of this chunk: chunk c + 2
+        load_hidden(c + 1 + HD, hreg[uu % HD]);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int ks = 0; ks < S::KSTEPS; ++ks) {
@@ -230,12 +245,13 @@ __global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB, PF_>::MIN_WAVES)) voi
             __builtin_amdgcn_sched_barrier(0);          // keep the ring's distance as written
           }
         }
-        // pieces past Hd become zeros by masking, not by a select: a select would let the compiler turn the
-        // loads above into conditional ones and sink them down here, behind every W load of the chunk
-        const unsigned keep = (more && k < (unsigned)a.Hd) ? 0xffffffffu : 0u;
+        // chunk c + 2 (asked for HD - 1 chunks ago) into the free stage.  Pieces past Hd become zeros by
+        // masking, not by a select: a select would let the compiler turn the loads into conditional ones
+        // and sink them down here
+        const unsigned keep = keep_mask(c + 2);
 #pragma unroll
         for (int i = 0; i < S::NPASS; ++i)
-          *reinterpret_cast<u32x4*>(stage + wr_off + soff[i]) = hreg[i] & u32x4{keep, keep, keep, keep};
+          *reinterpret_cast<u32x4*>(stage + wr_off + soff[i]) = hreg[(uu + 1) % HD][i] & u32x4{keep, keep, keep, keep};
         __syncthreads();
         const unsigned tmp = cur_off; cur_off = nxt_off; nxt_off = wr_off; wr_off = tmp;
       }
@@ -333,6 +349,9 @@ static LmPlan lm_plan(const sdllm_lm_head_params& p) {
   else if (rows <= 64) { pl.bm = 64; pl.wnb = 2; }
   else if (rows <= 128) { pl.bm = 128; pl.wnb = 4; }
   else { pl.bm = 256; pl.wnb = 4; }
+  // tuning knob for sweeps: SDLLM_LM_BM=128 forces 128-row chunks above 128 rows (read once)
+  static const int forced = [] { const char* e = getenv("SDLLM_LM_BM"); return e ? atoi(e) : 0; }();
+  if (forced == 128 && rows > 128) pl.bm = 128;
   pl.bn = kLmWaves * pl.wnb * 16;
   pl.ntile = (p.V + pl.bn - 1) / pl.bn;
   pl.nchunk = (int)((rows + pl.bm - 1) / pl.bm);
@@ -374,7 +393,7 @@ hipError_t launch_lm_head_unmask(const sdllm_lm_head_params& p, const void* hidd
   if (pl.bm == 32) e = launch_rows<32, 2, 8>(r, grid, stream);
   else if (pl.bm == 64) e = launch_rows<64, 2, 8>(r, grid, stream);
   else if (pl.bm == 128) e = launch_rows<128, 4, 8>(r, grid, stream);
-  else e = launch_rows<256, 4, 8>(r, grid, stream);
+  else e = launch_rows<256, 4, 4>(r, grid, stream);
   if (e != hipSuccess) return e;
 
   UnmaskArgs u;

@@ -171,7 +171,7 @@ __device__ __forceinline__ void commit_sequence(const UnmaskArgs& a, int b, floa
     float m = kNegBig, s = 0.f; int idx = 0x7fffffff;
     if (is_masked && k < a.nsplit) { m = pr.m; s = pr.s; idx = pr.idx; }
     if (a.nsplit > P2 && is_masked) {
-      constexpr int kBatch = 8;                       // independent loads in flight per lane
+      constexpr int kBatch = 16;                      // independent loads in flight per lane
       for (int k0 = k + P2; k0 < a.nsplit; k0 += kBatch * P2) {
         Partial q[kBatch];
 #pragma unroll
@@ -275,8 +275,12 @@ hipError_t launch_unmask_commit(const UnmaskArgs& args, int B, hipStream_t strea
   r.nsplit_p2 = 1;
   while (r.nsplit_p2 < r.nsplit && r.nsplit_p2 < 64) r.nsplit_p2 <<= 1;
   const size_t lds = (size_t)r.K * (sizeof(float) + sizeof(int));
-  // many triples per position: a wave per position, 16 positions per pass
-  if (r.nsplit > 64) hipLaunchKernelGGL(unmask_commit_kernel<1024>, dim3(B), dim3(1024), lds, stream, r);
+  // many triples per position: 1024 threads, and no more lanes per position than lets all K positions go
+  // in one pass when that is possible (every pass is another chain of dependent memory round trips)
+  if (r.nsplit > 64) {
+    while (r.nsplit_p2 > 1 && r.nsplit_p2 * r.K > 1024) r.nsplit_p2 >>= 1;
+    hipLaunchKernelGGL(unmask_commit_kernel<1024>, dim3(B), dim3(1024), lds, stream, r);
+  }
   else hipLaunchKernelGGL(unmask_commit_kernel<kRowThreads>, dim3(B), dim3(kRowThreads), lds, stream, r);
   return hipGetLastError();
 }
