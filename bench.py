@@ -338,6 +338,22 @@ def main():
             "tflops": lm_flops / t_lm / 1e9, "frac_mfma_peak": lm_flops / t_lm / 1e9 / MFMA_BF16_PEAK_TFLOPS,
             "masked_rows": lm_rows, "hidden": w.Hd, "in_timed_step": False}
         del lm, lm_call
+    # ---- what plain kernels reach on this machine (library diagnostics): the practical ceilings next to the
+    # published peaks the fractions are quoted against
+    buf = torch.empty((1 << 31,), dtype=torch.uint8, device="cuda").random_(0, 256)
+    half = buf.numel() // 2
+    sink = torch.zeros((16,), dtype=torch.float32, device="cuda")
+    t_rd = time_kernel(lambda: sd.probe_read(buf, sink), iters=10, warm=2)
+    t_cp = time_kernel(lambda: sd.probe_copy(buf[half:], buf[:half]), iters=10, warm=2)
+    iters_mfma = 4000
+    fl = sd.probe_mfma_bf16(iters_mfma, 0, sink)
+    t_m0 = time_kernel(lambda: sd.probe_mfma_bf16(iters_mfma, 0, sink), iters=5, warm=1)
+    t_m1 = time_kernel(lambda: sd.probe_mfma_bf16(iters_mfma, 1, sink), iters=5, warm=1)
+    ceilings = {"read_gbs": buf.numel() / t_rd / 1e6, "copy_gbs_read_plus_write": 2 * half / t_cp / 1e6,
+                "mfma_bf16_tflops_smooth_operands": fl / t_m0 / 1e9, "mfma_bf16_tflops_random_operands": fl / t_m1 / 1e9,
+                "note": "plain read / copy kernels over 2 GiB / 1 GiB and a loop of independent "
+                        "v_mfma_f32_16x16x32_bf16 (sdllm_probe_*); not part of the timed step"}
+    del buf
     dur = attn_ms_ev if use_ev else None
     if bound == "hbm":
         ach = attn_bytes / dur / 1e6 if dur else None
@@ -357,6 +373,8 @@ def main():
             roof["traffic_unit"] = "bytes per launch (read + write, main kernel + split merge)"
     except (OSError, KeyError, ValueError):
         pass
+    roof["measured_ceiling"] = ceilings["read_gbs"] if bound == "hbm" else ceilings["mfma_bf16_tflops_random_operands"]
+    roof["frac_of_measured_ceiling"] = (roof["achieved"] / roof["measured_ceiling"]) if roof["achieved"] else None
     roof.update({"kernel": "sdllm_block_attention (attn_bf16_kernel + attn_combine_kernel)" if w.dtype == "bf16"
                  else "sdllm_block_attention (attention_f32_kernel)",
                  "launch_ms": dur, "algorithmic_bytes": attn_bytes, "algorithmic_flops": attn_flops})
@@ -370,6 +388,7 @@ def main():
                    "committed_tokens_per_step": committed_per_step, "seed": args.seed},
         "roofline": roof,
         "kernels": kernels,
+        "device_ceilings": ceilings,
     }
     if not args.no_cpu_baseline:
         cb = cpu_baseline(w, args.seed)

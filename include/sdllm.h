@@ -12,6 +12,7 @@
  *   sdllm_kv_append          copy the finished block's K/V into the prefix cache
  *   sdllm_rope_gathered      rotary embedding of the pruned rows with their original position ids
  *   sdllm_suffix_keep_indices  (host) which suffix rows the attenuation-guided rule keeps
+ *   sdllm_probe_*            diagnostics: read / copy / matrix-instruction ceilings of the device
  *
  * Conventions common to all calls
  *   - Every buffer is CALLER-ALLOCATED DEVICE memory unless said otherwise; the library
@@ -283,6 +284,23 @@ typedef struct sdllm_attn_plan {
 } sdllm_attn_plan;
 
 int sdllm_plan_attention(const sdllm_attn_params* p, sdllm_attn_plan* plan);
+
+/* ---------------------------------------------------------------------------------------
+ * Device ceilings (diagnostics; not part of the decode step): what plain kernels reach on the
+ * device, to read the roofline fractions of the hot-path kernels against.
+ *   sdllm_probe_read       streams `bytes` (multiple of 16, > 0) of src once; sink: >= 4 bytes of
+ *                          device memory that is practically never written
+ *   sdllm_probe_copy       dst <- src, `bytes` (multiple of 16, > 0), bit for bit; no overlap
+ *   sdllm_probe_mfma_bf16  2 workgroups of 4 waves per CU, each wave `iters` (>= 1) rounds of 8 independent
+ *                          v_mfma_f32_16x16x32_bf16; operand_kind 0 = smooth small operand values,
+ *                          1 = pseudo-random sign / exponent / mantissa bits (more power per
+ *                          instruction, lower sustained clock).  *flops (HOST, optional) receives the
+ *                          floating-point operations of one launch.
+ * All three only enqueue one kernel on `stream`.  Errors: INVALID_ARG, HIP.
+ * ------------------------------------------------------------------------------------- */
+int sdllm_probe_read(const void* src, size_t bytes, void* sink, void* stream);
+int sdllm_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
+int sdllm_probe_mfma_bf16(int32_t iters, int32_t operand_kind, void* sink, void* stream, double* flops);
 
 const char* sdllm_status_string(int status);
 const char* sdllm_last_error(void); /* calling thread's last failure text ("" if none) */

@@ -21,6 +21,7 @@ EXPORTED_SYMBOLS = (
     "sdllm_confidence_unmask", "sdllm_unmask_workspace_bytes",
     "sdllm_lm_head_unmask", "sdllm_lm_head_unmask_workspace_bytes",
     "sdllm_kv_append", "sdllm_suffix_keep_indices", "sdllm_rope_gathered",
+    "sdllm_probe_read", "sdllm_probe_copy", "sdllm_probe_mfma_bf16",
     "sdllm_status_string", "sdllm_last_error", "sdllm_version",
 )
 
@@ -111,6 +112,12 @@ def load_library(path: Optional[str] = None):
     lib.sdllm_kv_append.argtypes = [ctypes.POINTER(AppendParams)] + [vp] * 5 + [vp]
     lib.sdllm_rope_gathered.restype = i32
     lib.sdllm_rope_gathered.argtypes = [ctypes.POINTER(RopeParams)] + [vp] * 5 + [vp]
+    lib.sdllm_probe_read.restype = i32
+    lib.sdllm_probe_read.argtypes = [vp, sz, vp, vp]
+    lib.sdllm_probe_copy.restype = i32
+    lib.sdllm_probe_copy.argtypes = [vp, vp, sz, vp]
+    lib.sdllm_probe_mfma_bf16.restype = i32
+    lib.sdllm_probe_mfma_bf16.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp, ctypes.POINTER(ctypes.c_double)]
     _lib = lib
     return lib
 
@@ -376,6 +383,28 @@ def bind_rope_gathered(x_block, x_suffix, keep_idx, pos0: int, theta_base: float
 
 
 # ---------------------------------------------------------------------------------------------
+def probe_read(src, sink, stream=None):
+    """sdllm_probe_read over the whole of `src` (device tensor, byte size a multiple of 16)."""
+    _require(src, "src"); _require(sink, "sink")
+    _check(load_library().sdllm_probe_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(stream)))
+
+
+def probe_copy(dst, src, stream=None):
+    """sdllm_probe_copy: dst <- src (device tensors of the same byte size, a multiple of 16)."""
+    _require(src, "src"); _require(dst, "dst")
+    if dst.numel() * dst.element_size() != src.numel() * src.element_size():
+        raise SdllmError(ERR_INVALID_ARG, "probe_copy: dst and src differ in size")
+    _check(load_library().sdllm_probe_copy(_ptr(dst), _ptr(src), src.numel() * src.element_size(), _stream(stream)))
+
+
+def probe_mfma_bf16(iters: int, operand_kind: int, sink, stream=None) -> float:
+    """sdllm_probe_mfma_bf16; returns the floating-point operations of the launch."""
+    _require(sink, "sink")
+    fl = ctypes.c_double(0.0)
+    _check(load_library().sdllm_probe_mfma_bf16(iters, operand_kind, _ptr(sink), _stream(stream), ctypes.byref(fl)))
+    return fl.value
+
+
 def suffix_keep_indices(S: int, K: int, w_blocks: int, keep_trailing: bool = True):
     """sdllm_suffix_keep_indices (host helper, paper Eq. 7).  Returns a Python list of the kept suffix
     positions (relative to the start of the suffix, strictly increasing)."""

@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsdllm.so")
-SOURCES = ["api.hip", "kv_append.hip", "unmask.hip", "attention_f32.hip", "attention_bf16.hip", "rope.hip", "lm_head.hip"]
+SOURCES = ["api.hip", "kv_append.hip", "unmask.hip", "attention_f32.hip", "attention_bf16.hip", "rope.hip", "lm_head.hip", "probe.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wno-inline-asm",
     # packed fp32 VALU forms are kept off for every HIP source of this build

@@ -299,4 +299,29 @@ int sdllm_rope_gathered(const sdllm_rope_params* p, const void* x_block, const v
   return SDLLM_OK;
 }
 
+int sdllm_probe_read(const void* src, size_t bytes, void* sink, void* stream) {
+  if (!src || !sink || bytes == 0 || bytes % 16 != 0 || !aligned16(src))
+    return fail(SDLLM_ERR_INVALID_ARG, "probe_read: need src (16-byte aligned), sink, bytes > 0 and a multiple of 16");
+  hipError_t e = sdllm::launch_probe_read(src, bytes, sink, (hipStream_t)stream);
+  if (e != hipSuccess) return fail(SDLLM_ERR_HIP, "probe_read: %s", hipGetErrorString(e));
+  return SDLLM_OK;
+}
+
+int sdllm_probe_copy(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!dst || !src || bytes == 0 || bytes % 16 != 0 || !aligned16(src) || !aligned16(dst))
+    return fail(SDLLM_ERR_INVALID_ARG, "probe_copy: need dst, src (16-byte aligned), bytes > 0 and a multiple of 16");
+  hipError_t e = sdllm::launch_probe_copy(dst, src, bytes, (hipStream_t)stream);
+  if (e != hipSuccess) return fail(SDLLM_ERR_HIP, "probe_copy: %s", hipGetErrorString(e));
+  return SDLLM_OK;
+}
+
+int sdllm_probe_mfma_bf16(int32_t iters, int32_t operand_kind, void* sink, void* stream, double* flops) {
+  if (iters < 1 || (operand_kind != 0 && operand_kind != 1) || !sink)
+    return fail(SDLLM_ERR_INVALID_ARG, "probe_mfma_bf16: need iters >= 1, operand_kind 0 or 1, sink");
+  if (flops) *flops = sdllm::probe_mfma_flops(iters);
+  hipError_t e = sdllm::launch_probe_mfma(iters, operand_kind, sink, (hipStream_t)stream);
+  if (e != hipSuccess) return fail(SDLLM_ERR_HIP, "probe_mfma_bf16: %s", hipGetErrorString(e));
+  return SDLLM_OK;
+}
+
 }  // extern "C"

@@ -56,6 +56,12 @@ hipError_t launch_lm_head_unmask(const sdllm_lm_head_params& p, const void* hidd
 hipError_t launch_rope(const sdllm_rope_params& p, const void* x_block, const void* x_suffix,
                        const int32_t* keep_idx, void* out_block, void* out_suffix, hipStream_t stream);
 
+// ---- device ceilings (diagnostics) ----
+hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStream_t stream);
+hipError_t launch_probe_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
+hipError_t launch_probe_mfma(int iters, int kind, void* sink, hipStream_t stream);
+double probe_mfma_flops(int iters);
+
 // ---- kv append ----
 hipError_t launch_kv_append(const sdllm_append_params& p, void* k_caches, void* v_caches,
                             const void* k_blocks, const void* v_blocks, const uint8_t* do_append,

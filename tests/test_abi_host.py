@@ -22,7 +22,7 @@ def lib():
 def test_exports_every_declared_symbol(lib):
     header = open(os.path.join(ROOT, "include", "sdllm.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(sdllm_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(sdllm_[a-z0-9_]+)\s*\(", header))
     assert declared == set(sd.EXPORTED_SYMBOLS)
     for name in declared:
         assert getattr(lib, name) is not None
@@ -226,3 +226,16 @@ def test_rope_null_and_misaligned(lib):
     assert lib.sdllm_rope_gathered(ctypes.byref(p), *bad, None) == sd.ERR_INVALID_ARG
     assert lib.sdllm_rope_gathered(None, *ok, None) == sd.ERR_INVALID_ARG
     assert ctypes.sizeof(sd.RopeParams) == 40
+
+
+def test_probe_validation(lib):
+    vp = ctypes.c_void_p
+    assert lib.sdllm_probe_read(vp(4096), 0, vp(4096), None) == sd.ERR_INVALID_ARG
+    assert lib.sdllm_probe_read(vp(4096), 24, vp(4096), None) == sd.ERR_INVALID_ARG          # not a multiple of 16
+    assert lib.sdllm_probe_read(None, 32, vp(4096), None) == sd.ERR_INVALID_ARG
+    assert lib.sdllm_probe_copy(vp(4096), vp(4104), 32, None) == sd.ERR_INVALID_ARG         # misaligned source
+    assert lib.sdllm_probe_copy(None, vp(4096), 32, None) == sd.ERR_INVALID_ARG
+    fl = ctypes.c_double(0.0)
+    assert lib.sdllm_probe_mfma_bf16(0, 0, vp(4096), None, ctypes.byref(fl)) == sd.ERR_INVALID_ARG
+    assert lib.sdllm_probe_mfma_bf16(10, 2, vp(4096), None, ctypes.byref(fl)) == sd.ERR_INVALID_ARG
+    assert lib.sdllm_probe_mfma_bf16(10, 0, None, None, ctypes.byref(fl)) == sd.ERR_INVALID_ARG
