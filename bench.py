@@ -6,7 +6,8 @@ resident in HBM: pruned-suffix attention for every layer of the workload, the co
 unmask over the block's logits, and the append of the block's K/V to the prefix caches.
 Prints ONE JSON line (metric: committed tokens per second of decode-step time), with the roofline
 figures of the dominant kernel (HIP events inside the timed region) and the CPU oracle timed on
-this machine's host cores as a baseline.
+this machine's host cores as a baseline.  Outside the timed step it also reports per-kernel timings, the fused
+vocabulary projection + unmask call, and what plain read / copy / matrix-instruction kernels reach on the box.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2]
 """
@@ -224,7 +225,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (every box has one; the path shards by batch / head without "
-              "communication, see DESIGN.md); --gpus must be 1", file=sys.stderr)
+              "communication); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
     import torch
     if not torch.cuda.is_available():

@@ -1,4 +1,4 @@
-"""The seeded generators: shapes of the BASELINE configs, determinism, bf16 rounding."""
+"""The seeded generators: shapes of the workload configurations, determinism, bf16 rounding."""
 import numpy as np
 
 import workloads as wl
