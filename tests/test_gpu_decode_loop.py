@@ -2,6 +2,8 @@
 suffix rule -> attention per layer -> unmask steps until the block is done -> KV append -> next block,
 with the EOS early exit -- checked against the oracle at every step.  The model forward is out of scope,
 so Q/K/V and logits are seeded tensors of the right shapes."""
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -81,3 +83,53 @@ def test_block_loop_with_append_and_early_exit(gpu_lib):
         if eos_host.all():                                                  # early exit: later blocks are skipped
             break
     assert eos_host[0] == 1 and blocks_decoded >= 2
+
+
+def test_block_steps_fed_by_the_vocabulary_projection(gpu_lib):
+    """The diffusion steps of one block with the logits coming from the projection of seeded hidden states
+    (never stored): every step is checked against the oracle from the same state, up to block termination.
+    An unboosted projection keeps the confidences low, so most steps go through the fallback of Eq. 9 and the
+    block takes one step per position; a boosted projection at the seventh step commits what is left at once."""
+    sd = gpu_lib
+    w = wl.WORKLOADS["small_bf16"]
+    B, K, Hd, V = w.B, w.K, 256, 1500
+    tau0, alpha = 0.9, 0.3
+    w_plain = dataclasses.replace(w, boost=False)
+    plain = wl.make_lm_head_inputs(w_plain, seed=3, V=V, Hd=Hd)        # a projection without any boosted row
+    tokens = np.full((B, K), wl.MASK_TOKEN, dtype=np.int32)
+    masked = np.ones((B, K), dtype=np.uint8)
+    tk, mk = torch.from_numpy(tokens).cuda(), torch.from_numpy(masked).cuda()
+    conf = torch.zeros((B, K), dtype=torch.float32, device="cuda")
+    steps = checked = 0
+    while masked.any():
+        assert steps <= B * K, "the block must terminate"
+        boosted = steps == 6                                             # six fallback steps, then a confident one
+        t = wl.make_lm_head_inputs(w if boosted else w_plain, seed=3, step=steps, V=V, Hd=Hd)
+        h, W = t["hidden"], (t["lm_weight"] if boosted else plain["lm_weight"])
+        ncom, done = sd.lm_head_unmask(to_dev(h), to_dev(W), tk, mk, tau0, alpha, confidence=conf)
+        ref = oracle.lm_head_unmask(wl.bf16_bits_to_f32(h), wl.bf16_bits_to_f32(W), tokens, masked,
+                                    float(np.float32(tau0)), float(np.float32(alpha)))
+        torch.cuda.synchronize()
+        g_tok, g_msk = tk.cpu().numpy(), mk.cpu().numpy()
+        was = masked != 0
+        np.testing.assert_allclose(conf.cpu().numpy()[was], ref["confidence"][was], rtol=2e-4, atol=0)
+        for b in range(B):
+            if not was[b].any():
+                assert ncom[b].item() == 0 and done[b].item() == 1
+                continue
+            c = ref["confidence"][b]
+            band = was[b] & (np.abs(np.nan_to_num(c) - ref["tau"][b]) < 1e-3)
+            top = np.sort(c[was[b]])[::-1]
+            ambiguous = band.any() or (ref["fallback"][b] and top.size > 1 and (top[0] - top[1]) <= 1e-4 * top[0])
+            newly = was[b] & (g_msk[b] == 0)
+            assert newly.any() and ncom[b].item() == newly.sum()           # progress in every step (Eq. 9's fallback)
+            assert done[b].item() == (0 if g_msk[b].any() else 1)
+            if not ambiguous:
+                assert (g_msk[b] == ref["masked"][b]).all(), (steps, b)
+                sure = newly & (np.nan_to_num(ref["gap"][b], nan=1.0) >= 1e-3)
+                assert (g_tok[b][sure] == ref["xhat"][b][sure]).all(), (steps, b)
+                checked += 1
+            assert (g_tok[b][~newly] == tokens[b][~newly]).all()            # Eq. 5: nothing else moves
+        tokens, masked = g_tok.copy(), g_msk.copy()                          # the next step starts from the GPU's state
+        steps += 1
+    assert steps >= 4 and checked >= steps                                   # many steps, most of them comparable
