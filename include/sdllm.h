@@ -189,6 +189,21 @@ int sdllm_lm_head_unmask(const sdllm_lm_head_params* p,
                          uint8_t* eos_seen,
                          void* workspace, size_t workspace_bytes, void* stream);
 
+/* Launch plan the library would use for these parameters (host only, no HIP call): rows of hidden per
+ * row chunk, rows of W per vocabulary tile, number of tiles (= triples per position in the workspace),
+ * row chunks in the grid, workgroups launched, LDS bytes per workgroup.  Returns SDLLM_OK or the
+ * validation error. */
+typedef struct sdllm_lm_head_plan {
+  int32_t rows_per_chunk;
+  int32_t vocab_rows_per_tile;
+  int32_t vocab_tiles;
+  int32_t row_chunks;
+  int32_t workgroups;
+  int32_t lds_bytes;
+} sdllm_lm_head_plan;
+
+int sdllm_plan_lm_head(const sdllm_lm_head_params* p, sdllm_lm_head_plan* plan);
+
 /* ---------------------------------------------------------------------------------------
  * KV append: the prefix K/V is kept and reused instead of recomputed (paper section 3.3,
  * first paragraph on decoding).  When a block is finished its K/V rows become rows

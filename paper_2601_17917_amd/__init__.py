@@ -19,7 +19,7 @@ FP32, BF16 = 0, 1
 EXPORTED_SYMBOLS = (
     "sdllm_block_attention", "sdllm_attention_workspace_bytes", "sdllm_plan_attention",
     "sdllm_confidence_unmask", "sdllm_unmask_workspace_bytes",
-    "sdllm_lm_head_unmask", "sdllm_lm_head_unmask_workspace_bytes",
+    "sdllm_lm_head_unmask", "sdllm_lm_head_unmask_workspace_bytes", "sdllm_plan_lm_head",
     "sdllm_kv_append", "sdllm_suffix_keep_indices", "sdllm_rope_gathered",
     "sdllm_probe_read", "sdllm_probe_copy", "sdllm_probe_mfma_bf16",
     "sdllm_status_string", "sdllm_last_error", "sdllm_version",
@@ -45,6 +45,12 @@ class LmHeadParams(ctypes.Structure):
                 ("ld_h", ctypes.c_int64), ("ld_w", ctypes.c_int64), ("tau0", ctypes.c_float), ("alpha", ctypes.c_float),
                 ("r_extra_masked", ctypes.c_int32), ("r_extra_total", ctypes.c_int32),
                 ("eos_id", ctypes.c_int32), ("tau_eos", ctypes.c_float)]
+
+
+class LmHeadPlan(ctypes.Structure):
+    _fields_ = [("rows_per_chunk", ctypes.c_int32), ("vocab_rows_per_tile", ctypes.c_int32),
+                ("vocab_tiles", ctypes.c_int32), ("row_chunks", ctypes.c_int32), ("workgroups", ctypes.c_int32),
+                ("lds_bytes", ctypes.c_int32)]
 
 
 class AppendParams(ctypes.Structure):
@@ -103,6 +109,8 @@ def load_library(path: Optional[str] = None):
     lib.sdllm_confidence_unmask.argtypes = [ctypes.POINTER(UnmaskParams)] + [vp] * 7 + [vp, sz, vp]
     lib.sdllm_lm_head_unmask_workspace_bytes.restype = sz
     lib.sdllm_lm_head_unmask_workspace_bytes.argtypes = [ctypes.POINTER(LmHeadParams)]
+    lib.sdllm_plan_lm_head.restype = i32
+    lib.sdllm_plan_lm_head.argtypes = [ctypes.POINTER(LmHeadParams), ctypes.POINTER(LmHeadPlan)]
     lib.sdllm_lm_head_unmask.restype = i32
     lib.sdllm_lm_head_unmask.argtypes = [ctypes.POINTER(LmHeadParams)] + [vp] * 8 + [vp, sz, vp]
     lib.sdllm_suffix_keep_indices.restype = i32
@@ -288,6 +296,12 @@ def lm_head_unmask_workspace_bytes(p: LmHeadParams) -> int:
     if n == ctypes.c_size_t(-1).value:
         raise SdllmError(ERR_INVALID_ARG, load_library().sdllm_last_error().decode())
     return n
+
+
+def plan_lm_head(p: LmHeadParams) -> LmHeadPlan:
+    plan = LmHeadPlan()
+    _check(load_library().sdllm_plan_lm_head(ctypes.byref(p), ctypes.byref(plan)))
+    return plan
 
 
 def lm_head_unmask(*args, **kw):

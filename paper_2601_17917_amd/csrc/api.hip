@@ -245,6 +245,14 @@ int sdllm_confidence_unmask(const sdllm_unmask_params* p, const void* logits,
   return SDLLM_OK;
 }
 
+int sdllm_plan_lm_head(const sdllm_lm_head_params* p, sdllm_lm_head_plan* plan) {
+  int rc = check_lm_head_params(p);
+  if (rc != SDLLM_OK) return rc;
+  if (!plan) return fail(SDLLM_ERR_INVALID_ARG, "plan_lm_head: plan is NULL");
+  sdllm::lm_head_plan(*p, plan);
+  return SDLLM_OK;
+}
+
 size_t sdllm_lm_head_unmask_workspace_bytes(const sdllm_lm_head_params* p) {
   if (check_lm_head_params(p) != SDLLM_OK) return (size_t)-1;
   return sdllm::lm_head_workspace_bytes(*p);

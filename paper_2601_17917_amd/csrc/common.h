@@ -46,7 +46,7 @@ hipError_t launch_unmask(const sdllm_unmask_params& p, const void* logits, int32
                          void* workspace, hipStream_t stream);
 
 // ---- vocabulary projection fused into the unmask ----
-int lm_head_tiles(const sdllm_lm_head_params& p);   // vocabulary tiles = triples per row
+void lm_head_plan(const sdllm_lm_head_params& p, sdllm_lm_head_plan* plan);
 size_t lm_head_workspace_bytes(const sdllm_lm_head_params& p);
 hipError_t launch_lm_head_unmask(const sdllm_lm_head_params& p, const void* hidden, const void* weight,
                                  int32_t* tokens, uint8_t* masked, float* confidence, int32_t* n_committed,

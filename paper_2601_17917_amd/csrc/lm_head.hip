@@ -358,7 +358,18 @@ static LmPlan lm_plan(const sdllm_lm_head_params& p) {
   return pl;
 }
 
-int lm_head_tiles(const sdllm_lm_head_params& p) { return lm_plan(p).ntile; }
+static size_t lm_lds_bytes(int bm) {
+  const int nst = bm >= 128 ? 3 : 2;                 // LmShape::NST
+  return (size_t)nst * kLmStageBytes + bm * sizeof(int) + (size_t)kLmWaves * bm * sizeof(Partial);
+}
+
+void lm_head_plan(const sdllm_lm_head_params& p, sdllm_lm_head_plan* plan) {
+  const LmPlan pl = lm_plan(p);
+  plan->rows_per_chunk = pl.bm; plan->vocab_rows_per_tile = pl.bn; plan->vocab_tiles = pl.ntile;
+  plan->row_chunks = pl.nchunk;
+  plan->workgroups = ((pl.ntile + kNumXCDs - 1) / kNumXCDs) * pl.nchunk * kNumXCDs;
+  plan->lds_bytes = (int32_t)lm_lds_bytes(pl.bm);
+}
 
 size_t lm_head_workspace_bytes(const sdllm_lm_head_params& p) {
   return (size_t)p.B * p.K * lm_plan(p).ntile * sizeof(Partial);
@@ -366,7 +377,8 @@ size_t lm_head_workspace_bytes(const sdllm_lm_head_params& p) {
 
 template <int BM, int WNB, int PF>
 static hipError_t launch_rows(const LmHeadArgs& r, unsigned grid, hipStream_t stream) {
-  const size_t lds = LmShape<BM, WNB, PF>::NST * kLmStageBytes + BM * sizeof(int) + kLmWaves * BM * sizeof(Partial);
+  static_assert(LmShape<BM, WNB, PF>::NST == (BM >= 128 ? 3 : 2), "lm_lds_bytes");
+  const size_t lds = lm_lds_bytes(BM);
   static bool attr_set = false;                     // > 64 KiB of dynamic LDS needs the opt-in, once
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_rows_kernel<BM, WNB, PF>),

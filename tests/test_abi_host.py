@@ -36,6 +36,7 @@ def test_struct_layouts_match_header():
     assert ctypes.sizeof(sd.AppendParams) == 48
     assert sd.AppendParams.cache_layer_stride.offset == 32
     assert ctypes.sizeof(sd.AttnPlan) == 16
+    assert ctypes.sizeof(sd.LmHeadPlan) == 24
     assert ctypes.sizeof(sd.LmHeadParams) == 56
     assert sd.LmHeadParams.ld_h.offset == 16 and sd.LmHeadParams.tau0.offset == 32
 
@@ -239,3 +240,19 @@ def test_probe_validation(lib):
     assert lib.sdllm_probe_mfma_bf16(0, 0, vp(4096), None, ctypes.byref(fl)) == sd.ERR_INVALID_ARG
     assert lib.sdllm_probe_mfma_bf16(10, 2, vp(4096), None, ctypes.byref(fl)) == sd.ERR_INVALID_ARG
     assert lib.sdllm_probe_mfma_bf16(10, 0, None, None, ctypes.byref(fl)) == sd.ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("B,K,V,Hd", [(1, 1, 1, 32), (1, 32, 126464, 4096), (2, 32, 5000, 512), (3, 40, 777, 96),
+                                       (8, 32, 126464, 4096), (16, 32, 152064, 3584), (9, 32, 700, 1024), (16, 4096, 100, 32)])
+def test_lm_head_plan_is_consistent(lib, B, K, V, Hd):
+    p = sd.lm_head_params(B, K, V, Hd, Hd, Hd, 0.9, 0.3)
+    pl = sd.plan_lm_head(p)
+    rows = B * K
+    assert pl.rows_per_chunk in (32, 64, 128, 256) and pl.vocab_rows_per_tile in (128, 256)
+    assert (pl.rows_per_chunk >= min(rows, 256)) and (rows > 32 or pl.rows_per_chunk == 32)
+    assert pl.vocab_tiles * pl.vocab_rows_per_tile >= V > (pl.vocab_tiles - 1) * pl.vocab_rows_per_tile
+    assert pl.row_chunks * pl.rows_per_chunk >= rows > (pl.row_chunks - 1) * pl.rows_per_chunk
+    assert pl.workgroups % 8 == 0 and pl.workgroups >= pl.vocab_tiles * pl.row_chunks
+    assert pl.workgroups < pl.vocab_tiles * pl.row_chunks + 8 * pl.row_chunks
+    assert 64 * 1024 <= pl.lds_bytes <= 160 * 1024
+    assert sd.lm_head_unmask_workspace_bytes(p) == rows * pl.vocab_tiles * 12
