@@ -114,6 +114,8 @@ def _oracle(h, W, tokens, masked, tau0, alpha, **kw):
     (1, 8, 32, 1), (1, 32, 64, 100), (2, 16, 96, 129), (1, 32, 1056, 1000), (1, 32, 512, 4099),
     (2, 32, 288, 300), (3, 20, 544, 777), (1, 64, 1024, 2048),
     (5, 32, 160, 513), (3, 64, 416, 1500), (9, 32, 1024, 700), (2, 160, 256, 2000),
+    (4, 600, 64, 300),        # 2400 positions: ten passes of the mask scan, ten row chunks, two triples per position
+    (2, 600, 64, 20000),      # 79 triples per position and more positions than the commit kernel has lanes to spare
 ])
 def test_lm_head_shapes(gpu_lib, B, K, Hd, V):
     h, W, tokens, masked, hd, Wd = _host_case(B, K, Hd, V, seed=B * 1000 + K + Hd + V)
