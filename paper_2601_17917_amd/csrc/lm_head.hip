@@ -339,13 +339,179 @@ __global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB, PF_>::MIN_WAVES)) voi
   }
 }
 
+
+// ---------------------------------------------------------------------------------------------------
+// Stream shape (at most 32 positions in the block): the call is a read of W, so the kernel is built around
+// that stream.  A workgroup owns kStRows = 512 consecutive vocabulary rows and walks Hd in chunks of 512
+// elements; within a chunk it visits its 16 sub-tiles of 32 rows one after the other, so that every
+// wave-wide load is ONE KILOBYTE OF ONE ROW of W (registers -> LDS, swizzled, two stages, one barrier per
+// sub-tile), and the matrix instructions read W back from LDS in operand layout.  The hidden rows never
+// touch LDS: wave (ib, jb) computes vocabulary block ib x row block jb of every sub-tile, its B operands of
+// a chunk (16 k-steps) sit in registers for all 16 sub-tiles and the next chunk's are asked for two
+// sub-tiles ahead.  All 16 x (16 x 16) accumulators of a wave stay in registers until the end: one triple
+// per (position, 512 vocabulary rows), a quarter of what the 128-row tiles of the other shapes write.
+constexpr int kStSub = 32;                 // vocabulary rows per sub-tile
+constexpr int kStTT = 16;                  // sub-tiles per workgroup
+constexpr int kStRows = kStSub * kStTT;    // vocabulary rows per workgroup
+constexpr int kStKC = 512;                 // elements of Hd per chunk (1 KB per row)
+constexpr int kStKS = kStKC / 32;          // k-steps per chunk
+constexpr int kStStage = kStSub * kStKC * 2;   // 32 KB
+
+__global__ __launch_bounds__(kLmThreads) void lm_head_stream_kernel(LmHeadArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  unsigned char* stage = lds_raw;                                            // 2 x kStStage
+  int* row_of = reinterpret_cast<int*>(lds_raw + 2 * kStStage);              // 32 compacted row ids (-1 = none)
+  Partial* red = reinterpret_cast<Partial*>(row_of + 32);                    // [waves][16]
+  __shared__ int wsum[kLmWaves];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int tile = blockIdx.x;                                               // < a.ntile by the grid size
+
+  // ---- compact the masked rows (rows_total <= 32 here, the loop is the general one)
+  int running = 0;
+  for (int base = 0; base < a.rows_total; base += kLmThreads) {
+    const int i = base + tid;
+    const bool f = i < a.rows_total && a.masked[i] != 0;
+    const unsigned long long bal = __ballot(f);
+    const int rank = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) wsum[wave] = __popcll(bal);
+    __syncthreads();
+    int pre = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kLmWaves; ++w) { const int c = wsum[w]; pre += (w < wave) ? c : 0; tot += c; }
+    const int ci = running + pre + rank;
+    if (f && ci < 32) row_of[ci] = i;
+    running += tot;
+    __syncthreads();
+  }
+  const int n_valid = min(running, 32);            // uniform
+  if (n_valid <= 0) return;
+  if (tid < 32 && tid >= n_valid) row_of[tid] = -1;
+  __syncthreads();
+
+  const int NCH = (a.Hd + kStKC - 1) / kStKC;      // chunks of Hd
+  const int NU = NCH * kStTT;                      // (chunk, sub-tile) steps of the walk
+  const int c0 = tile % NCH;                       // this workgroup's rotation of the chunk order
+  const int q = lane >> 4, l16 = lane & 15;
+  const int ib = wave & 1, jb = wave >> 1;
+  const unsigned klast = (unsigned)(a.Hd - 8);     // last whole 16-byte piece of a row
+
+  // W staging: this wave moves rows 8 wave + i (i = 0..7) of a sub-tile, lane l the l-th 16 bytes of the chunk
+  const long long vrow0 = (long long)tile * kStRows + 8 * wave;
+  unsigned sdst[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int r = 8 * wave + i;
+    sdst[i] = (unsigned)(r * (kStKC * 2) + ((lane ^ (r & 15)) << 4));
+  }
+  auto load_w_sub = [&](int u, u32x4 (&dst)[8]) {          // step u of the walk (clamped to the last one)
+    const int uc = min(u, NU - 1);
+    const int kc = uc / kStTT, t = uc - kc * kStTT;
+    int kcw = kc + c0; kcw -= (kcw >= NCH) ? NCH : 0;
+    const unsigned k = min((unsigned)(kcw * kStKC + 8 * lane), klast);     // pieces past Hd: any valid piece
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const long long n = min(vrow0 + t * kStSub + i, (long long)a.V - 1);   // rows past V: any valid row
+      dst[i] = *reinterpret_cast<const u32x4*>(a.weight + n * a.ld_w + k);
+    }
+  };
+  // B operands of a chunk for this wave's row block: row jb * 16 + l16, k-step ks, elements 8 q .. 8 q + 7
+  const long long hrow = (long long)max(row_of[jb * 16 + l16], 0) * a.ld_h;
+  auto load_b_chunk = [&](int kc, bf16x8 (&dst)[kStKS]) {  // chunk at walk position kc (clamped); zeros past Hd
+    int kcw = min(kc, NCH - 1) + c0; kcw -= (kcw >= NCH) ? NCH : 0;
+#pragma unroll
+    for (int ks = 0; ks < kStKS; ++ks) {
+      const unsigned k = (unsigned)(kcw * kStKC + 32 * ks + 8 * q);
+      const unsigned keep = (k < (unsigned)a.Hd) ? 0xffffffffu : 0u;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(a.hidden + hrow + min(k, klast));
+      dst[ks] = __builtin_bit_cast(bf16x8, v & u32x4{keep, keep, keep, keep});
+    }
+  };
+  // A operand of k-step ks: row ib * 16 + l16 of the sub-tile, piece 4 ks + q, swizzled by the row
+  const unsigned aoff = (unsigned)((ib * 16 + l16) * (kStKC * 2));
+
+  f32x4 acc[kStTT];
+#pragma unroll
+  for (int t = 0; t < kStTT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // ---- prologue: step 0 into stage 0, step 1 into registers, the first chunk's B operands
+  u32x4 wreg[2][8];
+  load_w_sub(0, wreg[0]);
+  load_w_sub(1, wreg[1]);
+  bf16x8 bcur[kStKS], bnext[kStKS];
+  load_b_chunk(0, bcur);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(stage + sdst[i]) = wreg[0][i];
+  __syncthreads();
+
+  // ---- main loop: chunks of Hd (rotated), 16 sub-tiles each; step u = kc * 16 + t reads stage u & 1
+  for (int kc = 0; kc < NCH; ++kc) {
+#pragma unroll
+    for (int t = 0; t < kStTT; ++t) {
+      const int u = kc * kStTT + t;
+      // two steps ahead into the register set that was written to LDS one step ago
+      load_w_sub(u + 2, wreg[t & 1]);
+      if (t == kStTT - 2) load_b_chunk(kc + 1, bnext);
+      __builtin_amdgcn_sched_barrier(0);
+      const unsigned char* cur = stage + (t & 1) * kStStage;
+#pragma unroll
+      for (int ks = 0; ks < kStKS; ++ks) {
+        const bf16x8 aop = *reinterpret_cast<const bf16x8*>(cur + aoff + (unsigned)(((4 * ks + q) ^ l16) << 4));
+        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bcur[ks], acc[t], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      // step u + 1 (asked for one step ago) into the other stage, which step u - 1 has finished reading
+      unsigned char* nxt = stage + ((t + 1) & 1) * kStStage;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(nxt + sdst[i]) = wreg[(t + 1) & 1][i];
+      __syncthreads();
+    }
+#pragma unroll
+    for (int ks = 0; ks < kStKS; ++ks) bcur[ks] = bnext[ks];
+  }
+
+  // ---- row reduction: this lane holds, for row jb * 16 + l16, the ids t * 32 + ib * 16 + 4 q + r of the tile
+  float m = kNegBig; int idx = 0x7fffffff;
+#pragma unroll
+  for (int t = 0; t < kStTT; ++t)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int n = tile * kStRows + t * kStSub + ib * 16 + 4 * q + r;
+      float v = acc[t][r];
+      if (n >= a.V) v = -INFINITY;
+      acc[t][r] = v;
+      if (v > m) { m = v; idx = n; }                 // ascending ids, strict: the lowest id keeps a tie
+    }
+  const float ml = m * kLog2e;
+  float s = 0.f;
+#pragma unroll
+  for (int t = 0; t < kStTT; ++t)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) s += fast_exp2(fmaf(acc[t][r], kLog2e, -ml));
+#pragma unroll
+  for (int off = 16; off <= 32; off <<= 1) {
+    const float m2 = __shfl_xor(m, off); const float s2 = __shfl_xor(s, off); const int i2 = __shfl_xor(idx, off);
+    merge_partial(m, s, idx, m2, s2, i2);
+  }
+  if (q == 0) red[wave * 16 + l16] = Partial{m, s, idx};
+  __syncthreads();
+  if (tid < 32 && row_of[tid] >= 0) {
+    const int rb = tid >> 4, l = tid & 15;           // row block, row inside it; its two waves are 2 rb and 2 rb + 1
+    Partial p0 = red[(2 * rb) * 16 + l];
+    const Partial p1 = red[(2 * rb + 1) * 16 + l];
+    merge_partial(p0.m, p0.s, p0.idx, p1.m, p1.s, p1.idx);
+    a.partials[(long long)row_of[tid] * a.ntile + tile] = p0;
+  }
+}
+
 // ---- host side ----
 struct LmPlan { int bm, wnb, bn, ntile, nchunk; };
 
 static LmPlan lm_plan(const sdllm_lm_head_params& p) {
   const long long rows = (long long)p.B * p.K;
   LmPlan pl;
-  if (rows <= 32) { pl.bm = 32; pl.wnb = 2; }
+  if (rows <= 32) { pl.bm = 32; pl.wnb = kStRows / 64; }      // stream shape: 512 vocabulary rows per workgroup
   else if (rows <= 64) { pl.bm = 64; pl.wnb = 2; }
   else if (rows <= 128) { pl.bm = 128; pl.wnb = 4; }
   else { pl.bm = 256; pl.wnb = 4; }
@@ -359,6 +525,7 @@ static LmPlan lm_plan(const sdllm_lm_head_params& p) {
 }
 
 static size_t lm_lds_bytes(int bm) {
+  if (bm == 32) return 2 * (size_t)kStStage + 32 * sizeof(int) + (size_t)kLmWaves * 16 * sizeof(Partial);
   const int nst = bm >= 128 ? 3 : 2;                 // LmShape::NST
   return (size_t)nst * kLmStageBytes + bm * sizeof(int) + (size_t)kLmWaves * bm * sizeof(Partial);
 }
@@ -367,7 +534,7 @@ void lm_head_plan(const sdllm_lm_head_params& p, sdllm_lm_head_plan* plan) {
   const LmPlan pl = lm_plan(p);
   plan->rows_per_chunk = pl.bm; plan->vocab_rows_per_tile = pl.bn; plan->vocab_tiles = pl.ntile;
   plan->row_chunks = pl.nchunk;
-  plan->workgroups = ((pl.ntile + kNumXCDs - 1) / kNumXCDs) * pl.nchunk * kNumXCDs;
+  plan->workgroups = pl.bm == 32 ? pl.ntile : ((pl.ntile + kNumXCDs - 1) / kNumXCDs) * pl.nchunk * kNumXCDs;
   plan->lds_bytes = (int32_t)lm_lds_bytes(pl.bm);
 }
 
@@ -402,7 +569,20 @@ hipError_t launch_lm_head_unmask(const sdllm_lm_head_params& p, const void* hidd
   r.ntile = pl.ntile; r.nchunk = pl.nchunk;
   const unsigned grid = (unsigned)(((pl.ntile + kNumXCDs - 1) / kNumXCDs) * pl.nchunk * kNumXCDs);
   hipError_t e;
-  if (pl.bm == 32) e = launch_rows<32, 2, 8>(r, grid, stream);
+  if (pl.bm == 32) {
+    const size_t lds = lm_lds_bytes(32);
+    static bool attr_set = false;
+    e = hipSuccess;
+    if (!attr_set) {
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_stream_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      attr_set = (e == hipSuccess);
+    }
+    if (e == hipSuccess) {
+      hipLaunchKernelGGL(lm_head_stream_kernel, dim3((unsigned)pl.ntile), dim3(kLmThreads), lds, stream, r);
+      e = hipGetLastError();
+    }
+  }
   else if (pl.bm == 64) e = launch_rows<64, 2, 8>(r, grid, stream);
   else if (pl.bm == 128) e = launch_rows<128, 4, 8>(r, grid, stream);
   else e = launch_rows<256, 4, 4>(r, grid, stream);

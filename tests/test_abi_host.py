@@ -248,11 +248,15 @@ def test_lm_head_plan_is_consistent(lib, B, K, V, Hd):
     p = sd.lm_head_params(B, K, V, Hd, Hd, Hd, 0.9, 0.3)
     pl = sd.plan_lm_head(p)
     rows = B * K
-    assert pl.rows_per_chunk in (32, 64, 128, 256) and pl.vocab_rows_per_tile in (128, 256)
+    assert pl.rows_per_chunk in (32, 64, 128, 256) and pl.vocab_rows_per_tile in (128, 256, 512)
+    assert (pl.vocab_rows_per_tile == 512) == (rows <= 32)          # the stream shape and only it
     assert (pl.rows_per_chunk >= min(rows, 256)) and (rows > 32 or pl.rows_per_chunk == 32)
     assert pl.vocab_tiles * pl.vocab_rows_per_tile >= V > (pl.vocab_tiles - 1) * pl.vocab_rows_per_tile
     assert pl.row_chunks * pl.rows_per_chunk >= rows > (pl.row_chunks - 1) * pl.rows_per_chunk
-    assert pl.workgroups % 8 == 0 and pl.workgroups >= pl.vocab_tiles * pl.row_chunks
-    assert pl.workgroups < pl.vocab_tiles * pl.row_chunks + 8 * pl.row_chunks
+    if rows <= 32:
+        assert pl.workgroups == pl.vocab_tiles and pl.row_chunks == 1
+    else:
+        assert pl.workgroups % 8 == 0 and pl.workgroups >= pl.vocab_tiles * pl.row_chunks
+        assert pl.workgroups < pl.vocab_tiles * pl.row_chunks + 8 * pl.row_chunks
     assert 64 * 1024 <= pl.lds_bytes <= 160 * 1024
     assert sd.lm_head_unmask_workspace_bytes(p) == rows * pl.vocab_tiles * 12
