@@ -17,9 +17,11 @@
 //     lane exchanges, then across the four waves through LDS.
 //   * Row chunks of one vocabulary tile get workgroup ids that are equal mod 8 and adjacent in
 //     dispatch order: same XCD, same L2, so W comes from HBM once.
-//   * Shapes: up to 32 / 64 rows the kernel is a W stream (two workgroups per CU); up to 128 / 256 rows
-//     per chunk it is bound by the matrix pipe (one wave per SIMD, accumulators in the accumulation
-//     registers, B operands through a register ring fed across chunk boundaries).
+//   * Shapes: up to 64 rows the kernel is a W stream (two workgroups per CU); up to 128 / 256 rows per
+//     chunk it is bound by the matrix pipe (one wave per SIMD, accumulators in the accumulation
+//     registers, B operands through a register ring fed across chunk boundaries).  Blocks of at most
+//     32 positions take lm_head_stream_kernel further down, which turns the roles around: W goes through
+//     LDS in 1 KB row pieces and the hidden operands stay in registers.
 #include "common.h"
 #include "unmask_common.h"
 #include <cstdlib>
