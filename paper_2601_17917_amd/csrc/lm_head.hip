@@ -17,14 +17,13 @@
 //     lane exchanges, then across the four waves through LDS.
 //   * Row chunks of one vocabulary tile get workgroup ids that are equal mod 8 and adjacent in
 //     dispatch order: same XCD, same L2, so W comes from HBM once.
-//   * Shapes: up to 64 rows the kernel is a W stream (two workgroups per CU); up to 128 / 256 rows per
+//   * Shapes: up to 64 rows the kernel is a W stream (two workgroups per CU); with 256 rows per
 //     chunk it is bound by the matrix pipe (one wave per SIMD, accumulators in the accumulation
 //     registers, B operands through a register ring fed across chunk boundaries).  Blocks of at most
 //     32 positions take lm_head_stream_kernel further down, which turns the roles around: W goes through
 //     LDS in 1 KB row pieces and the hidden operands stay in registers.
 #include "common.h"
 #include "unmask_common.h"
-#include <cstdlib>
 
 namespace sdllm {
 
@@ -515,11 +514,7 @@ static LmPlan lm_plan(const sdllm_lm_head_params& p) {
   LmPlan pl;
   if (rows <= 32) { pl.bm = 32; pl.wnb = kStRows / 64; }      // stream shape: 512 vocabulary rows per workgroup
   else if (rows <= 64) { pl.bm = 64; pl.wnb = 2; }
-  else if (rows <= 128) { pl.bm = 128; pl.wnb = 4; }
-  else { pl.bm = 256; pl.wnb = 4; }
-  // tuning knob for sweeps: SDLLM_LM_BM=128 forces 128-row chunks above 128 rows (read once)
-  static const int forced = [] { const char* e = getenv("SDLLM_LM_BM"); return e ? atoi(e) : 0; }();
-  if (forced == 128 && rows > 128) pl.bm = 128;
+  else { pl.bm = 256; pl.wnb = 4; }    // also for 65..128 rows: a half-empty 256-row tile beat 128-row tiles
   pl.bn = kLmWaves * pl.wnb * 16;
   pl.ntile = (p.V + pl.bn - 1) / pl.bn;
   pl.nchunk = (int)((rows + pl.bm - 1) / pl.bm);
@@ -586,7 +581,6 @@ hipError_t launch_lm_head_unmask(const sdllm_lm_head_params& p, const void* hidd
     }
   }
   else if (pl.bm == 64) e = launch_rows<64, 2, 8>(r, grid, stream);
-  else if (pl.bm == 128) e = launch_rows<128, 4, 8>(r, grid, stream);
   else e = launch_rows<256, 4, 4>(r, grid, stream);
   if (e != hipSuccess) return e;
 

@@ -248,7 +248,7 @@ def test_lm_head_plan_is_consistent(lib, B, K, V, Hd):
     p = sd.lm_head_params(B, K, V, Hd, Hd, Hd, 0.9, 0.3)
     pl = sd.plan_lm_head(p)
     rows = B * K
-    assert pl.rows_per_chunk in (32, 64, 128, 256) and pl.vocab_rows_per_tile in (128, 256, 512)
+    assert pl.rows_per_chunk in (32, 64, 256) and pl.vocab_rows_per_tile in (128, 256, 512)
     assert (pl.vocab_rows_per_tile == 512) == (rows <= 32)          # the stream shape and only it
     assert (pl.rows_per_chunk >= min(rows, 256)) and (rows > 32 or pl.rows_per_chunk == 32)
     assert pl.vocab_tiles * pl.vocab_rows_per_tile >= V > (pl.vocab_tiles - 1) * pl.vocab_rows_per_tile
