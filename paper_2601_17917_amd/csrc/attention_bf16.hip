@@ -76,25 +76,45 @@ __device__ __forceinline__ void dma16_sbase(unsigned lds_addr, const void* sbase
 // the LDS address and the global address alike, so transfer j carries offset j KiB and its lane offset
 // voffj has those j KiB taken off beforehand.  One wait state separates the write of m0 from the
 // first transfer that reads it.
-template <int NT>
+// ONCE: every byte of K/V is read by exactly one workgroup of the launch (one query tile per K/V head and
+// split); the transfers then carry the nontemporal hint (cfg3A 31.1 -> 28.6 us).  Where query tiles share a
+// K/V stream through L2 the hint costs 4-6 %, so it is left off there.
+template <int NT, bool ONCE>
 __device__ __forceinline__ void dma_slab(unsigned lds_addr, const void* sbase, const unsigned (&voffj)[4]) {
   static_assert(NT == 2 || NT == 4, "transfers per slab");
-  if (NT == 4)
+  if constexpr (NT == 4 && ONCE)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %2, %1 nt\n\t"
+                 "global_load_lds_dwordx4 %3, %1 offset:1024 nt\n\t"
+                 "global_load_lds_dwordx4 %4, %1 offset:2048 nt\n\t"
+                 "global_load_lds_dwordx4 %5, %1 offset:3072 nt"
+                 :: "s"(lds_addr), "s"(sbase), "v"(voffj[0]), "v"(voffj[1]), "v"(voffj[2]), "v"(voffj[3]) : "memory", "m0");
+  else if constexpr (NT == 4)
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
                  "global_load_lds_dwordx4 %2, %1\n\t"
                  "global_load_lds_dwordx4 %3, %1 offset:1024\n\t"
                  "global_load_lds_dwordx4 %4, %1 offset:2048\n\t"
                  "global_load_lds_dwordx4 %5, %1 offset:3072"
                  :: "s"(lds_addr), "s"(sbase), "v"(voffj[0]), "v"(voffj[1]), "v"(voffj[2]), "v"(voffj[3]) : "memory", "m0");
+  else if constexpr (ONCE)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %2, %1 nt\n\t"
+                 "global_load_lds_dwordx4 %3, %1 offset:1024 nt"
+                 :: "s"(lds_addr), "s"(sbase), "v"(voffj[0]), "v"(voffj[1]) : "memory", "m0");
   else
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
                  "global_load_lds_dwordx4 %2, %1\n\t"
                  "global_load_lds_dwordx4 %3, %1 offset:1024"
                  :: "s"(lds_addr), "s"(sbase), "v"(voffj[0]), "v"(voffj[1]) : "memory", "m0");
 }
+template <bool ONCE>
 __device__ __forceinline__ void dma16_vaddr(unsigned lds_addr, const void* vaddr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-               :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(vaddr) : "memory", "m0");
+  if constexpr (ONCE)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt"
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(vaddr) : "memory", "m0");
+  else
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(vaddr) : "memory", "m0");
 }
 // A pointer that is the same in every lane, moved into a scalar register pair (64-bit address
 // arithmetic with products is done on the vector ALU; everything derived from the result would
@@ -172,20 +192,20 @@ __device__ __forceinline__ SlabRanges slab_ranges(const AttnArgs& a, int wave) {
 // 16 consecutive rows of one source tensor starting at source row `row0`: scalar bases, the lane's
 // constant offsets, no per-lane address arithmetic.  The lane offsets kgj / vgj count rows from the
 // start of the tile, hence the step back by the wave's 16*wave rows.
-template <int D>
+template <int D, bool ONCE>
 __device__ __forceinline__ void issue_slab(const Lane<D>& L, unsigned sk, const uint16_t* kp, const uint16_t* vp, long long row0) {
   using S = Shape<D>;
   const unsigned char* kt = reinterpret_cast<const unsigned char*>(kp) + (row0 - 16 * L.wave) * S::ROWB;
   const unsigned char* vt = reinterpret_cast<const unsigned char*>(vp) + (row0 - 16 * L.wave) * S::ROWB;
   static_assert(S::RPI * S::ROWB == 1024, "a transfer moves 1 KiB");
-  dma_slab<S::IPT>(sk, kt, L.kgj);
-  dma_slab<S::IPT>(sk + S::VBASE, vt, L.vgj);
+  dma_slab<S::IPT, ONCE>(sk, kt, L.kgj);
+  dma_slab<S::IPT, ONCE>(sk + S::VBASE, vt, L.vgj);
 }
 
 // Puts key tile `tile` in flight into ring stage `stage`: 2 * IPT transfers per wave, which moves
 // rows 16*wave .. 16*wave+15 of the tile.  `ka` holds the keep_idx bounds of these rows on entry and
 // those of the next tile on return.
-template <int D>
+template <int D, bool ONCE>
 __device__ __forceinline__ void issue_tile(const AttnArgs& a, const Lane<D>& L, const SlabRanges& R,
                                            const uint16_t* kc, const uint16_t* vc,
                                            const uint16_t* kb, const uint16_t* vb, const uint16_t* ks, const uint16_t* vs,
@@ -198,11 +218,11 @@ __device__ __forceinline__ void issue_tile(const AttnArgs& a, const Lane<D>& L, 
   // cache, the block, or a run of the suffix that keep_idx maps to consecutive rows: increasing
   // indices whose ends differ by 15) are one contiguous slab.
   if (tile <= R.tc) {
-    issue_slab<D>(L, sk, kc, vc, r0);
+    issue_slab<D, ONCE>(L, sk, kc, vc, r0);
   } else if (tile >= R.tb0 && tile <= R.tb1) {
-    issue_slab<D>(L, sk, kb, vb, r0 - a.P);
+    issue_slab<D, ONCE>(L, sk, kb, vb, r0 - a.P);
   } else if (tile >= R.ts0 && tile <= R.ts1 && ka.last - ka.first == 15) {
-    issue_slab<D>(L, sk, ks, vs, ka.first);
+    issue_slab<D, ONCE>(L, sk, ks, vs, ka.first);
   } else {
     // rows from more than one place, a gap in keep_idx, the ragged tail: per-row addresses without a
     // divergent branch.  keep_idx is read through the constant address space with uniform indices
@@ -239,9 +259,9 @@ __device__ __forceinline__ void issue_tile(const AttnArgs& a, const Lane<D>& L, 
       vpp[j] = reinterpret_cast<const unsigned char*>(vp + off) + (L.vgj[j] + 1024 * j - (16 * L.wave + rl) * S::ROWB);
     }
 #pragma unroll
-    for (int j = 0; j < S::IPT; ++j) dma16_vaddr(sk + j * S::RPI * S::ROWB, kpp[j]);
+    for (int j = 0; j < S::IPT; ++j) dma16_vaddr<ONCE>(sk + j * S::RPI * S::ROWB, kpp[j]);
 #pragma unroll
-    for (int j = 0; j < S::IPT; ++j) dma16_vaddr(sv + j * S::RPI * S::ROWB, vpp[j]);
+    for (int j = 0; j < S::IPT; ++j) dma16_vaddr<ONCE>(sv + j * S::RPI * S::ROWB, vpp[j]);
   }
   load_keep_ahead(a, L.wave, tile + 1, ka);
 }
@@ -392,7 +412,7 @@ __device__ __forceinline__ void compute_tile(const AttnArgs& a, const Lane<D>& L
   }
 }
 
-template <int D, int RB>
+template <int D, int RB, bool ONCE>
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   using S = Shape<D>;
   constexpr int CPR = S::CPR, RPI = S::RPI, IPT = S::IPT, R256 = S::R256, NS = S::NS, NDB = S::NDB, ROWB = S::ROWB;
@@ -449,7 +469,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   const SlabRanges R = slab_ranges(a, wave);
   KeepAhead ka;
   load_keep_ahead(a, wave, t0, ka);
-  issue_tile<D>(a, L, R, kc, vc, kb, vb, ks, vs, t0, 0, ka);
+  issue_tile<D, ONCE>(a, L, R, kc, vc, kb, vb, ks, vs, t0, 0, ka);
 
   // ---- query rows of this wave, as MFMA B operands (lane: row l16, d = 32*s + 8*G .. +7)
   const int row_base = qt * (64 * RB) + wave * (16 * RB);
@@ -483,12 +503,12 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   for (int t = t0; t < t1; t += 2) {
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
-    if (t + 1 < t1) issue_tile<D>(a, L, R, kc, vc, kb, vb, ks, vs, t + 1, 1, ka);
+    if (t + 1 < t1) issue_tile<D, ONCE>(a, L, R, kc, vc, kb, vb, ks, vs, t + 1, 1, ka);
     compute_tile<D, RB, 0>(a, L, lds, t, qreg, o, m, thr, lsum);
     if (t + 1 >= t1) break;
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
-    if (t + 2 < t1) issue_tile<D>(a, L, R, kc, vc, kb, vb, ks, vs, t + 2, 0, ka);
+    if (t + 2 < t1) issue_tile<D, ONCE>(a, L, R, kc, vc, kb, vb, ks, vs, t + 2, 0, ka);
     compute_tile<D, RB, 1>(a, L, lds, t + 1, qreg, o, m, thr, lsum);
   }
 
@@ -610,23 +630,26 @@ size_t attention_bf16_workspace_bytes(const sdllm_attn_params& p, const AttnPlan
   return rows * pl.kv_splits * (size_t)(p.D + 2) * sizeof(float);
 }
 
-template <int D, int RB>
+template <int D, int RB, bool ONCE>
 static hipError_t launch_main(const AttnArgs& a, const AttnPlan& pl, hipStream_t stream) {
   constexpr size_t lds_bytes = Shape<D>::LDS_BYTES;
   static bool attr_set = false;                     // benign race: the call is idempotent
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<D, RB>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<D, RB, ONCE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((attn_bf16_kernel<D, RB>), dim3(pl.workgroups), dim3(256), lds_bytes, stream, a);
+  hipLaunchKernelGGL((attn_bf16_kernel<D, RB, ONCE>), dim3(pl.workgroups), dim3(256), lds_bytes, stream, a);
   return hipGetLastError();
 }
 
 template <int D>
 static hipError_t launch_d(const AttnArgs& a, const AttnPlan& pl, hipStream_t stream) {
-  return pl.rb == 2 ? launch_main<D, 2>(a, pl, stream) : launch_main<D, 1>(a, pl, stream);
+  // one query tile per K/V head (and split): every K/V byte is read by one workgroup only
+  if (pl.q_tiles == 1)
+    return pl.rb == 2 ? launch_main<D, 2, true>(a, pl, stream) : launch_main<D, 1, true>(a, pl, stream);
+  return pl.rb == 2 ? launch_main<D, 2, false>(a, pl, stream) : launch_main<D, 1, false>(a, pl, stream);
 }
 
 hipError_t launch_attention_bf16(const sdllm_attn_params& p, const AttnPlan& pl,
