@@ -594,6 +594,10 @@ AttnPlan plan_attention_bf16(const sdllm_attn_params& p) {
   // 32 query rows per wave (128 per workgroup) pay off only when many query rows share one K/V
   // stream (dense suffix); measured: 1024 rows -> 1.4x faster, 448 rows (GQA 7:1) -> 8 % slower
   pl.rb = Rtot >= 512 ? 2 : 1;
+  // ... and when one 128-row tile then covers a K/V head with a long key stream: every K/V byte is read by
+  // one workgroup only, which lets the transfers carry the nontemporal hint (32 layers x 5248 keys, 128 rows:
+  // 2650 -> 2510 us per step; with 1312 keys the extra key splits it takes cost more than it gains)
+  if (Rtot > 64 && Rtot <= 128 && Nkv >= 64 * kKeyTile) pl.rb = 2;
   if (env_rb == 1 || env_rb == 2) pl.rb = env_rb;
   // Two ring stages, two workgroups per CU.  Deeper rings (3, 4 stages: one workgroup per CU) were
   // measured and are slower at every shape: with one wave per SIMD the per-tile latencies of the
