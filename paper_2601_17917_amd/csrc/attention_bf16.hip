@@ -611,7 +611,9 @@ AttnPlan plan_attention_bf16(const sdllm_attn_params& p) {
   if (p.kv_splits > 0) {
     ns = p.kv_splits;
   } else {
-    ns = (2LL * kNumCUs + base - 1) / base;        // aim at two workgroups per CU ...
+    // aim at two workgroups per CU (one when they are 128-row tiles: 32 layers x 5248 keys x 128 rows
+    // measured 2402 us per step with 2 splits, 2480 with 4) ...
+    ns = ((pl.rb == 2 ? 1LL : 2LL) * kNumCUs + base - 1) / base;
     // ... but keep a split long enough to amortise its merge: 16 key tiles once there is a workgroup
     // per CU without splitting, 8 with one per two CUs, 2 when the launch would otherwise leave most
     // of the chip idle (sweeps: 256 workgroups x 17 tiles -> 1 split, x 82 -> 2; 128 x 20 -> 2; 32 x 11 -> 4)
