@@ -17,11 +17,11 @@
 //     lane exchanges, then across the four waves through LDS.
 //   * Row chunks of one vocabulary tile get workgroup ids that are equal mod 8 and adjacent in
 //     dispatch order: same XCD, same L2, so W comes from HBM once.
-//   * Shapes: up to 64 rows the kernel is a W stream (two workgroups per CU); with 256 rows per
-//     chunk it is bound by the matrix pipe (one wave per SIMD, accumulators in the accumulation
-//     registers, B operands through a register ring fed across chunk boundaries).  Blocks of at most
-//     32 positions take lm_head_stream_kernel further down, which turns the roles around: W goes through
-//     LDS in 1 KB row pieces and the hidden operands stay in registers.
+//   * Shapes: with 256 rows per chunk (more than 64 positions) lm_head_rows_kernel is bound by the
+//     matrix pipe (one wave per SIMD, accumulators in the accumulation registers, B operands through a
+//     register ring fed across chunk boundaries).  Calls of at most 64 positions are a read of W and
+//     take the two stream kernels further down, which turn the roles around: W goes through LDS in
+//     1 KB row pieces, the hidden operands stay in registers (up to 32 positions) or in LDS (33..64).
 #include "common.h"
 #include "unmask_common.h"
 
@@ -507,6 +507,181 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_stream_kernel(LmHeadArgs a
   }
 }
 
+// Stream shape for 33..64 positions: same walk and the same W route as lm_head_stream_kernel, but a wave owns two
+// 16-row blocks of positions, and the B operands of two chunks for two blocks (256 registers) do not fit beside
+// its 128 accumulator registers.  The hidden chunk (64 rows x 1 KB) therefore lives in LDS, one stage: the next
+// chunk is asked for at the start of a chunk, waits in registers, and is written between two barriers at the
+// chunk's end; B operands are read from LDS per matrix instruction (a stream-bound kernel has the LDS cycles).
+constexpr int kSt2Rows = 64;                               // positions per workgroup
+constexpr int kSt2Hid = kSt2Rows * kStKC * 2;              // 64 KB: one hidden chunk
+
+__global__ __launch_bounds__(kLmThreads) void lm_head_stream64_kernel(LmHeadArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  unsigned char* stage = lds_raw;                                            // 2 x kStStage (W ring)
+  unsigned char* hid = lds_raw + 2 * kStStage;                               // kSt2Hid (hidden chunk)
+  int* row_of = reinterpret_cast<int*>(hid + kSt2Hid);                       // 64 compacted row ids (-1 = none)
+  Partial* red = reinterpret_cast<Partial*>(row_of + kSt2Rows);              // [waves][32]
+  __shared__ int wsum[kLmWaves];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int tile = blockIdx.x;                                               // < a.ntile by the grid size
+
+  // ---- compact the masked rows (rows_total <= 64 here, the loop is the general one)
+  int running = 0;
+  for (int base = 0; base < a.rows_total; base += kLmThreads) {
+    const int i = base + tid;
+    const bool f = i < a.rows_total && a.masked[i] != 0;
+    const unsigned long long bal = __ballot(f);
+    const int rank = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) wsum[wave] = __popcll(bal);
+    __syncthreads();
+    int pre = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kLmWaves; ++w) { const int c = wsum[w]; pre += (w < wave) ? c : 0; tot += c; }
+    const int ci = running + pre + rank;
+    if (f && ci < kSt2Rows) row_of[ci] = i;
+    running += tot;
+    __syncthreads();
+  }
+  const int n_valid = min(running, kSt2Rows);      // uniform
+  if (n_valid <= 0) return;
+  if (tid < kSt2Rows && tid >= n_valid) row_of[tid] = -1;
+  __syncthreads();
+
+  const int NCH = (a.Hd + kStKC - 1) / kStKC;      // chunks of Hd
+  const int NU = NCH * kStTT;                      // (chunk, sub-tile) steps of the walk
+  const int c0 = tile % NCH;                       // this workgroup's rotation of the chunk order
+  const int q = lane >> 4, l16 = lane & 15;
+  const int ib = wave & 1, jw = wave >> 1;         // vocabulary block of a sub-tile; row blocks 2 jw, 2 jw + 1
+  const unsigned klast = (unsigned)(a.Hd - 8);     // last whole 16-byte piece of a row
+
+  // W staging: this wave moves rows 8 wave + i (i = 0..7) of a sub-tile, lane l the l-th 16 bytes of the chunk
+  const long long vrow0 = (long long)tile * kStRows + 8 * wave;
+  unsigned sdst[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int r = 8 * wave + i;
+    sdst[i] = (unsigned)(r * (kStKC * 2) + ((lane ^ (r & 15)) << 4));
+  }
+  auto load_w_sub = [&](int u, u32x4 (&dst)[8]) {          // step u of the walk (clamped to the last one)
+    const int uc = min(u, NU - 1);
+    const int kc = uc / kStTT, t = uc - kc * kStTT;
+    int kcw = kc + c0; kcw -= (kcw >= NCH) ? NCH : 0;
+    const unsigned k = min((unsigned)(kcw * kStKC + 8 * lane), klast);     // pieces past Hd: any valid piece
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const long long n = min(vrow0 + t * kStSub + i, (long long)a.V - 1);   // rows past V: any valid row
+      dst[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(a.weight + n * a.ld_w + k));
+    }
+  };
+  // hidden staging: this wave moves rows 16 wave + i (i = 0..15) of the chunk, lane l the l-th 16 bytes
+  unsigned hsrc[16], hdst[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int r = 16 * wave + i;
+    hsrc[i] = (unsigned)((long long)max(row_of[r], 0) * a.ld_h);           // B*K*ld_h < 2^31 is validated
+    hdst[i] = (unsigned)(r * (kStKC * 2) + ((lane ^ (r & 15)) << 4));
+  }
+  auto load_hidden = [&](int kc, u32x4 (&dst)[16]) {       // chunk at walk position kc (clamped); zeros past Hd
+    int kcw = min(kc, NCH - 1) + c0; kcw -= (kcw >= NCH) ? NCH : 0;
+    const unsigned k = (unsigned)(kcw * kStKC + 8 * lane);
+    const unsigned keep = (k < (unsigned)a.Hd) ? 0xffffffffu : 0u;
+    const unsigned kk = min(k, klast);
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      dst[i] = *reinterpret_cast<const u32x4*>(a.hidden + hsrc[i] + kk) & u32x4{keep, keep, keep, keep};
+  };
+  // operands of k-step ks: A = row ib * 16 + l16 of the sub-tile, B = row (2 jw + rb) * 16 + l16 of the hidden
+  // chunk; both piece 4 ks + q, swizzled by the row (row & 15 = l16 for both)
+  const unsigned aoff = (unsigned)((ib * 16 + l16) * (kStKC * 2));
+  const unsigned boff0 = (unsigned)(((2 * jw) * 16 + l16) * (kStKC * 2));
+  const unsigned boff1 = boff0 + 16 * (kStKC * 2);
+
+  f32x4 acc[kStTT][2];
+#pragma unroll
+  for (int t = 0; t < kStTT; ++t) { acc[t][0] = f32x4{0.f, 0.f, 0.f, 0.f}; acc[t][1] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+
+  // ---- prologue: W step 0 into stage 0, step 1 into registers, the first hidden chunk into LDS
+  u32x4 wreg[2][8];
+  u32x4 hreg[16];
+  load_w_sub(0, wreg[0]);
+  load_w_sub(1, wreg[1]);
+  load_hidden(0, hreg);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(stage + sdst[i]) = wreg[0][i];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) *reinterpret_cast<u32x4*>(hid + hdst[i]) = hreg[i];
+  __syncthreads();
+
+  for (int kc = 0; kc < NCH; ++kc) {
+    load_hidden(kc + 1, hreg);                     // waits in registers until the end of this chunk
+#pragma unroll
+    for (int t = 0; t < kStTT; ++t) {
+      const int u = kc * kStTT + t;
+      load_w_sub(u + 2, wreg[t & 1]);
+      __builtin_amdgcn_sched_barrier(0);
+      const unsigned char* cur = stage + (t & 1) * kStStage;
+#pragma unroll
+      for (int ks = 0; ks < kStKS; ++ks) {
+        const unsigned po = (unsigned)(((4 * ks + q) ^ l16) << 4);
+        const bf16x8 aop = *reinterpret_cast<const bf16x8*>(cur + aoff + po);
+        const bf16x8 b0 = *reinterpret_cast<const bf16x8*>(hid + boff0 + po);
+        const bf16x8 b1 = *reinterpret_cast<const bf16x8*>(hid + boff1 + po);
+        acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, b0, acc[t][0], 0, 0, 0);
+        acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, b1, acc[t][1], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      unsigned char* nxt = stage + ((t + 1) & 1) * kStStage;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(nxt + sdst[i]) = wreg[(t + 1) & 1][i];
+      __syncthreads();
+    }
+    // every wave has passed the barrier of the last sub-tile: nobody reads the hidden chunk any more
+#pragma unroll
+    for (int i = 0; i < 16; ++i) *reinterpret_cast<u32x4*>(hid + hdst[i]) = hreg[i];
+    __syncthreads();
+  }
+
+  // ---- row reduction: this lane holds, for row (2 jw + rb) * 16 + l16, the ids t * 32 + ib * 16 + 4 q + r
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+    float m = kNegBig; int idx = 0x7fffffff;
+#pragma unroll
+    for (int t = 0; t < kStTT; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int n = tile * kStRows + t * kStSub + ib * 16 + 4 * q + r;
+        float v = acc[t][rb][r];
+        if (n >= a.V) v = -INFINITY;
+        acc[t][rb][r] = v;
+        if (v > m) { m = v; idx = n; }               // ascending ids, strict: the lowest id keeps a tie
+      }
+    const float ml = m * kLog2e;
+    float s = 0.f;
+#pragma unroll
+    for (int t = 0; t < kStTT; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) s += fast_exp2(fmaf(acc[t][rb][r], kLog2e, -ml));
+#pragma unroll
+    for (int off = 16; off <= 32; off <<= 1) {
+      const float m2 = __shfl_xor(m, off); const float s2 = __shfl_xor(s, off); const int i2 = __shfl_xor(idx, off);
+      merge_partial(m, s, idx, m2, s2, i2);
+    }
+    if (q == 0) red[wave * 32 + rb * 16 + l16] = Partial{m, s, idx};
+  }
+  __syncthreads();
+  if (tid < kSt2Rows && row_of[tid] >= 0) {
+    // position tid sits in row block tid / 16 = 2 jw + rb; its two waves are 2 jw (ib = 0) and 2 jw + 1 (ib = 1)
+    const int blk = tid >> 4, l = tid & 15;
+    const int w0 = 2 * (blk >> 1), rb = blk & 1;
+    Partial p0 = red[w0 * 32 + rb * 16 + l];
+    const Partial p1 = red[(w0 + 1) * 32 + rb * 16 + l];
+    merge_partial(p0.m, p0.s, p0.idx, p1.m, p1.s, p1.idx);
+    a.partials[(long long)row_of[tid] * a.ntile + tile] = p0;
+  }
+}
+
 // ---- host side ----
 struct LmPlan { int bm, wnb, bn, ntile, nchunk; };
 
@@ -514,7 +689,7 @@ static LmPlan lm_plan(const sdllm_lm_head_params& p) {
   const long long rows = (long long)p.B * p.K;
   LmPlan pl;
   if (rows <= 32) { pl.bm = 32; pl.wnb = kStRows / 64; }      // stream shape: 512 vocabulary rows per workgroup
-  else if (rows <= 64) { pl.bm = 64; pl.wnb = 2; }
+  else if (rows <= 64) { pl.bm = 64; pl.wnb = kStRows / 64; }   // stream shape, hidden chunk in LDS
   else { pl.bm = 256; pl.wnb = 4; }    // also for 65..128 rows: a half-empty 256-row tile beat 128-row tiles
   pl.bn = kLmWaves * pl.wnb * 16;
   pl.ntile = (p.V + pl.bn - 1) / pl.bn;
@@ -524,6 +699,7 @@ static LmPlan lm_plan(const sdllm_lm_head_params& p) {
 
 static size_t lm_lds_bytes(int bm) {
   if (bm == 32) return 2 * (size_t)kStStage + 32 * sizeof(int) + (size_t)kLmWaves * 16 * sizeof(Partial);
+  if (bm == 64) return 2 * (size_t)kStStage + kSt2Hid + kSt2Rows * sizeof(int) + (size_t)kLmWaves * 32 * sizeof(Partial);
   const int nst = bm >= 128 ? 3 : 2;                 // LmShape::NST
   return (size_t)nst * kLmStageBytes + bm * sizeof(int) + (size_t)kLmWaves * bm * sizeof(Partial);
 }
@@ -532,7 +708,7 @@ void lm_head_plan(const sdllm_lm_head_params& p, sdllm_lm_head_plan* plan) {
   const LmPlan pl = lm_plan(p);
   plan->rows_per_chunk = pl.bm; plan->vocab_rows_per_tile = pl.bn; plan->vocab_tiles = pl.ntile;
   plan->row_chunks = pl.nchunk;
-  plan->workgroups = pl.bm == 32 ? pl.ntile : ((pl.ntile + kNumXCDs - 1) / kNumXCDs) * pl.nchunk * kNumXCDs;
+  plan->workgroups = pl.bm <= 64 ? pl.ntile : ((pl.ntile + kNumXCDs - 1) / kNumXCDs) * pl.nchunk * kNumXCDs;
   plan->lds_bytes = (int32_t)lm_lds_bytes(pl.bm);
 }
 
@@ -555,6 +731,21 @@ static hipError_t launch_rows(const LmHeadArgs& r, unsigned grid, hipStream_t st
   return hipGetLastError();
 }
 
+// the two stream shapes: one workgroup per 512 vocabulary rows, every position of the call in it
+static hipError_t launch_stream(void (*kernel)(LmHeadArgs), int bm, const LmHeadArgs& r, hipStream_t stream) {
+  const size_t lds = lm_lds_bytes(bm);
+  static bool attr_set[2] = {false, false};         // > 64 KiB of dynamic LDS needs the opt-in, once per kernel
+  bool& set = attr_set[bm == 64];
+  if (!set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    set = true;
+  }
+  hipLaunchKernelGGL(kernel, dim3((unsigned)r.ntile), dim3(kLmThreads), lds, stream, r);
+  return hipGetLastError();
+}
+
 hipError_t launch_lm_head_unmask(const sdllm_lm_head_params& p, const void* hidden, const void* weight,
                                  int32_t* tokens, uint8_t* masked, float* confidence, int32_t* n_committed,
                                  uint8_t* block_done, uint8_t* eos_seen, void* workspace, hipStream_t stream) {
@@ -567,21 +758,8 @@ hipError_t launch_lm_head_unmask(const sdllm_lm_head_params& p, const void* hidd
   r.ntile = pl.ntile; r.nchunk = pl.nchunk;
   const unsigned grid = (unsigned)(((pl.ntile + kNumXCDs - 1) / kNumXCDs) * pl.nchunk * kNumXCDs);
   hipError_t e;
-  if (pl.bm == 32) {
-    const size_t lds = lm_lds_bytes(32);
-    static bool attr_set = false;
-    e = hipSuccess;
-    if (!attr_set) {
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_stream_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      attr_set = (e == hipSuccess);
-    }
-    if (e == hipSuccess) {
-      hipLaunchKernelGGL(lm_head_stream_kernel, dim3((unsigned)pl.ntile), dim3(kLmThreads), lds, stream, r);
-      e = hipGetLastError();
-    }
-  }
-  else if (pl.bm == 64) e = launch_rows<64, 2, 8>(r, grid, stream);
+  if (pl.bm == 32) e = launch_stream(lm_head_stream_kernel, 32, r, stream);
+  else if (pl.bm == 64) e = launch_stream(lm_head_stream64_kernel, 64, r, stream);
   else e = launch_rows<256, 4, 4>(r, grid, stream);
   if (e != hipSuccess) return e;
 

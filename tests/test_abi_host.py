@@ -243,17 +243,17 @@ def test_probe_validation(lib):
 
 
 @pytest.mark.parametrize("B,K,V,Hd", [(1, 1, 1, 32), (1, 32, 126464, 4096), (2, 32, 5000, 512), (3, 40, 777, 96),
-                                       (8, 32, 126464, 4096), (16, 32, 152064, 3584), (9, 32, 700, 1024), (16, 4096, 100, 32)])
+                                       (8, 32, 126464, 4096), (16, 32, 152064, 3584), (9, 32, 700, 1024), (2, 32, 126464, 4096), (16, 4096, 100, 32)])
 def test_lm_head_plan_is_consistent(lib, B, K, V, Hd):
     p = sd.lm_head_params(B, K, V, Hd, Hd, Hd, 0.9, 0.3)
     pl = sd.plan_lm_head(p)
     rows = B * K
-    assert pl.rows_per_chunk in (32, 64, 256) and pl.vocab_rows_per_tile in (128, 256, 512)
-    assert (pl.vocab_rows_per_tile == 512) == (rows <= 32)          # the stream shape and only it
+    assert pl.rows_per_chunk in (32, 64, 256) and pl.vocab_rows_per_tile in (256, 512)
+    assert (pl.vocab_rows_per_tile == 512) == (rows <= 64)          # the stream shapes and only they
     assert (pl.rows_per_chunk >= min(rows, 256)) and (rows > 32 or pl.rows_per_chunk == 32)
     assert pl.vocab_tiles * pl.vocab_rows_per_tile >= V > (pl.vocab_tiles - 1) * pl.vocab_rows_per_tile
     assert pl.row_chunks * pl.rows_per_chunk >= rows > (pl.row_chunks - 1) * pl.rows_per_chunk
-    if rows <= 32:
+    if rows <= 64:
         assert pl.workgroups == pl.vocab_tiles and pl.row_chunks == 1
     else:
         assert pl.workgroups % 8 == 0 and pl.workgroups >= pl.vocab_tiles * pl.row_chunks

@@ -6,6 +6,8 @@ within 1e-3 of the threshold or whose top-2 probability gap is under 1e-3 (fp32 
 over Hd terms can reorder two near-equal logits); those are excluded and counted.  Confidence values:
 relative error <= 2e-4 -- a logit is a sum of Hd exact bf16 x bf16 products accumulated in fp32, absolute
 error ~ sqrt(Hd) * 2^-24 * |z| ~ 1e-5 at Hd = 4096, and d(ln c) is a probability-weighted mean of those."""
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -112,7 +114,7 @@ def _oracle(h, W, tokens, masked, tau0, alpha, **kw):
 # a hidden width below one LDS chunk, and widths that end inside a chunk
 @pytest.mark.parametrize("B,K,Hd,V", [
     (1, 8, 32, 1), (1, 32, 64, 100), (2, 16, 96, 129), (1, 32, 1056, 1000), (1, 32, 512, 4099),
-    (2, 32, 288, 300), (3, 20, 544, 777), (1, 64, 1024, 2048),
+    (2, 32, 288, 300), (3, 20, 544, 777), (1, 64, 1024, 2048), (2, 24, 1568, 1100),
     (5, 32, 160, 513), (3, 64, 416, 1500), (9, 32, 1024, 700), (2, 160, 256, 2000),
     (4, 600, 64, 300),        # 2400 positions: ten passes of the mask scan, ten row chunks, two triples per position
     (2, 600, 64, 20000),      # 79 triples per position and more positions than the commit kernel has lanes to spare
@@ -127,7 +129,8 @@ def test_lm_head_shapes(gpu_lib, B, K, Hd, V):
     assert skipped <= 1
 
 
-@pytest.mark.parametrize("B,K,Hd,V,ld_h,ld_w", [(2, 16, 64, 200, 72, 80), (3, 32, 320, 1000, 328, 384)])
+@pytest.mark.parametrize("B,K,Hd,V,ld_h,ld_w", [(2, 16, 64, 200, 72, 80), (2, 32, 320, 1000, 328, 384),
+                                                 (3, 32, 320, 1000, 328, 384)])
 def test_lm_head_row_strides_and_poisoned_padding(gpu_lib, B, K, Hd, V, ld_h, ld_w):
     h, W, tokens, masked, hd, Wd = _host_case(B, K, Hd, V, seed=77, ld_h=ld_h, ld_w=ld_w)
     got = run_gpu(gpu_lib, hd, Wd, tokens, masked, 0.6, 0.2)
@@ -177,8 +180,10 @@ def test_lm_head_threshold_extremes_eos_and_query_wide_ratio(gpu_lib):
     assert got["eos_seen"][b0] == 1 and got["eos_seen"][(b0 + 1) % B] == 1
 
 
-def _full_size(gpu_lib, name, seqs=None):
+def _full_size(gpu_lib, name, seqs=None, B=None):
     w = wl.WORKLOADS[name]
+    if B is not None:
+        w = dataclasses.replace(w, B=B)
     t = wl.make_lm_head_inputs_device(w, seed=0)
     got = run_gpu(gpu_lib, t["hidden"], t["lm_weight"], t["tokens"], t["masked"], w.tau0, w.alpha)
     # the oracle sees the same bits: copy the operands back (bf16 -> fp32 is exact)
@@ -198,6 +203,12 @@ def _full_size(gpu_lib, name, seqs=None):
 def test_lm_head_cfg2_full_size(gpu_lib):
     skipped, want = _full_size(gpu_lib, "cfg2")
     assert skipped == 0 and want["n_committed"][0] >= 1
+
+
+def test_lm_head_cfg2_two_sequences_full_size(gpu_lib):
+    # 64 positions: the stream shape that keeps the hidden chunk in LDS, at the full vocabulary and width
+    skipped, _ = _full_size(gpu_lib, "cfg2", B=2)
+    assert skipped == 0
 
 
 def test_lm_head_cfg3A_full_size(gpu_lib):
