@@ -24,6 +24,7 @@
 //     1 KB row pieces, the hidden operands stay in registers (up to 32 positions) or in LDS (33..64).
 #include "common.h"
 #include "unmask_common.h"
+#include <climits>
 
 namespace sdllm {
 
@@ -43,6 +44,12 @@ struct LmHeadArgs {
   int rows_total, V, Hd;
   int ntile;                  // vocabulary tiles
   int nchunk;                 // row chunks in the grid (upper bound of ceil(masked rows / BM))
+  // The masked count is device data, the shape that suits it is not known to the host: a call launches every
+  // shape its B x K admits and each launch exits at once unless min_masked <= masked count <= max_masked.
+  int min_masked, max_masked;
+  // stream kernels: a position's triples are [ntile_out] with this workgroup's at tile * tile_mul; the
+  // tile_mul - 1 slots after it get neutral triples (the layout of the widest shape launched for the call)
+  int ntile_out, tile_mul;
 };
 
 template <int BM, int WNB, int PF_>
@@ -121,7 +128,8 @@ __global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB, PF_>::MIN_WAVES)) voi
     if (running >= lo + BM) break;                 // uniform: the chunk is full
   }
   const int n_valid = min(running - lo, BM);       // uniform
-  if (n_valid <= 0) return;
+  // running is the whole masked count here unless the scan stopped at a full chunk (then it is >= BM)
+  if (n_valid <= 0 || running < a.min_masked) return;
   if (tid < BM && tid >= n_valid) row_of[tid] = -1;
   __syncthreads();
 
@@ -385,7 +393,9 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_stream_kernel(LmHeadArgs a
     if (f && ci < 32) row_of[ci] = i;
     running += tot;
     __syncthreads();
+    if (running > a.max_masked) break;             // uniform: another shape's launch has this call
   }
+  if (running < a.min_masked || running > a.max_masked) return;
   const int n_valid = min(running, 32);            // uniform
   if (n_valid <= 0) return;
   if (tid < 32 && tid >= n_valid) row_of[tid] = -1;
@@ -503,7 +513,10 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_stream_kernel(LmHeadArgs a
     Partial p0 = red[(2 * rb) * 16 + l];
     const Partial p1 = red[(2 * rb + 1) * 16 + l];
     merge_partial(p0.m, p0.s, p0.idx, p1.m, p1.s, p1.idx);
-    a.partials[(long long)row_of[tid] * a.ntile + tile] = p0;
+    Partial* out = a.partials + (long long)row_of[tid] * a.ntile_out + (long long)tile * a.tile_mul;
+    out[0] = p0;
+    for (int j = 1; j < a.tile_mul; ++j)
+      if (tile * a.tile_mul + j < a.ntile_out) out[j] = Partial{kNegBig, 0.f, 0x7fffffff};
   }
 }
 
@@ -543,7 +556,9 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_stream64_kernel(LmHeadArgs
     if (f && ci < kSt2Rows) row_of[ci] = i;
     running += tot;
     __syncthreads();
+    if (running > a.max_masked) break;             // uniform: another shape's launch has this call
   }
+  if (running < a.min_masked || running > a.max_masked) return;
   const int n_valid = min(running, kSt2Rows);      // uniform
   if (n_valid <= 0) return;
   if (tid < kSt2Rows && tid >= n_valid) row_of[tid] = -1;
@@ -678,7 +693,10 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_stream64_kernel(LmHeadArgs
     Partial p0 = red[w0 * 32 + rb * 16 + l];
     const Partial p1 = red[(w0 + 1) * 32 + rb * 16 + l];
     merge_partial(p0.m, p0.s, p0.idx, p1.m, p1.s, p1.idx);
-    a.partials[(long long)row_of[tid] * a.ntile + tile] = p0;
+    Partial* out = a.partials + (long long)row_of[tid] * a.ntile_out + (long long)tile * a.tile_mul;
+    out[0] = p0;
+    for (int j = 1; j < a.tile_mul; ++j)
+      if (tile * a.tile_mul + j < a.ntile_out) out[j] = Partial{kNegBig, 0.f, 0x7fffffff};
   }
 }
 
@@ -756,11 +774,23 @@ hipError_t launch_lm_head_unmask(const sdllm_lm_head_params& p, const void* hidd
   r.ld_h = p.ld_h; r.ld_w = p.ld_w;
   r.rows_total = p.B * p.K; r.V = p.V; r.Hd = p.Hd;
   r.ntile = pl.ntile; r.nchunk = pl.nchunk;
+  r.min_masked = 0; r.max_masked = INT_MAX; r.ntile_out = pl.ntile; r.tile_mul = 1;
   const unsigned grid = (unsigned)(((pl.ntile + kNumXCDs - 1) / kNumXCDs) * pl.nchunk * kNumXCDs);
-  hipError_t e;
+  hipError_t e = hipSuccess;
   if (pl.bm == 32) e = launch_stream(lm_head_stream_kernel, 32, r, stream);
-  else if (pl.bm == 64) e = launch_stream(lm_head_stream64_kernel, 64, r, stream);
-  else e = launch_rows<256, 4, 4>(r, grid, stream);
+  else {
+    // the stream shapes take the call when few enough positions are still masked (the later steps of a block)
+    LmHeadArgs s = r;
+    s.ntile = (p.V + kStRows - 1) / kStRows;
+    s.tile_mul = kStRows / pl.bn;                   // 1, or 2 under the 256-row tiles of the wide shape
+    s.min_masked = 1; s.max_masked = 32;
+    e = launch_stream(lm_head_stream_kernel, 32, s, stream);
+    if (e != hipSuccess) return e;
+    s.min_masked = 33; s.max_masked = pl.bm == 64 ? INT_MAX : kSt2Rows;
+    e = launch_stream(lm_head_stream64_kernel, 64, s, stream);
+    if (e != hipSuccess) return e;
+    if (pl.bm > 64) { r.min_masked = kSt2Rows + 1; e = launch_rows<256, 4, 4>(r, grid, stream); }
+  }
   if (e != hipSuccess) return e;
 
   UnmaskArgs u;

@@ -129,6 +129,27 @@ def test_lm_head_shapes(gpu_lib, B, K, Hd, V):
     assert skipped <= 1
 
 
+@pytest.mark.parametrize("B,K", [(2, 32), (5, 32), (9, 64)])
+@pytest.mark.parametrize("n_masked", [1, 31, 32, 33, 63, 64, 65, 130])
+def test_lm_head_shape_follows_the_masked_count(gpu_lib, B, K, n_masked):
+    # the masked count is device data: every shape that B x K admits is launched and the one whose range holds
+    # the count does the work; counts on both sides of each boundary, spread over the sequences, with V chosen so
+    # that the narrower tiles of the wide shape leave an odd number of triple slots per position
+    if n_masked > B * K:
+        pytest.skip("more masked positions than positions")
+    Hd, V = 1056, 1100
+    h, W, tokens, masked, hd, Wd = _host_case(B, K, Hd, V, seed=77 * B + n_masked, frac=0.0)
+    g = np.random.Generator(np.random.Philox(key=n_masked))
+    flat = g.permutation(B * K)[:n_masked]
+    masked.reshape(-1)[flat] = 1
+    tokens.reshape(-1)[flat] = wl.MASK_TOKEN
+    assert int(masked.sum()) == n_masked
+    got = run_gpu(gpu_lib, hd, Wd, tokens, masked, 0.7, 0.3)
+    want = _oracle(h, W, tokens, masked, 0.7, 0.3)
+    n_gap, n_band, skipped = compare(got, want, tokens, masked)
+    assert skipped <= 1
+
+
 @pytest.mark.parametrize("B,K,Hd,V,ld_h,ld_w", [(2, 16, 64, 200, 72, 80), (2, 32, 320, 1000, 328, 384),
                                                  (3, 32, 320, 1000, 328, 384)])
 def test_lm_head_row_strides_and_poisoned_padding(gpu_lib, B, K, Hd, V, ld_h, ld_w):
