@@ -189,10 +189,14 @@ int sdllm_lm_head_unmask(const sdllm_lm_head_params* p,
                          uint8_t* eos_seen,
                          void* workspace, size_t workspace_bytes, void* stream);
 
-/* Launch plan the library would use for these parameters (host only, no HIP call): rows of hidden per
- * row chunk, rows of W per vocabulary tile, number of tiles (= triples per position in the workspace),
- * row chunks in the grid, workgroups launched, LDS bytes per workgroup.  Returns SDLLM_OK or the
- * validation error. */
+/* Launch plan the library would use for these parameters (host only, no HIP call).  The masked count is
+ * device data, so a call launches every kernel shape that B*K admits and the masked count found on the
+ * device decides which of them does the work (the others exit at once): up to 32 masked positions and
+ * 33..64 take two kernels that stream W once with every position resident, more take 256-position row
+ * chunks.  The plan describes the shape that serves B*K masked positions: rows of hidden per row chunk,
+ * rows of W per vocabulary tile, number of tiles, row chunks in the grid, workgroups launched, LDS bytes
+ * per workgroup; triples_per_position is the workspace's row length (the largest tile count among the
+ * shapes launched).  Returns SDLLM_OK or the validation error. */
 typedef struct sdllm_lm_head_plan {
   int32_t rows_per_chunk;
   int32_t vocab_rows_per_tile;
@@ -200,6 +204,7 @@ typedef struct sdllm_lm_head_plan {
   int32_t row_chunks;
   int32_t workgroups;
   int32_t lds_bytes;
+  int32_t triples_per_position;
 } sdllm_lm_head_plan;
 
 int sdllm_plan_lm_head(const sdllm_lm_head_params* p, sdllm_lm_head_plan* plan);

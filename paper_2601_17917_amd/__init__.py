@@ -50,7 +50,7 @@ class LmHeadParams(ctypes.Structure):
 class LmHeadPlan(ctypes.Structure):
     _fields_ = [("rows_per_chunk", ctypes.c_int32), ("vocab_rows_per_tile", ctypes.c_int32),
                 ("vocab_tiles", ctypes.c_int32), ("row_chunks", ctypes.c_int32), ("workgroups", ctypes.c_int32),
-                ("lds_bytes", ctypes.c_int32)]
+                ("lds_bytes", ctypes.c_int32), ("triples_per_position", ctypes.c_int32)]
 
 
 class AppendParams(ctypes.Structure):

@@ -47,10 +47,17 @@ struct LmHeadArgs {
   // The masked count is device data, the shape that suits it is not known to the host: a call launches every
   // shape its B x K admits and each launch exits at once unless min_masked <= masked count <= max_masked.
   int min_masked, max_masked;
-  // stream kernels: a position's triples are [ntile_out] with this workgroup's at tile * tile_mul; the
-  // tile_mul - 1 slots after it get neutral triples (the layout of the widest shape launched for the call)
-  int ntile_out, tile_mul;
+  // a position's triples are [ntile_out] (the largest tile count among the call's launches); the launch that
+  // runs writes its ntile of them and neutral triples into the rest (slot tile + j ntile from workgroup tile)
+  int ntile_out;
 };
+
+__device__ __forceinline__ void store_partial(const LmHeadArgs& a, int row, int tile, const Partial& p) {
+  Partial* out = a.partials + (long long)row * a.ntile_out;
+  out[tile] = p;
+  for (int j = tile + a.ntile; j < a.ntile_out; j += a.ntile) out[j] = Partial{kNegBig, 0.f, 0x7fffffff};
+}
+
 
 template <int BM, int WNB, int PF_>
 struct LmShape {
@@ -344,14 +351,14 @@ __global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB, PF_>::MIN_WAVES)) voi
       const Partial p2 = red[w * BM + tid];
       merge_partial(p.m, p.s, p.idx, p2.m, p2.s, p2.idx);
     }
-    a.partials[(long long)row_of[tid] * a.ntile + tile] = p;
+    store_partial(a, row_of[tid], tile, p);
   }
 }
 
 
 // ---------------------------------------------------------------------------------------------------
 // Stream shape (at most 32 positions in the block): the call is a read of W, so the kernel is built around
-// that stream.  A workgroup owns kStRows = 512 consecutive vocabulary rows and walks Hd in chunks of 512
+// that stream.  A workgroup owns 32 TT consecutive vocabulary rows (TT = 16: 512) and walks Hd in chunks of 512
 // elements; within a chunk it visits its 16 sub-tiles of 32 rows one after the other, so that every
 // wave-wide load is ONE KILOBYTE OF ONE ROW of W (registers -> LDS, swizzled, two stages, one barrier per
 // sub-tile), and the matrix instructions read W back from LDS in operand layout.  The hidden rows never
@@ -360,13 +367,16 @@ __global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB, PF_>::MIN_WAVES)) voi
 // sub-tiles ahead.  All 16 x (16 x 16) accumulators of a wave stay in registers until the end: one triple
 // per (position, 512 vocabulary rows), a quarter of what the 128-row tiles of the other shapes write.
 constexpr int kStSub = 32;                 // vocabulary rows per sub-tile
-constexpr int kStTT = 16;                  // sub-tiles per workgroup
-constexpr int kStRows = kStSub * kStTT;    // vocabulary rows per workgroup
+constexpr int kStTTMax = 20;               // most sub-tiles per workgroup: the accumulators a wave can hold
+constexpr int kSt2TTMax = 16;              // the same with two row blocks per wave (33..64 positions)
 constexpr int kStKC = 512;                 // elements of Hd per chunk (1 KB per row)
 constexpr int kStKS = kStKC / 32;          // k-steps per chunk
 constexpr int kStStage = kStSub * kStKC * 2;   // 32 KB
 
+template <int TT>   // sub-tiles per workgroup (even: the two W stages alternate across chunk boundaries)
 __global__ __launch_bounds__(kLmThreads) void lm_head_stream_kernel(LmHeadArgs a) {
+  static_assert(TT % 2 == 0 && TT >= 2 && TT <= kStTTMax, "sub-tiles per workgroup");
+  constexpr int kStTT = TT, kStRows = TT * kStSub;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   unsigned char* stage = lds_raw;                                            // 2 x kStStage
   int* row_of = reinterpret_cast<int*>(lds_raw + 2 * kStStage);              // 32 compacted row ids (-1 = none)
@@ -513,10 +523,7 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_stream_kernel(LmHeadArgs a
     Partial p0 = red[(2 * rb) * 16 + l];
     const Partial p1 = red[(2 * rb + 1) * 16 + l];
     merge_partial(p0.m, p0.s, p0.idx, p1.m, p1.s, p1.idx);
-    Partial* out = a.partials + (long long)row_of[tid] * a.ntile_out + (long long)tile * a.tile_mul;
-    out[0] = p0;
-    for (int j = 1; j < a.tile_mul; ++j)
-      if (tile * a.tile_mul + j < a.ntile_out) out[j] = Partial{kNegBig, 0.f, 0x7fffffff};
+    store_partial(a, row_of[tid], tile, p0);
   }
 }
 
@@ -528,7 +535,10 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_stream_kernel(LmHeadArgs a
 constexpr int kSt2Rows = 64;                               // positions per workgroup
 constexpr int kSt2Hid = kSt2Rows * kStKC * 2;              // 64 KB: one hidden chunk
 
+template <int TT>
 __global__ __launch_bounds__(kLmThreads) void lm_head_stream64_kernel(LmHeadArgs a) {
+  static_assert(TT % 2 == 0 && TT >= 2 && TT <= kSt2TTMax, "sub-tiles per workgroup");
+  constexpr int kStTT = TT, kStRows = TT * kStSub;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   unsigned char* stage = lds_raw;                                            // 2 x kStStage (W ring)
   unsigned char* hid = lds_raw + 2 * kStStage;                               // kSt2Hid (hidden chunk)
@@ -693,24 +703,49 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_stream64_kernel(LmHeadArgs
     Partial p0 = red[w0 * 32 + rb * 16 + l];
     const Partial p1 = red[(w0 + 1) * 32 + rb * 16 + l];
     merge_partial(p0.m, p0.s, p0.idx, p1.m, p1.s, p1.idx);
-    Partial* out = a.partials + (long long)row_of[tid] * a.ntile_out + (long long)tile * a.tile_mul;
-    out[0] = p0;
-    for (int j = 1; j < a.tile_mul; ++j)
-      if (tile * a.tile_mul + j < a.ntile_out) out[j] = Partial{kNegBig, 0.f, 0x7fffffff};
+    store_partial(a, row_of[tid], tile, p0);
   }
 }
 
 // ---- host side ----
-struct LmPlan { int bm, wnb, bn, ntile, nchunk; };
+// bm: the shape for B x K positions all masked (32 / 64: the stream kernels, 256: the rows kernel).  The stream
+// shapes that serve smaller masked counts are launched too; ntile_out is the largest tile count among them.
+struct LmPlan { int bm, bn, ntile, nchunk, tt32, ntile32, tt64, ntile64, ntile_out; };
+
+// Sub-tiles per workgroup of a stream kernel, out of the counts it is compiled for.  One workgroup per CU is
+// resident, so a launch runs in rounds of kNumCUs workgroups and costs about rounds x (sub-tiles + a half for
+// the prologue): 126464 vocabulary rows take 16 sub-tiles (247 workgroups), 152064 take 20 (238 workgroups; 16
+// would leave 41 of 297 for a second round) or, with two row blocks per wave, 10 (476 workgroups, two rounds).
+constexpr int kStTTs[] = {2, 4, 8, 12, 16, 20};
+constexpr int kSt2TTs[] = {2, 4, 8, 10, 12, 16};
+
+template <size_t N>
+static int stream_tt(int V, const int (&tts)[N]) {
+  const int nsub = (V + kStSub - 1) / kStSub;
+  int best = tts[0];
+  long long best_cost = LLONG_MAX;
+  for (int tt : tts) {
+    const int ntile = (nsub + tt - 1) / tt;
+    const long long cost = (long long)((ntile + kNumCUs - 1) / kNumCUs) * (2 * tt + 1);
+    if (cost <= best_cost) { best_cost = cost; best = tt; }     // ties: fewer, larger tiles
+  }
+  return best;
+}
 
 static LmPlan lm_plan(const sdllm_lm_head_params& p) {
   const long long rows = (long long)p.B * p.K;
   LmPlan pl;
-  if (rows <= 32) { pl.bm = 32; pl.wnb = kStRows / 64; }      // stream shape: 512 vocabulary rows per workgroup
-  else if (rows <= 64) { pl.bm = 64; pl.wnb = kStRows / 64; }   // stream shape, hidden chunk in LDS
-  else { pl.bm = 256; pl.wnb = 4; }    // also for 65..128 rows: a half-empty 256-row tile beat 128-row tiles
-  pl.bn = kLmWaves * pl.wnb * 16;
-  pl.ntile = (p.V + pl.bn - 1) / pl.bn;
+  pl.tt32 = stream_tt(p.V, kStTTs);
+  pl.ntile32 = (p.V + pl.tt32 * kStSub - 1) / (pl.tt32 * kStSub);
+  pl.tt64 = stream_tt(p.V, kSt2TTs);
+  pl.ntile64 = (p.V + pl.tt64 * kStSub - 1) / (pl.tt64 * kStSub);
+  if (rows <= 32) { pl.bm = 32; pl.bn = pl.tt32 * kStSub; pl.ntile = pl.ntile32; pl.ntile_out = pl.ntile32; }
+  else if (rows <= 64) {
+    pl.bm = 64; pl.bn = pl.tt64 * kStSub; pl.ntile = pl.ntile64; pl.ntile_out = std::max(pl.ntile32, pl.ntile64);
+  } else {            // also for 65..128 rows: a half-empty 256-row tile beat 128-row tiles
+    pl.bm = 256; pl.bn = 256; pl.ntile = (p.V + pl.bn - 1) / pl.bn;
+    pl.ntile_out = std::max(pl.ntile, std::max(pl.ntile32, pl.ntile64));
+  }
   pl.nchunk = (int)((rows + pl.bm - 1) / pl.bm);
   return pl;
 }
@@ -718,8 +753,7 @@ static LmPlan lm_plan(const sdllm_lm_head_params& p) {
 static size_t lm_lds_bytes(int bm) {
   if (bm == 32) return 2 * (size_t)kStStage + 32 * sizeof(int) + (size_t)kLmWaves * 16 * sizeof(Partial);
   if (bm == 64) return 2 * (size_t)kStStage + kSt2Hid + kSt2Rows * sizeof(int) + (size_t)kLmWaves * 32 * sizeof(Partial);
-  const int nst = bm >= 128 ? 3 : 2;                 // LmShape::NST
-  return (size_t)nst * kLmStageBytes + bm * sizeof(int) + (size_t)kLmWaves * bm * sizeof(Partial);
+  return (size_t)3 * kLmStageBytes + bm * sizeof(int) + (size_t)kLmWaves * bm * sizeof(Partial);   // LmShape::NST
 }
 
 void lm_head_plan(const sdllm_lm_head_params& p, sdllm_lm_head_plan* plan) {
@@ -728,15 +762,16 @@ void lm_head_plan(const sdllm_lm_head_params& p, sdllm_lm_head_plan* plan) {
   plan->row_chunks = pl.nchunk;
   plan->workgroups = pl.bm <= 64 ? pl.ntile : ((pl.ntile + kNumXCDs - 1) / kNumXCDs) * pl.nchunk * kNumXCDs;
   plan->lds_bytes = (int32_t)lm_lds_bytes(pl.bm);
+  plan->triples_per_position = pl.ntile_out;
 }
 
 size_t lm_head_workspace_bytes(const sdllm_lm_head_params& p) {
-  return (size_t)p.B * p.K * lm_plan(p).ntile * sizeof(Partial);
+  return (size_t)p.B * p.K * lm_plan(p).ntile_out * sizeof(Partial);
 }
 
 template <int BM, int WNB, int PF>
 static hipError_t launch_rows(const LmHeadArgs& r, unsigned grid, hipStream_t stream) {
-  static_assert(LmShape<BM, WNB, PF>::NST == (BM >= 128 ? 3 : 2), "lm_lds_bytes");
+  static_assert(LmShape<BM, WNB, PF>::NST == 3 && LmShape<BM, WNB, PF>::BN == 256, "lm_lds_bytes, lm_plan");
   const size_t lds = lm_lds_bytes(BM);
   static bool attr_set = false;                     // > 64 KiB of dynamic LDS needs the opt-in, once
   if (!attr_set) {
@@ -749,19 +784,49 @@ static hipError_t launch_rows(const LmHeadArgs& r, unsigned grid, hipStream_t st
   return hipGetLastError();
 }
 
-// the two stream shapes: one workgroup per 512 vocabulary rows, every position of the call in it
-static hipError_t launch_stream(void (*kernel)(LmHeadArgs), int bm, const LmHeadArgs& r, hipStream_t stream) {
+// the two stream shapes: one workgroup per 32 tt vocabulary rows, every position of the call in it
+static hipError_t launch_stream_kernel(void (*kernel)(LmHeadArgs), bool& attr_set, int bm, const LmHeadArgs& r,
+                                       hipStream_t stream) {
   const size_t lds = lm_lds_bytes(bm);
-  static bool attr_set[2] = {false, false};         // > 64 KiB of dynamic LDS needs the opt-in, once per kernel
-  bool& set = attr_set[bm == 64];
-  if (!set) {
+  if (!attr_set) {                                  // > 64 KiB of dynamic LDS needs the opt-in, once per kernel
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    set = true;
+    attr_set = true;
   }
   hipLaunchKernelGGL(kernel, dim3((unsigned)r.ntile), dim3(kLmThreads), lds, stream, r);
   return hipGetLastError();
+}
+
+template <int TT>
+static hipError_t launch_stream32(const LmHeadArgs& r, hipStream_t stream) {
+  static bool attr_set = false;
+  return launch_stream_kernel(lm_head_stream_kernel<TT>, attr_set, 32, r, stream);
+}
+template <int TT>
+static hipError_t launch_stream64(const LmHeadArgs& r, hipStream_t stream) {
+  static bool attr_set = false;
+  return launch_stream_kernel(lm_head_stream64_kernel<TT>, attr_set, 64, r, stream);
+}
+
+static hipError_t launch_stream(int bm, int tt, const LmHeadArgs& r, hipStream_t stream) {
+  if (bm == 32) switch (tt) {       // kStTTs
+    case 2: return launch_stream32<2>(r, stream);
+    case 4: return launch_stream32<4>(r, stream);
+    case 8: return launch_stream32<8>(r, stream);
+    case 12: return launch_stream32<12>(r, stream);
+    case 16: return launch_stream32<16>(r, stream);
+    case 20: return launch_stream32<20>(r, stream);
+  }
+  else switch (tt) {                // kSt2TTs
+    case 2: return launch_stream64<2>(r, stream);
+    case 4: return launch_stream64<4>(r, stream);
+    case 8: return launch_stream64<8>(r, stream);
+    case 10: return launch_stream64<10>(r, stream);
+    case 12: return launch_stream64<12>(r, stream);
+    case 16: return launch_stream64<16>(r, stream);
+  }
+  return hipErrorInvalidValue;      // not reached: lm_plan picks from the same lists
 }
 
 hipError_t launch_lm_head_unmask(const sdllm_lm_head_params& p, const void* hidden, const void* weight,
@@ -773,23 +838,24 @@ hipError_t launch_lm_head_unmask(const sdllm_lm_head_params& p, const void* hidd
   r.partials = (Partial*)workspace;
   r.ld_h = p.ld_h; r.ld_w = p.ld_w;
   r.rows_total = p.B * p.K; r.V = p.V; r.Hd = p.Hd;
-  r.ntile = pl.ntile; r.nchunk = pl.nchunk;
-  r.min_masked = 0; r.max_masked = INT_MAX; r.ntile_out = pl.ntile; r.tile_mul = 1;
-  const unsigned grid = (unsigned)(((pl.ntile + kNumXCDs - 1) / kNumXCDs) * pl.nchunk * kNumXCDs);
+  r.ntile = pl.ntile; r.nchunk = pl.nchunk; r.ntile_out = pl.ntile_out;
+  r.min_masked = 0; r.max_masked = INT_MAX;
   hipError_t e = hipSuccess;
-  if (pl.bm == 32) e = launch_stream(lm_head_stream_kernel, 32, r, stream);
+  if (pl.bm == 32) e = launch_stream(32, pl.tt32, r, stream);
   else {
     // the stream shapes take the call when few enough positions are still masked (the later steps of a block)
     LmHeadArgs s = r;
-    s.ntile = (p.V + kStRows - 1) / kStRows;
-    s.tile_mul = kStRows / pl.bn;                   // 1, or 2 under the 256-row tiles of the wide shape
-    s.min_masked = 1; s.max_masked = 32;
-    e = launch_stream(lm_head_stream_kernel, 32, s, stream);
+    s.ntile = pl.ntile32; s.min_masked = 1; s.max_masked = 32;
+    e = launch_stream(32, pl.tt32, s, stream);
     if (e != hipSuccess) return e;
-    s.min_masked = 33; s.max_masked = pl.bm == 64 ? INT_MAX : kSt2Rows;
-    e = launch_stream(lm_head_stream64_kernel, 64, s, stream);
+    s.ntile = pl.ntile64; s.min_masked = 33; s.max_masked = pl.bm == 64 ? INT_MAX : kSt2Rows;
+    e = launch_stream(64, pl.tt64, s, stream);
     if (e != hipSuccess) return e;
-    if (pl.bm > 64) { r.min_masked = kSt2Rows + 1; e = launch_rows<256, 4, 4>(r, grid, stream); }
+    if (pl.bm > 64) {
+      const unsigned grid = (unsigned)(((pl.ntile + kNumXCDs - 1) / kNumXCDs) * pl.nchunk * kNumXCDs);
+      r.min_masked = kSt2Rows + 1;
+      e = launch_rows<256, 4, 4>(r, grid, stream);
+    }
   }
   if (e != hipSuccess) return e;
 
@@ -798,7 +864,7 @@ hipError_t launch_lm_head_unmask(const sdllm_lm_head_params& p, const void* hidd
   u.tokens = tokens; u.masked = masked; u.confidence = confidence;
   u.n_committed = n_committed; u.block_done = block_done; u.eos_seen = eos_seen;
   u.ld = 0; u.V = p.V; u.nvec = 0; u.vec_per_split = 0;
-  u.nsplit = pl.ntile; u.nsplit_p2 = 1; u.K = p.K;
+  u.nsplit = pl.ntile_out; u.nsplit_p2 = 1; u.K = p.K;
   u.tau0 = p.tau0; u.alpha = p.alpha; u.r_extra_masked = p.r_extra_masked; u.r_extra_total = p.r_extra_total;
   u.eos_id = p.eos_id; u.tau_eos = p.tau_eos;
   return launch_unmask_commit(u, p.B, stream);

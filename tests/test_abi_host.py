@@ -36,7 +36,7 @@ def test_struct_layouts_match_header():
     assert ctypes.sizeof(sd.AppendParams) == 48
     assert sd.AppendParams.cache_layer_stride.offset == 32
     assert ctypes.sizeof(sd.AttnPlan) == 16
-    assert ctypes.sizeof(sd.LmHeadPlan) == 24
+    assert ctypes.sizeof(sd.LmHeadPlan) == 28
     assert ctypes.sizeof(sd.LmHeadParams) == 56
     assert sd.LmHeadParams.ld_h.offset == 16 and sd.LmHeadParams.tau0.offset == 32
 
@@ -243,20 +243,33 @@ def test_probe_validation(lib):
 
 
 @pytest.mark.parametrize("B,K,V,Hd", [(1, 1, 1, 32), (1, 32, 126464, 4096), (2, 32, 5000, 512), (3, 40, 777, 96),
-                                       (8, 32, 126464, 4096), (16, 32, 152064, 3584), (9, 32, 700, 1024), (2, 32, 126464, 4096), (16, 4096, 100, 32)])
+                                       (8, 32, 126464, 4096), (16, 32, 152064, 3584), (9, 32, 700, 1024), (2, 32, 126464, 4096), (1, 32, 152064, 3584), (2, 32, 152064, 3584), (16, 4096, 100, 32)])
 def test_lm_head_plan_is_consistent(lib, B, K, V, Hd):
     p = sd.lm_head_params(B, K, V, Hd, Hd, Hd, 0.9, 0.3)
     pl = sd.plan_lm_head(p)
     rows = B * K
-    assert pl.rows_per_chunk in (32, 64, 256) and pl.vocab_rows_per_tile in (256, 512)
-    assert (pl.vocab_rows_per_tile == 512) == (rows <= 64)          # the stream shapes and only they
+    assert pl.rows_per_chunk in (32, 64, 256)
     assert (pl.rows_per_chunk >= min(rows, 256)) and (rows > 32 or pl.rows_per_chunk == 32)
     assert pl.vocab_tiles * pl.vocab_rows_per_tile >= V > (pl.vocab_tiles - 1) * pl.vocab_rows_per_tile
     assert pl.row_chunks * pl.rows_per_chunk >= rows > (pl.row_chunks - 1) * pl.rows_per_chunk
     if rows <= 64:
+        # stream shapes: an even number of 32-row sub-tiles per workgroup out of the compiled counts; one
+        # workgroup per CU is resident, so the launch runs in rounds of 256 workgroups
+        tt = pl.vocab_rows_per_tile // 32
+        assert pl.vocab_rows_per_tile % 64 == 0
+        assert tt in ((2, 4, 8, 12, 16, 20) if rows <= 32 else (2, 4, 8, 10, 12, 16))
         assert pl.workgroups == pl.vocab_tiles and pl.row_chunks == 1
+        rounds = -(-pl.vocab_tiles // 256)
+        ideal = -(-V // 32) / 256.0                   # sub-tiles per CU if they could be spread evenly
+        assert rounds * tt <= max(2.0, 1.35 * ideal + 2)
+        if V == 126464:
+            assert tt == 16                           # 247 workgroups
+        if V == 152064:
+            assert tt == (20 if rows <= 32 else 10)   # 238 workgroups in one round / 476 in two
     else:
+        assert pl.vocab_rows_per_tile == 256
         assert pl.workgroups % 8 == 0 and pl.workgroups >= pl.vocab_tiles * pl.row_chunks
         assert pl.workgroups < pl.vocab_tiles * pl.row_chunks + 8 * pl.row_chunks
+    assert pl.triples_per_position >= pl.vocab_tiles
     assert 64 * 1024 <= pl.lds_bytes <= 160 * 1024
-    assert sd.lm_head_unmask_workspace_bytes(p) == rows * pl.vocab_tiles * 12
+    assert sd.lm_head_unmask_workspace_bytes(p) == rows * pl.triples_per_position * 12

@@ -129,6 +129,30 @@ def test_lm_head_shapes(gpu_lib, B, K, Hd, V):
     assert skipped <= 1
 
 
+_TILE_CASES = [3000, 20000, 50000, 80000, 90000, 126464, 152064]
+
+
+def test_tile_cases_cover_every_compiled_stream_kernel(gpu_lib):
+    seen32 = {gpu_lib.plan_lm_head(gpu_lib.lm_head_params(1, 32, V, 64, 64, 64, 0.9, 0.3)).vocab_rows_per_tile // 32
+              for V in _TILE_CASES}
+    seen64 = {gpu_lib.plan_lm_head(gpu_lib.lm_head_params(2, 32, V, 64, 64, 64, 0.9, 0.3)).vocab_rows_per_tile // 32
+              for V in _TILE_CASES}
+    assert seen32 == {2, 4, 8, 12, 16, 20} and seen64 == {2, 4, 8, 10, 12, 16}
+
+
+@pytest.mark.parametrize("V", _TILE_CASES)
+@pytest.mark.parametrize("B", [1, 2])
+def test_lm_head_every_vocabulary_tile_size(gpu_lib, B, V):
+    # the stream kernels are compiled for a list of tile sizes and the vocabulary size picks one: every one of
+    # them runs here (narrow hidden width, so that the oracle stays cheap), masked counts 24 and 48
+    K, Hd = 32, 64
+    h, W, tokens, masked, hd, Wd = _host_case(B, K, Hd, V, seed=V + B, frac=0.75, std=1.0)
+    got = run_gpu(gpu_lib, hd, Wd, tokens, masked, 0.3, 0.3)
+    want = _oracle(h, W, tokens, masked, 0.3, 0.3)
+    n_gap, n_band, skipped = compare(got, want, tokens, masked)
+    assert skipped <= 1 and n_gap <= masked.sum() // 2      # most positions have a clear arg-max to compare
+
+
 @pytest.mark.parametrize("B,K", [(2, 32), (5, 32), (9, 64)])
 @pytest.mark.parametrize("n_masked", [1, 31, 32, 33, 63, 64, 65, 130])
 def test_lm_head_shape_follows_the_masked_count(gpu_lib, B, K, n_masked):
