@@ -109,10 +109,26 @@ __global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB, PF_>::MIN_WAVES)) voi
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  // ---- workgroup -> (vocabulary tile, row chunk): chunks of a tile share id mod 8 (the XCD)
+  // ---- the masked count decides how many row chunks there are (uniform): one pass without barriers
+  int mine = 0;
+  for (int i = tid; i < a.rows_total; i += kLmThreads) mine += a.masked[i] != 0;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) mine += __shfl_xor(mine, off);
+  if (lane == 0) wsum[wave] = mine;
+  __syncthreads();
+  int total = 0;
+#pragma unroll
+  for (int w = 0; w < kLmWaves; ++w) total += wsum[w];
+  __syncthreads();                                 // wsum is written again below
+  if (total < max(a.min_masked, 1)) return;        // another shape's launch has this call, or nothing is masked
+  const int nact = (total + BM - 1) / BM;          // <= a.nchunk, since total <= rows_total
+  // ---- workgroup -> (vocabulary tile, row chunk): chunks of a tile share id mod 8 (the XCD) and are adjacent
+  // in dispatch order.  Only chunks that hold rows get workgroup ids: the idle workgroups of a grid sized for
+  // B x K rows are its last ones (interleaved with the working ones they kept half of the chip idle: 256 of
+  // 512 positions masked took 497 us, not the 320 us of 256 of 256).
   const int slot = blockIdx.x >> 3;
-  const int tile = (slot / a.nchunk) * kNumXCDs + (blockIdx.x & 7);
-  const int chunk = slot % a.nchunk;
+  const int tile = (slot / nact) * kNumXCDs + (blockIdx.x & 7);
+  const int chunk = slot % nact;
   if (tile >= a.ntile) return;
 
   // ---- compact the masked rows; this workgroup takes compacted rows [lo, lo + BM)
@@ -134,9 +150,7 @@ __global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB, PF_>::MIN_WAVES)) voi
     __syncthreads();
     if (running >= lo + BM) break;                 // uniform: the chunk is full
   }
-  const int n_valid = min(running - lo, BM);       // uniform
-  // running is the whole masked count here unless the scan stopped at a full chunk (then it is >= BM)
-  if (n_valid <= 0 || running < a.min_masked) return;
+  const int n_valid = min(running - lo, BM);       // uniform, >= 1 because chunk < nact
   if (tid < BM && tid >= n_valid) row_of[tid] = -1;
   __syncthreads();
 
