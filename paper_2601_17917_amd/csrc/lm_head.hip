@@ -25,6 +25,7 @@
 #include "common.h"
 #include "unmask_common.h"
 #include <climits>
+#include <type_traits>
 
 namespace sdllm {
 
@@ -721,17 +722,252 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_stream64_kernel(LmHeadArgs
   }
 }
 
+// Stream shape for 64 RB positions (RB = 2: 128).  The walk is the same, the route is not: W and the hidden rows
+// go from global memory straight into LDS (global_load_lds_dwordx4, no staging registers, no LDS store
+// instructions), so the registers hold accumulators and B operands only and the number of sub-tiles per
+// workgroup needs no parity.  A chunk is 256 elements of Hd (8 k-steps), a sub-tile 32 vocabulary rows x 512
+// bytes (16 KB; a transfer of one wave = two rows), the W ring has five stages and is filled four steps
+// ahead.  A wave owns RB 16-row blocks of positions and both vocabulary blocks of a sub-tile; its hidden rows of
+// the next chunk are transferred into a region of LDS that only this wave touches, as soon as it has read the
+// current chunk's B operands from there into registers (8 RB reads per chunk).  No wave shares a position
+// with another, so the row reduction ends in the wave.
+// The transfers are inline assembly, invisible to the compiler's wait-count insertion: every wait for them
+// is written out below, counted in transfers issued by the same wave after the one waited for (they complete
+// in issue order), and the kernel has no other global load after its prologue.
+constexpr int kDmSub = 32;                     // vocabulary rows per sub-tile
+constexpr int kDmKC = 256;                     // elements of Hd per chunk (512 bytes per row)
+constexpr int kDmKS = kDmKC / 32;              // k-steps per chunk
+constexpr int kDmStage = kDmSub * kDmKC * 2;   // 16 KB
+constexpr int kDmNST = 5;                      // W ring stages: filled kDmNST - 1 steps ahead (64 KB per CU in flight)
+constexpr int kDmWT = kDmStage / 1024 / kLmWaves;   // W transfers per wave and step (4)
+constexpr int kDmTTMax = 16;
+
+template <int N> __device__ __forceinline__ void lm_wait_vmcnt() {
+  static_assert(N >= 0 && N <= 63, "vmcnt is a six-bit field");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));    // expcnt / lgkmcnt: no wait
+}
+// one transfer: lane i's 16 bytes at vaddr land at lds_addr + 16 i (lds_addr uniform)
+template <bool NT>
+__device__ __forceinline__ void lm_dma16(unsigned lds_addr, const void* vaddr) {
+  if constexpr (NT)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt"
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(vaddr) : "memory", "m0");
+  else
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(vaddr) : "memory", "m0");
+}
+
+template <int TT, int RB>
+__global__ __launch_bounds__(kLmThreads) void lm_head_dma_kernel(LmHeadArgs a) {
+  static_assert(TT >= 1 && TT <= kDmTTMax && (RB == 1 || RB == 2), "shape");
+  constexpr int ROWS = kLmWaves * RB * 16;                                   // positions per workgroup
+  constexpr int BT = RB * 8;                                                 // hidden transfers per wave and chunk
+  constexpr int kHidWave = RB * 16 * kDmKC * 2;                              // bytes of a wave's hidden region
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  int* row_of = reinterpret_cast<int*>(lds_raw + kDmNST * kDmStage + kLmWaves * kHidWave);   // ROWS ids (-1 = none)
+  __shared__ int wsum[kLmWaves];
+  // LDS byte addresses (what m0 and the read instructions take)
+  const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)lds_raw;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const unsigned hid0 = lds0 + kDmNST * kDmStage + wave * kHidWave;          // this wave's hidden region
+  const int tile = blockIdx.x;                                               // < a.ntile by the grid size
+
+  // ---- compact the masked rows
+  int running = 0;
+  for (int base = 0; base < a.rows_total; base += kLmThreads) {
+    const int i = base + tid;
+    const bool f = i < a.rows_total && a.masked[i] != 0;
+    const unsigned long long bal = __ballot(f);
+    const int rank = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) wsum[wave] = __popcll(bal);
+    __syncthreads();
+    int pre = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kLmWaves; ++w) { const int c = wsum[w]; pre += (w < wave) ? c : 0; tot += c; }
+    const int ci = running + pre + rank;
+    if (f && ci < ROWS) row_of[ci] = i;
+    running += tot;
+    __syncthreads();
+    if (running > a.max_masked) break;             // uniform: another shape's launch has this call
+  }
+  if (running < a.min_masked || running > a.max_masked) return;
+  const int n_valid = min(running, ROWS);          // uniform
+  if (n_valid <= 0) return;
+  if (tid < ROWS && tid >= n_valid) row_of[tid] = -1;
+  __syncthreads();
+
+  const int NCH = (a.Hd + kDmKC - 1) / kDmKC;      // chunks of Hd
+  const int NU = NCH * TT;                         // (chunk, sub-tile) steps of the walk
+  const int c0 = tile % NCH;                       // this workgroup's rotation of the chunk order
+  const int q = lane >> 4, l16 = lane & 15;
+  const unsigned klast = (unsigned)(a.Hd - 8);     // last whole 16-byte piece of a row
+  const int half = lane >> 5, slot = lane & 31;    // a transfer covers two LDS rows of 32 slots
+  auto chunk_at = [&](int kc) { int c = min(kc, NCH - 1) + c0; return c - ((c >= NCH) ? NCH : 0); };
+
+  // W transfer j (0..3) of this wave fills rows 8 wave + 2 j + half of a sub-tile; LDS slot s of row r
+  // holds piece s ^ (r & 15)
+  const unsigned char* wrow[kDmWT];                // row 8 wave + 2 j + half of the workgroup's first sub-tile
+  unsigned wpiece[kDmWT];
+#pragma unroll
+  for (int j = 0; j < kDmWT; ++j) {
+    const int r = 8 * wave + 2 * j + half;
+    wpiece[j] = (unsigned)(slot ^ (r & 15));
+    wrow[j] = nullptr;
+  }
+  const long long vrow0 = (long long)tile * (TT * kDmSub) + 8 * wave + half;
+  auto issue_w = [&](int u) {                      // step u of the walk (clamped to the last one) into stage u % 4
+    const int uc = min(u, NU - 1);
+    const int kc = uc / TT, t = uc - kc * TT;
+    const unsigned kb = (unsigned)(chunk_at(kc) * kDmKC);
+    const unsigned st = lds0 + (unsigned)(u % kDmNST) * kDmStage + wave * (kDmWT * 1024);
+#pragma unroll
+    for (int j = 0; j < kDmWT; ++j) {
+      const long long n = min(vrow0 + t * kDmSub + 2 * j, (long long)a.V - 1);   // rows past V: any valid row
+      const unsigned k = min(kb + 8 * wpiece[j], klast);                          // pieces past Hd: any valid piece
+      lm_dma16<true>(st + j * 1024, a.weight + n * a.ld_w + k);
+    }
+  };
+  // hidden transfer j (0..BT-1) fills rows 2 j + half of this wave's region (row = rb * 16 + position in block)
+  unsigned hoff[BT], hpiece[BT];
+#pragma unroll
+  for (int j = 0; j < BT; ++j) {
+    const int r = 2 * j + half;                    // 0 .. RB * 16 - 1
+    hoff[j] = (unsigned)((long long)max(row_of[wave * RB * 16 + r], 0) * a.ld_h);   // B*K*ld_h < 2^31 is validated
+    hpiece[j] = (unsigned)(slot ^ (r & 15));
+  }
+  auto issue_b = [&](int kc) {                     // chunk at walk position kc (clamped to the last one)
+    const unsigned kb = (unsigned)(chunk_at(kc) * kDmKC);
+#pragma unroll
+    for (int j = 0; j < BT; ++j)
+      lm_dma16<false>(hid0 + j * 1024, a.hidden + hoff[j] + min(kb + 8 * hpiece[j], klast));
+  };
+  // operand reads: row (block * 16 + l16), piece 4 ks + q, swizzled by the row (row & 15 = l16)
+  bf16x8 bcur[kDmKS][RB];
+  auto read_b = [&](int kc) {                      // this wave's region -> registers; zeros past Hd
+    const unsigned kb = (unsigned)(chunk_at(kc) * kDmKC);
+#pragma unroll
+    for (int ks = 0; ks < kDmKS; ++ks) {
+      const unsigned keep = (kb + 32 * ks + 8 * q < (unsigned)a.Hd) ? 0xffffffffu : 0u;
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        const unsigned off = (unsigned)((rb * 16 + l16) * (kDmKC * 2) + (((4 * ks + q) ^ l16) << 4));
+        const u32x4 v = *reinterpret_cast<const u32x4*>(lds_raw + kDmNST * kDmStage + wave * kHidWave + off);
+        bcur[ks][rb] = __builtin_bit_cast(bf16x8, v & u32x4{keep, keep, keep, keep});
+      }
+    }
+  };
+
+  f32x4 acc[TT][2][RB];
+#pragma unroll
+  for (int t = 0; t < TT; ++t)
+#pragma unroll
+    for (int ib = 0; ib < 2; ++ib)
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) acc[t][ib][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // ---- prologue: the first chunk's hidden rows, steps 0..2 of W
+  issue_b(0);
+#pragma unroll
+  for (int u = 0; u < kDmNST - 1; ++u) issue_w(u);
+  lm_wait_vmcnt<0>();
+  __syncthreads();
+
+  for (int kc = 0; kc < NCH; ++kc) {
+    // the hidden rows of this chunk were asked for at the start of the chunk before (or in the prologue);
+    // issued after them by this wave: that chunk's TT steps of W
+    lm_wait_vmcnt<(TT * kDmWT < 63 ? TT * kDmWT : 63)>();
+    read_b(kc);
+    // the next chunk's rows may only start to arrive in the region once these reads have returned
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    issue_b(kc + 1);
+#pragma unroll
+    for (int t = 0; t < TT; ++t) {
+      const int u = kc * TT + t;
+      issue_w(u + kDmNST - 1);                     // into the stage that step u - 1 has finished reading
+      __builtin_amdgcn_sched_barrier(0);
+      const unsigned char* cur = lds_raw + (unsigned)(u % kDmNST) * kDmStage;
+      // all A operands of the step are asked for at once: the matrix instructions then run back to back,
+      // each waiting only for its own operand
+      bf16x8 aop[kDmKS][2];
+#pragma unroll
+      for (int ks = 0; ks < kDmKS; ++ks) {
+        const unsigned po = (unsigned)(l16 * (kDmKC * 2) + (((4 * ks + q) ^ l16) << 4));
+        aop[ks][0] = *reinterpret_cast<const bf16x8*>(cur + po);
+        aop[ks][1] = *reinterpret_cast<const bf16x8*>(cur + 16 * (kDmKC * 2) + po);
+      }
+      __builtin_amdgcn_sched_barrier(0);           // (the scheduler would sink the reads back between the MFMAs)
+#pragma unroll
+      for (int ks = 0; ks < kDmKS; ++ks)
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+          acc[t][0][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[ks][0], bcur[ks][rb], acc[t][0][rb], 0, 0, 0);
+          acc[t][1][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[ks][1], bcur[ks][rb], acc[t][1][rb], 0, 0, 0);
+        }
+      __builtin_amdgcn_sched_barrier(0);
+      // step u + 1 must have landed before the barrier: issued after it by this wave are the D = kDmNST - 2
+      // steps u + 2 .. u + kDmNST - 1 (one in each of the steps u - D + 1 .. u), and the next chunk's hidden
+      // rows wherever one of those steps began a chunk (t < D; with TT < D more than one of them may have)
+      constexpr int D = kDmNST - 2;
+      const int chunk_starts = TT >= D ? (t < D ? 1 : 0) : (D - 1 - t) / TT + 1;
+      static_assert(D * kDmWT + D * BT <= 63, "vmcnt");
+      if (chunk_starts == 0) lm_wait_vmcnt<D * kDmWT>();
+      else if (chunk_starts == 1) lm_wait_vmcnt<D * kDmWT + BT>();
+      else if (chunk_starts == 2) lm_wait_vmcnt<D * kDmWT + 2 * BT>();
+      else lm_wait_vmcnt<D * kDmWT + 3 * BT>();
+      __syncthreads();
+    }
+  }
+  lm_wait_vmcnt<0>();                              // nothing of this workgroup's is in flight when it ends
+
+  // ---- row reduction: this lane holds, for row (wave RB + rb) * 16 + l16, the ids t * 32 + ib * 16 + 4 q + r
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    float m = kNegBig; int idx = 0x7fffffff;
+#pragma unroll
+    for (int t = 0; t < TT; ++t)
+#pragma unroll
+      for (int ib = 0; ib < 2; ++ib)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int n = tile * (TT * kDmSub) + t * kDmSub + ib * 16 + 4 * q + r;
+          float v = acc[t][ib][rb][r];
+          if (n >= a.V) v = -INFINITY;
+          acc[t][ib][rb][r] = v;
+          if (v > m) { m = v; idx = n; }             // ascending ids, strict: the lowest id keeps a tie
+        }
+    const float ml = m * kLog2e;
+    float s = 0.f;
+#pragma unroll
+    for (int t = 0; t < TT; ++t)
+#pragma unroll
+      for (int ib = 0; ib < 2; ++ib)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) s += fast_exp2(fmaf(acc[t][ib][rb][r], kLog2e, -ml));
+#pragma unroll
+    for (int off = 16; off <= 32; off <<= 1) {
+      const float m2 = __shfl_xor(m, off); const float s2 = __shfl_xor(s, off); const int i2 = __shfl_xor(idx, off);
+      merge_partial(m, s, idx, m2, s2, i2);
+    }
+    const int row = row_of[(wave * RB + rb) * 16 + l16];
+    if (q == 0 && row >= 0) store_partial(a, row, tile, Partial{m, s, idx});
+  }
+}
+
 // ---- host side ----
-// bm: the shape for B x K positions all masked (32 / 64: the stream kernels, 256: the rows kernel).  The stream
-// shapes that serve smaller masked counts are launched too; ntile_out is the largest tile count among them.
-struct LmPlan { int bm, bn, ntile, nchunk, tt32, ntile32, tt64, ntile64, ntile_out; };
+// The kernel shapes, by the masked counts they serve: up to 32 (stream, B operands in registers), up to 64
+// (stream, hidden chunk in LDS), up to 128 (stream, global -> LDS transfers), any (256-row chunks).
+enum { kShape32 = 0, kShape64, kShape128, kShapeRows, kNumShapes };
+constexpr int kShapeMax[kNumShapes] = {32, kSt2Rows, 128, INT_MAX};
 
 // Sub-tiles per workgroup of a stream kernel, out of the counts it is compiled for.  One workgroup per CU is
 // resident, so a launch runs in rounds of kNumCUs workgroups and costs about rounds x (sub-tiles + a half for
 // the prologue): 126464 vocabulary rows take 16 sub-tiles (247 workgroups), 152064 take 20 (238 workgroups; 16
-// would leave 41 of 297 for a second round) or, with two row blocks per wave, 10 (476 workgroups, two rounds).
+// would leave 41 of 297 for a second round) or, where the accumulators allow no more, 10 (476, two rounds).
 constexpr int kStTTs[] = {2, 4, 8, 12, 16, 20};
 constexpr int kSt2TTs[] = {2, 4, 8, 10, 12, 16};
+constexpr int kDmTTs[] = {1, 2, 3, 4, 6, 8, 10, 16};
+static_assert(kStSub == kDmSub, "one sub-tile size for the tile-size choice");
 
 template <size_t N>
 static int stream_tt(int V, const int (&tts)[N]) {
@@ -746,36 +982,46 @@ static int stream_tt(int V, const int (&tts)[N]) {
   return best;
 }
 
+// top: the shape for B x K positions all masked; the shapes below it are launched too and serve the smaller
+// masked counts; ntile_out is the largest tile count among the launched shapes.
+struct LmPlan { int top, nchunk, tt[kNumShapes], bn[kNumShapes], ntile[kNumShapes], ntile_out; };
+
 static LmPlan lm_plan(const sdllm_lm_head_params& p) {
   const long long rows = (long long)p.B * p.K;
   LmPlan pl;
-  pl.tt32 = stream_tt(p.V, kStTTs);
-  pl.ntile32 = (p.V + pl.tt32 * kStSub - 1) / (pl.tt32 * kStSub);
-  pl.tt64 = stream_tt(p.V, kSt2TTs);
-  pl.ntile64 = (p.V + pl.tt64 * kStSub - 1) / (pl.tt64 * kStSub);
-  if (rows <= 32) { pl.bm = 32; pl.bn = pl.tt32 * kStSub; pl.ntile = pl.ntile32; pl.ntile_out = pl.ntile32; }
-  else if (rows <= 64) {
-    pl.bm = 64; pl.bn = pl.tt64 * kStSub; pl.ntile = pl.ntile64; pl.ntile_out = std::max(pl.ntile32, pl.ntile64);
-  } else {            // also for 65..128 rows: a half-empty 256-row tile beat 128-row tiles
-    pl.bm = 256; pl.bn = 256; pl.ntile = (p.V + pl.bn - 1) / pl.bn;
-    pl.ntile_out = std::max(pl.ntile, std::max(pl.ntile32, pl.ntile64));
+  pl.tt[kShape32] = stream_tt(p.V, kStTTs);
+  pl.tt[kShape64] = stream_tt(p.V, kSt2TTs);
+  pl.tt[kShape128] = stream_tt(p.V, kDmTTs);
+  pl.tt[kShapeRows] = 256 / kStSub;       // 256-row tiles (also for a half-empty chunk: it beat 128-row tiles)
+  pl.top = 0;
+  while (rows > kShapeMax[pl.top]) ++pl.top;
+  pl.ntile_out = 0;
+  for (int i = 0; i < kNumShapes; ++i) {
+    pl.bn[i] = pl.tt[i] * kStSub;
+    pl.ntile[i] = (p.V + pl.bn[i] - 1) / pl.bn[i];
+    if (i <= pl.top) pl.ntile_out = std::max(pl.ntile_out, pl.ntile[i]);
   }
-  pl.nchunk = (int)((rows + pl.bm - 1) / pl.bm);
+  pl.nchunk = pl.top == kShapeRows ? (int)((rows + 255) / 256) : 1;
   return pl;
 }
 
-static size_t lm_lds_bytes(int bm) {
-  if (bm == 32) return 2 * (size_t)kStStage + 32 * sizeof(int) + (size_t)kLmWaves * 16 * sizeof(Partial);
-  if (bm == 64) return 2 * (size_t)kStStage + kSt2Hid + kSt2Rows * sizeof(int) + (size_t)kLmWaves * 32 * sizeof(Partial);
-  return (size_t)3 * kLmStageBytes + bm * sizeof(int) + (size_t)kLmWaves * bm * sizeof(Partial);   // LmShape::NST
+static size_t lm_lds_bytes(int shape) {
+  switch (shape) {
+    case kShape32: return 2 * (size_t)kStStage + 32 * sizeof(int) + (size_t)kLmWaves * 16 * sizeof(Partial);
+    case kShape64: return 2 * (size_t)kStStage + kSt2Hid + kSt2Rows * sizeof(int) + (size_t)kLmWaves * 32 * sizeof(Partial);
+    case kShape128: return (size_t)kDmNST * kDmStage + (size_t)kLmWaves * (2 * 16 * kDmKC * 2) + 128 * sizeof(int);
+    default: return (size_t)3 * kLmStageBytes + 256 * sizeof(int) + (size_t)kLmWaves * 256 * sizeof(Partial);   // LmShape::NST
+  }
 }
 
 void lm_head_plan(const sdllm_lm_head_params& p, sdllm_lm_head_plan* plan) {
   const LmPlan pl = lm_plan(p);
-  plan->rows_per_chunk = pl.bm; plan->vocab_rows_per_tile = pl.bn; plan->vocab_tiles = pl.ntile;
+  const int t = pl.top;
+  plan->rows_per_chunk = t == kShapeRows ? 256 : kShapeMax[t];
+  plan->vocab_rows_per_tile = pl.bn[t]; plan->vocab_tiles = pl.ntile[t];
   plan->row_chunks = pl.nchunk;
-  plan->workgroups = pl.bm <= 64 ? pl.ntile : ((pl.ntile + kNumXCDs - 1) / kNumXCDs) * pl.nchunk * kNumXCDs;
-  plan->lds_bytes = (int32_t)lm_lds_bytes(pl.bm);
+  plan->workgroups = t != kShapeRows ? pl.ntile[t] : ((pl.ntile[t] + kNumXCDs - 1) / kNumXCDs) * pl.nchunk * kNumXCDs;
+  plan->lds_bytes = (int32_t)lm_lds_bytes(t);
   plan->triples_per_position = pl.ntile_out;
 }
 
@@ -783,62 +1029,71 @@ size_t lm_head_workspace_bytes(const sdllm_lm_head_params& p) {
   return (size_t)p.B * p.K * lm_plan(p).ntile_out * sizeof(Partial);
 }
 
-template <int BM, int WNB, int PF>
-static hipError_t launch_rows(const LmHeadArgs& r, unsigned grid, hipStream_t stream) {
-  static_assert(LmShape<BM, WNB, PF>::NST == 3 && LmShape<BM, WNB, PF>::BN == 256, "lm_lds_bytes, lm_plan");
-  const size_t lds = lm_lds_bytes(BM);
-  static bool attr_set = false;                     // > 64 KiB of dynamic LDS needs the opt-in, once
+// one launch; the kernel's opt-in to more than 64 KiB of dynamic LDS is set once
+static hipError_t launch_kernel(void (*kernel)(LmHeadArgs), bool& attr_set, int shape, unsigned grid,
+                                const LmHeadArgs& r, hipStream_t stream) {
+  const size_t lds = lm_lds_bytes(shape);
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_rows_kernel<BM, WNB, PF>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
-  hipLaunchKernelGGL((lm_head_rows_kernel<BM, WNB, PF>), dim3(grid), dim3(kLmThreads), lds, stream, r);
-  return hipGetLastError();
-}
-
-// the two stream shapes: one workgroup per 32 tt vocabulary rows, every position of the call in it
-static hipError_t launch_stream_kernel(void (*kernel)(LmHeadArgs), bool& attr_set, int bm, const LmHeadArgs& r,
-                                       hipStream_t stream) {
-  const size_t lds = lm_lds_bytes(bm);
-  if (!attr_set) {                                  // > 64 KiB of dynamic LDS needs the opt-in, once per kernel
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(kernel, dim3((unsigned)r.ntile), dim3(kLmThreads), lds, stream, r);
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(kLmThreads), lds, stream, r);
   return hipGetLastError();
 }
 
 template <int TT>
 static hipError_t launch_stream32(const LmHeadArgs& r, hipStream_t stream) {
   static bool attr_set = false;
-  return launch_stream_kernel(lm_head_stream_kernel<TT>, attr_set, 32, r, stream);
+  return launch_kernel(lm_head_stream_kernel<TT>, attr_set, kShape32, (unsigned)r.ntile, r, stream);
 }
 template <int TT>
 static hipError_t launch_stream64(const LmHeadArgs& r, hipStream_t stream) {
   static bool attr_set = false;
-  return launch_stream_kernel(lm_head_stream64_kernel<TT>, attr_set, 64, r, stream);
+  return launch_kernel(lm_head_stream64_kernel<TT>, attr_set, kShape64, (unsigned)r.ntile, r, stream);
+}
+template <int TT>
+static hipError_t launch_stream128(const LmHeadArgs& r, hipStream_t stream) {
+  static bool attr_set = false;
+  return launch_kernel(lm_head_dma_kernel<TT, 2>, attr_set, kShape128, (unsigned)r.ntile, r, stream);
+}
+static hipError_t launch_rows(const LmHeadArgs& r, hipStream_t stream) {
+  static_assert(LmShape<256, 4, 4>::NST == 3 && LmShape<256, 4, 4>::BN == 256, "lm_lds_bytes, lm_plan");
+  static bool attr_set = false;
+  const unsigned grid = (unsigned)(((r.ntile + kNumXCDs - 1) / kNumXCDs) * r.nchunk * kNumXCDs);
+  return launch_kernel(lm_head_rows_kernel<256, 4, 4>, attr_set, kShapeRows, grid, r, stream);
 }
 
-static hipError_t launch_stream(int bm, int tt, const LmHeadArgs& r, hipStream_t stream) {
-  if (bm == 32) switch (tt) {       // kStTTs
-    case 2: return launch_stream32<2>(r, stream);
-    case 4: return launch_stream32<4>(r, stream);
-    case 8: return launch_stream32<8>(r, stream);
-    case 12: return launch_stream32<12>(r, stream);
-    case 16: return launch_stream32<16>(r, stream);
-    case 20: return launch_stream32<20>(r, stream);
-  }
-  else switch (tt) {                // kSt2TTs
-    case 2: return launch_stream64<2>(r, stream);
-    case 4: return launch_stream64<4>(r, stream);
-    case 8: return launch_stream64<8>(r, stream);
-    case 10: return launch_stream64<10>(r, stream);
-    case 12: return launch_stream64<12>(r, stream);
-    case 16: return launch_stream64<16>(r, stream);
+static hipError_t launch_shape(int shape, int tt, const LmHeadArgs& r, hipStream_t stream) {
+  switch (shape) {
+    case kShape32: switch (tt) {       // kStTTs
+      case 2: return launch_stream32<2>(r, stream);
+      case 4: return launch_stream32<4>(r, stream);
+      case 8: return launch_stream32<8>(r, stream);
+      case 12: return launch_stream32<12>(r, stream);
+      case 16: return launch_stream32<16>(r, stream);
+      case 20: return launch_stream32<20>(r, stream);
+    } break;
+    case kShape64: switch (tt) {       // kSt2TTs
+      case 2: return launch_stream64<2>(r, stream);
+      case 4: return launch_stream64<4>(r, stream);
+      case 8: return launch_stream64<8>(r, stream);
+      case 10: return launch_stream64<10>(r, stream);
+      case 12: return launch_stream64<12>(r, stream);
+      case 16: return launch_stream64<16>(r, stream);
+    } break;
+    case kShape128: switch (tt) {      // kDmTTs
+      case 1: return launch_stream128<1>(r, stream);
+      case 2: return launch_stream128<2>(r, stream);
+      case 3: return launch_stream128<3>(r, stream);
+      case 4: return launch_stream128<4>(r, stream);
+      case 6: return launch_stream128<6>(r, stream);
+      case 8: return launch_stream128<8>(r, stream);
+      case 10: return launch_stream128<10>(r, stream);
+      case 16: return launch_stream128<16>(r, stream);
+    } break;
+    case kShapeRows: return launch_rows(r, stream);
   }
   return hipErrorInvalidValue;      // not reached: lm_plan picks from the same lists
 }
@@ -852,24 +1107,15 @@ hipError_t launch_lm_head_unmask(const sdllm_lm_head_params& p, const void* hidd
   r.partials = (Partial*)workspace;
   r.ld_h = p.ld_h; r.ld_w = p.ld_w;
   r.rows_total = p.B * p.K; r.V = p.V; r.Hd = p.Hd;
-  r.ntile = pl.ntile; r.nchunk = pl.nchunk; r.ntile_out = pl.ntile_out;
-  r.min_masked = 0; r.max_masked = INT_MAX;
+  r.nchunk = pl.nchunk; r.ntile_out = pl.ntile_out;
   hipError_t e = hipSuccess;
-  if (pl.bm == 32) e = launch_stream(32, pl.tt32, r, stream);
-  else {
-    // the stream shapes take the call when few enough positions are still masked (the later steps of a block)
-    LmHeadArgs s = r;
-    s.ntile = pl.ntile32; s.min_masked = 1; s.max_masked = 32;
-    e = launch_stream(32, pl.tt32, s, stream);
-    if (e != hipSuccess) return e;
-    s.ntile = pl.ntile64; s.min_masked = 33; s.max_masked = pl.bm == 64 ? INT_MAX : kSt2Rows;
-    e = launch_stream(64, pl.tt64, s, stream);
-    if (e != hipSuccess) return e;
-    if (pl.bm > 64) {
-      const unsigned grid = (unsigned)(((pl.ntile + kNumXCDs - 1) / kNumXCDs) * pl.nchunk * kNumXCDs);
-      r.min_masked = kSt2Rows + 1;
-      e = launch_rows<256, 4, 4>(r, grid, stream);
-    }
+  // every shape up to the one that B x K needs: the smaller ones take the call when few enough positions are
+  // still masked (the later steps of a block); each launch exits unless the masked count is in its range
+  for (int i = 0; i <= pl.top && e == hipSuccess; ++i) {
+    r.ntile = pl.ntile[i];
+    r.min_masked = i == 0 ? 1 : kShapeMax[i - 1] + 1;
+    r.max_masked = i == pl.top ? INT_MAX : kShapeMax[i];
+    e = launch_shape(i, pl.tt[i], r, stream);
   }
   if (e != hipSuccess) return e;
 

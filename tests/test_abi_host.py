@@ -243,21 +243,21 @@ def test_probe_validation(lib):
 
 
 @pytest.mark.parametrize("B,K,V,Hd", [(1, 1, 1, 32), (1, 32, 126464, 4096), (2, 32, 5000, 512), (3, 40, 777, 96),
-                                       (8, 32, 126464, 4096), (16, 32, 152064, 3584), (9, 32, 700, 1024), (2, 32, 126464, 4096), (1, 32, 152064, 3584), (2, 32, 152064, 3584), (16, 4096, 100, 32)])
+                                       (8, 32, 126464, 4096), (16, 32, 152064, 3584), (9, 32, 700, 1024), (2, 32, 126464, 4096), (4, 32, 126464, 4096), (3, 32, 152064, 3584), (4, 32, 700, 64), (1, 32, 152064, 3584), (2, 32, 152064, 3584), (16, 4096, 100, 32)])
 def test_lm_head_plan_is_consistent(lib, B, K, V, Hd):
     p = sd.lm_head_params(B, K, V, Hd, Hd, Hd, 0.9, 0.3)
     pl = sd.plan_lm_head(p)
     rows = B * K
-    assert pl.rows_per_chunk in (32, 64, 256)
+    assert pl.rows_per_chunk in (32, 64, 128, 256)
     assert (pl.rows_per_chunk >= min(rows, 256)) and (rows > 32 or pl.rows_per_chunk == 32)
     assert pl.vocab_tiles * pl.vocab_rows_per_tile >= V > (pl.vocab_tiles - 1) * pl.vocab_rows_per_tile
     assert pl.row_chunks * pl.rows_per_chunk >= rows > (pl.row_chunks - 1) * pl.rows_per_chunk
-    if rows <= 64:
-        # stream shapes: an even number of 32-row sub-tiles per workgroup out of the compiled counts; one
+    if rows <= 128:
+        # stream shapes: 32-row sub-tiles per workgroup out of the compiled counts; one
         # workgroup per CU is resident, so the launch runs in rounds of 256 workgroups
         tt = pl.vocab_rows_per_tile // 32
-        assert pl.vocab_rows_per_tile % 64 == 0
-        assert tt in ((2, 4, 8, 12, 16, 20) if rows <= 32 else (2, 4, 8, 10, 12, 16))
+        assert pl.vocab_rows_per_tile % 32 == 0
+        assert tt in ((2, 4, 8, 12, 16, 20) if rows <= 32 else (2, 4, 8, 10, 12, 16) if rows <= 64 else (1, 2, 3, 4, 6, 8, 10, 16))
         assert pl.workgroups == pl.vocab_tiles and pl.row_chunks == 1
         rounds = -(-pl.vocab_tiles // 256)
         ideal = -(-V // 32) / 256.0                   # sub-tiles per CU if they could be spread evenly

@@ -115,6 +115,7 @@ def _oracle(h, W, tokens, masked, tau0, alpha, **kw):
 @pytest.mark.parametrize("B,K,Hd,V", [
     (1, 8, 32, 1), (1, 32, 64, 100), (2, 16, 96, 129), (1, 32, 1056, 1000), (1, 32, 512, 4099),
     (2, 32, 288, 300), (3, 20, 544, 777), (1, 64, 1024, 2048), (2, 24, 1568, 1100),
+    (3, 32, 288, 300), (4, 25, 544, 777), (1, 128, 1024, 2048), (4, 32, 1568, 1100), (2, 60, 32, 40000),
     (5, 32, 160, 513), (3, 64, 416, 1500), (9, 32, 1024, 700), (2, 160, 256, 2000),
     (4, 600, 64, 300),        # 2400 positions: ten passes of the mask scan, ten row chunks, two triples per position
     (2, 600, 64, 20000),      # 79 triples per position and more positions than the commit kernel has lanes to spare
@@ -129,7 +130,7 @@ def test_lm_head_shapes(gpu_lib, B, K, Hd, V):
     assert skipped <= 1
 
 
-_TILE_CASES = [3000, 20000, 50000, 80000, 90000, 126464, 152064]
+_TILE_CASES = [3000, 12000, 20000, 30000, 45000, 50000, 60000, 80000, 90000, 126464, 152064]
 
 
 def test_tile_cases_cover_every_compiled_stream_kernel(gpu_lib):
@@ -137,14 +138,16 @@ def test_tile_cases_cover_every_compiled_stream_kernel(gpu_lib):
               for V in _TILE_CASES}
     seen64 = {gpu_lib.plan_lm_head(gpu_lib.lm_head_params(2, 32, V, 64, 64, 64, 0.9, 0.3)).vocab_rows_per_tile // 32
               for V in _TILE_CASES}
-    assert seen32 == {2, 4, 8, 12, 16, 20} and seen64 == {2, 4, 8, 10, 12, 16}
+    seen128 = {gpu_lib.plan_lm_head(gpu_lib.lm_head_params(4, 32, V, 64, 64, 64, 0.9, 0.3)).vocab_rows_per_tile // 32
+               for V in _TILE_CASES}
+    assert seen32 == {2, 4, 8, 12, 16, 20} and seen64 == {2, 4, 8, 10, 12, 16} and seen128 == {1, 2, 3, 4, 6, 8, 10, 16}
 
 
 @pytest.mark.parametrize("V", _TILE_CASES)
-@pytest.mark.parametrize("B", [1, 2])
+@pytest.mark.parametrize("B", [1, 2, 4])
 def test_lm_head_every_vocabulary_tile_size(gpu_lib, B, V):
     # the stream kernels are compiled for a list of tile sizes and the vocabulary size picks one: every one of
-    # them runs here (narrow hidden width, so that the oracle stays cheap), masked counts 24 and 48
+    # them runs here (narrow hidden width, so that the oracle stays cheap), about 24, 48 and 96 masked positions
     K, Hd = 32, 64
     h, W, tokens, masked, hd, Wd = _host_case(B, K, Hd, V, seed=V + B, frac=0.75, std=1.0)
     got = run_gpu(gpu_lib, hd, Wd, tokens, masked, 0.3, 0.3)
@@ -153,8 +156,8 @@ def test_lm_head_every_vocabulary_tile_size(gpu_lib, B, V):
     assert skipped <= 1 and n_gap <= masked.sum() // 2      # most positions have a clear arg-max to compare
 
 
-@pytest.mark.parametrize("B,K", [(2, 32), (5, 32), (9, 64)])
-@pytest.mark.parametrize("n_masked", [1, 31, 32, 33, 63, 64, 65, 130])
+@pytest.mark.parametrize("B,K", [(2, 32), (4, 32), (5, 32), (9, 64)])
+@pytest.mark.parametrize("n_masked", [1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 160])
 def test_lm_head_shape_follows_the_masked_count(gpu_lib, B, K, n_masked):
     # the masked count is device data: every shape that B x K admits is launched and the one whose range holds
     # the count does the work; counts on both sides of each boundary, spread over the sequences, with V chosen so
@@ -175,6 +178,7 @@ def test_lm_head_shape_follows_the_masked_count(gpu_lib, B, K, n_masked):
 
 
 @pytest.mark.parametrize("B,K,Hd,V,ld_h,ld_w", [(2, 16, 64, 200, 72, 80), (2, 32, 320, 1000, 328, 384),
+                                                 (4, 32, 320, 1000, 328, 384),
                                                  (3, 32, 320, 1000, 328, 384)])
 def test_lm_head_row_strides_and_poisoned_padding(gpu_lib, B, K, Hd, V, ld_h, ld_w):
     h, W, tokens, masked, hd, Wd = _host_case(B, K, Hd, V, seed=77, ld_h=ld_h, ld_w=ld_w)
@@ -254,6 +258,12 @@ def test_lm_head_cfg2_two_sequences_full_size(gpu_lib):
     # 64 positions: the stream shape that keeps the hidden chunk in LDS, at the full vocabulary and width
     skipped, _ = _full_size(gpu_lib, "cfg2", B=2)
     assert skipped == 0
+
+
+def test_lm_head_cfg2_four_sequences_full_size(gpu_lib):
+    # 128 positions: the stream shape fed by global -> LDS transfers, at the full vocabulary and width
+    skipped, _ = _full_size(gpu_lib, "cfg2", B=4)
+    assert skipped <= 1
 
 
 def test_lm_head_cfg3A_full_size(gpu_lib):
