@@ -59,6 +59,23 @@ __device__ __forceinline__ void store_partial(const LmHeadArgs& a, int row, int 
   for (int j = tile + a.ntile; j < a.ntile_out; j += a.ntile) out[j] = Partial{kNegBig, 0.f, 0x7fffffff};
 }
 
+// Number of masked positions of the call (uniform over the workgroup): one pass over the mask bytes without
+// barriers, then one reduction.  wsum: kLmWaves ints of LDS, free for other use on return.
+__device__ __forceinline__ int lm_masked_count(const LmHeadArgs& a, int* wsum) {
+  const int tid = threadIdx.x;
+  int mine = 0;
+  for (int i = tid; i < a.rows_total; i += kLmThreads) mine += a.masked[i] != 0;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) mine += __shfl_xor(mine, off);
+  if ((tid & 63) == 0) wsum[tid >> 6] = mine;
+  __syncthreads();
+  int total = 0;
+#pragma unroll
+  for (int w = 0; w < kLmWaves; ++w) total += wsum[w];
+  __syncthreads();
+  return total;
+}
+
 
 template <int BM, int WNB, int PF_>
 struct LmShape {
@@ -110,17 +127,8 @@ __global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB, PF_>::MIN_WAVES)) voi
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  // ---- the masked count decides how many row chunks there are (uniform): one pass without barriers
-  int mine = 0;
-  for (int i = tid; i < a.rows_total; i += kLmThreads) mine += a.masked[i] != 0;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) mine += __shfl_xor(mine, off);
-  if (lane == 0) wsum[wave] = mine;
-  __syncthreads();
-  int total = 0;
-#pragma unroll
-  for (int w = 0; w < kLmWaves; ++w) total += wsum[w];
-  __syncthreads();                                 // wsum is written again below
+  // ---- the masked count decides how many row chunks there are
+  const int total = lm_masked_count(a, wsum);
   if (total < max(a.min_masked, 1)) return;        // another shape's launch has this call, or nothing is masked
   const int nact = (total + BM - 1) / BM;          // <= a.nchunk, since total <= rows_total
   // ---- workgroup -> (vocabulary tile, row chunk): chunks of a tile share id mod 8 (the XCD) and are adjacent
@@ -402,7 +410,12 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_stream_kernel(LmHeadArgs a
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int tile = blockIdx.x;                                               // < a.ntile by the grid size
 
-  // ---- compact the masked rows (rows_total <= 32 here, the loop is the general one)
+  // ---- this launch works only if the masked count is in its range (another shape's launch has the call
+  // otherwise); then the masked rows are compacted
+  {
+    const int total = lm_masked_count(a, wsum);
+    if (total < a.min_masked || total > a.max_masked) return;
+  }
   int running = 0;
   for (int base = 0; base < a.rows_total; base += kLmThreads) {
     const int i = base + tid;
@@ -418,9 +431,7 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_stream_kernel(LmHeadArgs a
     if (f && ci < 32) row_of[ci] = i;
     running += tot;
     __syncthreads();
-    if (running > a.max_masked) break;             // uniform: another shape's launch has this call
   }
-  if (running < a.min_masked || running > a.max_masked) return;
   const int n_valid = min(running, 32);            // uniform
   if (n_valid <= 0) return;
   if (tid < 32 && tid >= n_valid) row_of[tid] = -1;
@@ -565,7 +576,12 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_stream64_kernel(LmHeadArgs
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int tile = blockIdx.x;                                               // < a.ntile by the grid size
 
-  // ---- compact the masked rows (rows_total <= 64 here, the loop is the general one)
+  // ---- this launch works only if the masked count is in its range (another shape's launch has the call
+  // otherwise); then the masked rows are compacted
+  {
+    const int total = lm_masked_count(a, wsum);
+    if (total < a.min_masked || total > a.max_masked) return;
+  }
   int running = 0;
   for (int base = 0; base < a.rows_total; base += kLmThreads) {
     const int i = base + tid;
@@ -581,9 +597,7 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_stream64_kernel(LmHeadArgs
     if (f && ci < kSt2Rows) row_of[ci] = i;
     running += tot;
     __syncthreads();
-    if (running > a.max_masked) break;             // uniform: another shape's launch has this call
   }
-  if (running < a.min_masked || running > a.max_masked) return;
   const int n_valid = min(running, kSt2Rows);      // uniform
   if (n_valid <= 0) return;
   if (tid < kSt2Rows && tid >= n_valid) row_of[tid] = -1;
@@ -773,7 +787,12 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_dma_kernel(LmHeadArgs a) {
   const unsigned hid0 = lds0 + kDmNST * kDmStage + wave * kHidWave;          // this wave's hidden region
   const int tile = blockIdx.x;                                               // < a.ntile by the grid size
 
-  // ---- compact the masked rows
+  // ---- this launch works only if the masked count is in its range (another shape's launch has the call
+  // otherwise); then the masked rows are compacted
+  {
+    const int total = lm_masked_count(a, wsum);
+    if (total < a.min_masked || total > a.max_masked) return;
+  }
   int running = 0;
   for (int base = 0; base < a.rows_total; base += kLmThreads) {
     const int i = base + tid;
@@ -789,9 +808,7 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_dma_kernel(LmHeadArgs a) {
     if (f && ci < ROWS) row_of[ci] = i;
     running += tot;
     __syncthreads();
-    if (running > a.max_masked) break;             // uniform: another shape's launch has this call
   }
-  if (running < a.min_masked || running > a.max_masked) return;
   const int n_valid = min(running, ROWS);          // uniform
   if (n_valid <= 0) return;
   if (tid < ROWS && tid >= n_valid) row_of[tid] = -1;
