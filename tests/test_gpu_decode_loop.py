@@ -85,14 +85,20 @@ def test_block_loop_with_append_and_early_exit(gpu_lib):
     assert eos_host[0] == 1 and blocks_decoded >= 2
 
 
-def test_block_steps_fed_by_the_vocabulary_projection(gpu_lib):
+@pytest.mark.parametrize("B,K,boost_at", [(None, None, 6), (8, 32, 30)])
+def test_block_steps_fed_by_the_vocabulary_projection(gpu_lib, B, K, boost_at):
     """The diffusion steps of one block with the logits coming from the projection of seeded hidden states
     (never stored): every step is checked against the oracle from the same state, up to block termination.
-    An unboosted projection keeps the confidences low, so most steps go through the fallback of Eq. 9 and the
-    block takes one step per position; a boosted projection at the seventh step commits what is left at once."""
+    An unboosted projection keeps the confidences low, so most steps go through the fallback of Eq. 9 and
+    commit one position per sequence; a boosted projection at step boost_at commits what is left at once.
+    With 8 x 32 positions the masked count goes 256, 248, ... down through every range that picks another
+    kernel shape of the projection (above 128, 65-128, 33-64, at most 32)."""
     sd = gpu_lib
     w = wl.WORKLOADS["small_bf16"]
+    if B is not None:
+        w = dataclasses.replace(w, B=B, K=K)
     B, K, Hd, V = w.B, w.K, 256, 1500
+    counts = []
     tau0, alpha = 0.9, 0.3
     w_plain = dataclasses.replace(w, boost=False)
     plain = wl.make_lm_head_inputs(w_plain, seed=3, V=V, Hd=Hd)        # a projection without any boosted row
@@ -103,7 +109,8 @@ def test_block_steps_fed_by_the_vocabulary_projection(gpu_lib):
     steps = checked = 0
     while masked.any():
         assert steps <= B * K, "the block must terminate"
-        boosted = steps == 6                                             # six fallback steps, then a confident one
+        boosted = steps == boost_at                                      # fallback steps, then a confident one
+        counts.append(int(masked.sum()))
         t = wl.make_lm_head_inputs(w if boosted else w_plain, seed=3, step=steps, V=V, Hd=Hd)
         h, W = t["hidden"], (t["lm_weight"] if boosted else plain["lm_weight"])
         ncom, done = sd.lm_head_unmask(to_dev(h), to_dev(W), tk, mk, tau0, alpha, confidence=conf)
@@ -133,3 +140,6 @@ def test_block_steps_fed_by_the_vocabulary_projection(gpu_lib):
         tokens, masked = g_tok.copy(), g_msk.copy()                          # the next step starts from the GPU's state
         steps += 1
     assert steps >= 4 and checked >= steps                                   # many steps, most of them comparable
+    if B * K > 128:
+        assert any(c > 128 for c in counts) and any(64 < c <= 128 for c in counts)
+        assert any(32 < c <= 64 for c in counts) and any(0 < c <= 32 for c in counts)
