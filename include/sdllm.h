@@ -191,8 +191,8 @@ int sdllm_lm_head_unmask(const sdllm_lm_head_params* p,
 
 /* Launch plan the library would use for these parameters (host only, no HIP call).  The masked count is
  * device data, so a call launches every kernel shape that B*K admits and the masked count found on the
- * device decides which of them does the work (the others exit at once): up to 32 masked positions and
- * 33..64 take two kernels that stream W once with every position resident, more take 256-position row
+ * device decides which of them does the work (the others exit at once): up to 32, 33..64 and 65..128 masked
+ * positions take three kernels that stream W once with every position resident, more take 256-position row
  * chunks.  The plan describes the shape that serves B*K masked positions: rows of hidden per row chunk,
  * rows of W per vocabulary tile, number of tiles, row chunks in the grid, workgroups launched, LDS bytes
  * per workgroup; triples_per_position is the workspace's row length (the largest tile count among the
