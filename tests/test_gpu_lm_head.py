@@ -229,6 +229,25 @@ def test_lm_head_threshold_extremes_eos_and_query_wide_ratio(gpu_lib):
     assert got["eos_seen"][b0] == 1 and got["eos_seen"][(b0 + 1) % B] == 1
 
 
+@pytest.mark.parametrize("n_masked", [40, 100, 65536])
+def test_lm_head_most_positions(gpu_lib, n_masked):
+    # B x K = 65536, the most positions the entry point takes (256 passes of the mask count and of the row
+    # compaction, 256 row chunks in the grid when all are masked), K = 4096 the longest block; a narrow
+    # projection keeps the oracle cheap.  40 / 100 masked positions go to two of the stream shapes.
+    B, K, Hd, V = 16, 4096, 32, 300
+    g = np.random.Generator(np.random.Philox(key=65536 + n_masked))
+    h = wl.f32_to_bf16_bits(g.standard_normal((B, K, Hd), dtype=np.float32))
+    W = wl.f32_to_bf16_bits(g.standard_normal((V, Hd), dtype=np.float32) * np.float32(2.0 / np.sqrt(Hd)))
+    masked = np.zeros((B, K), dtype=np.uint8)
+    masked.reshape(-1)[g.permutation(B * K)[:n_masked]] = 1
+    tokens = g.integers(0, V, size=(B, K)).astype(np.int32)
+    tokens[masked != 0] = wl.MASK_TOKEN
+    got = run_gpu(gpu_lib, to_dev(h), to_dev(W), tokens, masked, 0.2, 0.3)
+    want = _oracle(h, W, tokens, masked, 0.2, 0.3)
+    n_gap, n_band, skipped = compare(got, want, tokens, masked)
+    assert skipped <= 2
+
+
 def _full_size(gpu_lib, name, seqs=None, B=None):
     w = wl.WORKLOADS[name]
     if B is not None:

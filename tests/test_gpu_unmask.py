@@ -213,6 +213,21 @@ def test_unmask_full_size_configs(gpu_lib, name):
     assert skip <= w.B // 8
 
 
+@pytest.mark.parametrize("frac", [0.5, 1.0])
+def test_unmask_longest_block(gpu_lib, frac):
+    # K = 4096, the longest block the entry point takes (four passes of the commit kernel over the positions,
+    # 32 KB of its LDS), ragged vocabulary, padded rows; two sequences with different masked counts
+    B, K, V, ld = 2, 4096, 523, 528
+    logits = wl.make_logits("bf16", B, K, V, 3.0, True, seed=11, ld=ld)
+    g = np.random.Generator(np.random.Philox(key=4096))
+    masked = (g.uniform(size=(B, K)) < np.array([[frac], [frac / 2]])).astype(np.uint8)
+    tokens = g.integers(0, V, size=(B, K)).astype(np.int32)
+    tokens[masked != 0] = wl.MASK_TOKEN
+    got = run_gpu(gpu_lib, logits, tokens, masked, 0.9, 0.3, V=V)
+    n_gap, n_band, skip, want = compare(got, logits, tokens, masked, 0.9, 0.3, V=V)
+    assert skip == 0 and want["n_committed"].min() >= 1
+
+
 def test_unmask_non_finite_logits_stay_in_bounds(gpu_lib):
     """NaN / inf logits are outside the method's domain (the oracle defines nothing for them); the
     kernel must still stay in bounds and keep its invariants: exactly the fallback's single commit per
