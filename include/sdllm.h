@@ -163,6 +163,9 @@ int sdllm_confidence_unmask(const sdllm_unmask_params* p,
  *   B, K (1..4096; B*K <= 65536), V >= 1, Hd = model width (multiple of 32)
  *   ld_h, ld_w  row strides of hidden / weight in elements (>= Hd, multiples of 8; B*K*ld_h < 2^31)
  *   tau0 ... tau_eos as in sdllm_unmask_params.  bf16 only.
+ *   weight_packed  0: weight is [V, ld_w] row-major.  1: weight is the image that
+ *                  sdllm_lm_head_pack_weight writes (ld_w is ignored).  W is a model weight: packed once,
+ *                  it lets every kernel read its matrix-core operands as contiguous kilobytes.
  * ------------------------------------------------------------------------------------- */
 typedef struct sdllm_lm_head_params {
   int32_t B, K, V, Hd;
@@ -171,7 +174,17 @@ typedef struct sdllm_lm_head_params {
   int32_t r_extra_masked, r_extra_total;
   int32_t eos_id;
   float tau_eos;
+  int32_t weight_packed;
 } sdllm_lm_head_params;
+
+/* The packed image of a projection matrix: [ceil(V/16)][Hd/32][64][8] bf16, where entry [nb][ks][lane][e]
+ * is W[min(16 nb + lane % 16, V - 1)][32 ks + 8 (lane / 16) + e] -- the A operand of one
+ * v_mfma_f32_16x16x32_bf16 for vocabulary rows 16 nb .. 16 nb + 15 and k-step ks, one kilobyte, lane by lane
+ * (rows past V repeat the last row; their logits are discarded).  Hd must be a multiple of 32, ld_w >= Hd a
+ * multiple of 8; weight and packed are device pointers, 16-byte aligned, and must not overlap.
+ * sdllm_lm_head_packed_weight_bytes returns the size of the image ((size_t)-1 for invalid V / Hd). */
+size_t sdllm_lm_head_packed_weight_bytes(int32_t V, int32_t Hd);
+int sdllm_lm_head_pack_weight(int32_t V, int32_t Hd, int64_t ld_w, const void* weight, void* packed, void* stream);
 
 size_t sdllm_lm_head_unmask_workspace_bytes(const sdllm_lm_head_params* p);
 

@@ -20,6 +20,7 @@ EXPORTED_SYMBOLS = (
     "sdllm_block_attention", "sdllm_attention_workspace_bytes", "sdllm_plan_attention",
     "sdllm_confidence_unmask", "sdllm_unmask_workspace_bytes",
     "sdllm_lm_head_unmask", "sdllm_lm_head_unmask_workspace_bytes", "sdllm_plan_lm_head",
+    "sdllm_lm_head_pack_weight", "sdllm_lm_head_packed_weight_bytes",
     "sdllm_kv_append", "sdllm_suffix_keep_indices", "sdllm_rope_gathered",
     "sdllm_probe_read", "sdllm_probe_copy", "sdllm_probe_mfma_bf16",
     "sdllm_status_string", "sdllm_last_error", "sdllm_version",
@@ -44,7 +45,7 @@ class LmHeadParams(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("K", ctypes.c_int32), ("V", ctypes.c_int32), ("Hd", ctypes.c_int32),
                 ("ld_h", ctypes.c_int64), ("ld_w", ctypes.c_int64), ("tau0", ctypes.c_float), ("alpha", ctypes.c_float),
                 ("r_extra_masked", ctypes.c_int32), ("r_extra_total", ctypes.c_int32),
-                ("eos_id", ctypes.c_int32), ("tau_eos", ctypes.c_float)]
+                ("eos_id", ctypes.c_int32), ("tau_eos", ctypes.c_float), ("weight_packed", ctypes.c_int32)]
 
 
 class LmHeadPlan(ctypes.Structure):
@@ -113,6 +114,10 @@ def load_library(path: Optional[str] = None):
     lib.sdllm_plan_lm_head.argtypes = [ctypes.POINTER(LmHeadParams), ctypes.POINTER(LmHeadPlan)]
     lib.sdllm_lm_head_unmask.restype = i32
     lib.sdllm_lm_head_unmask.argtypes = [ctypes.POINTER(LmHeadParams)] + [vp] * 8 + [vp, sz, vp]
+    lib.sdllm_lm_head_packed_weight_bytes.restype = sz
+    lib.sdllm_lm_head_packed_weight_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32]
+    lib.sdllm_lm_head_pack_weight.restype = i32
+    lib.sdllm_lm_head_pack_weight.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, vp, vp, vp]
     lib.sdllm_suffix_keep_indices.restype = i32
     lib.sdllm_suffix_keep_indices.argtypes = [ctypes.c_int32] * 4 + [ctypes.POINTER(ctypes.c_int32), ctypes.c_int32,
                                                                     ctypes.POINTER(ctypes.c_int32)]
@@ -286,9 +291,35 @@ def bind_confidence_unmask(logits, tokens, masked, tau0: float, alpha: float, V:
 
 # ---------------------------------------------------------------------------------------------
 def lm_head_params(B, K, V, Hd, ld_h, ld_w, tau0, alpha, r_extra_masked=0, r_extra_total=0, eos_id=-1,
-                   tau_eos=None) -> LmHeadParams:
+                   tau_eos=None, weight_packed=0) -> LmHeadParams:
     return LmHeadParams(B, K, V, Hd, ld_h, ld_w, tau0, alpha, r_extra_masked, r_extra_total, eos_id,
-                        tau0 if tau_eos is None else tau_eos)
+                        tau0 if tau_eos is None else tau_eos, weight_packed)
+
+
+class PackedLmWeight:
+    """The image sdllm_lm_head_pack_weight wrote for a projection matrix [V, Hd]: `data` is a flat bf16 device
+    tensor; pass the object as `weight` to lm_head_unmask / bind_lm_head_unmask."""
+
+    def __init__(self, data, V: int, Hd: int):
+        self.data, self.V, self.Hd = data, V, Hd
+
+
+def lm_head_packed_weight_bytes(V: int, Hd: int) -> int:
+    n = load_library().sdllm_lm_head_packed_weight_bytes(V, Hd)
+    if n == ctypes.c_size_t(-1).value:
+        raise SdllmError(ERR_INVALID_ARG, "lm_head_packed_weight_bytes: need V >= 1 and Hd a positive multiple of 32")
+    return n
+
+
+def lm_head_pack_weight(weight, stream=None) -> PackedLmWeight:
+    """sdllm_lm_head_pack_weight: weight bf16 [V, Hd] (row stride ld_w) -> PackedLmWeight (a new device tensor)."""
+    import torch
+    if weight.dtype != torch.bfloat16 or not weight.is_cuda or weight.dim() != 2 or weight.stride(1) != 1:
+        raise ValueError("lm_head_pack_weight: need a bfloat16 device tensor [V, Hd] with contiguous rows")
+    V, Hd = weight.shape
+    data = torch.empty((lm_head_packed_weight_bytes(V, Hd) // 2,), dtype=torch.bfloat16, device=weight.device)
+    _check(load_library().sdllm_lm_head_pack_weight(V, Hd, weight.stride(0), _ptr(weight), _ptr(data), _stream(stream)))
+    return PackedLmWeight(data, V, Hd)
 
 
 def lm_head_unmask_workspace_bytes(p: LmHeadParams) -> int:
@@ -305,7 +336,8 @@ def plan_lm_head(p: LmHeadParams) -> LmHeadPlan:
 
 
 def lm_head_unmask(*args, **kw):
-    """sdllm_lm_head_unmask.  hidden bf16 [B,K,Hd] (row stride ld_h), weight bf16 [V,Hd] (row stride ld_w);
+    """sdllm_lm_head_unmask.  hidden bf16 [B,K,Hd] (row stride ld_h), weight bf16 [V,Hd] (row stride ld_w) or
+    a PackedLmWeight;
     tokens int32 [B,K] and masked uint8 [B,K] are updated in place.  Returns (n_committed int32 [B],
     block_done uint8 [B]).  Signature: see bind_lm_head_unmask."""
     return bind_lm_head_unmask(*args, **kw)()
@@ -317,11 +349,17 @@ def bind_lm_head_unmask(hidden, weight, tokens, masked, tau0: float, alpha: floa
                         workspace=None, stream=None) -> BoundCall:
     import torch
     B, K, Hd = hidden.shape
-    V = weight.shape[0]
+    packed = isinstance(weight, PackedLmWeight)
+    if packed:
+        V, w_hd, ld_w, weight = weight.V, weight.Hd, weight.Hd, weight.data
+    else:
+        V, w_hd, ld_w = weight.shape[0], weight.shape[1], weight.stride(0)
+        if weight.stride(1) != 1:
+            raise ValueError("lm_head_unmask: weight [V,Hd] needs a contiguous last dimension")
     if hidden.dtype != torch.bfloat16 or weight.dtype != torch.bfloat16:
         raise TypeError("lm_head_unmask: hidden and weight must be bfloat16")
-    if weight.shape[1] != Hd or hidden.stride(2) != 1 or weight.stride(1) != 1 or hidden.stride(0) != K * hidden.stride(1):
-        raise ValueError("lm_head_unmask: need hidden [B,K,Hd] and weight [V,Hd] with contiguous last dimension")
+    if w_hd != Hd or hidden.stride(2) != 1 or hidden.stride(0) != K * hidden.stride(1):
+        raise ValueError("lm_head_unmask: need hidden [B,K,Hd] with contiguous last dimension and a weight of the same Hd")
     if not hidden.is_cuda or not weight.is_cuda:
         raise ValueError("lm_head_unmask: hidden and weight must be device tensors")
     _require(tokens, "tokens", torch.int32)
@@ -334,8 +372,8 @@ def bind_lm_head_unmask(hidden, weight, tokens, masked, tau0: float, alpha: floa
         block_done = torch.empty((B,), dtype=torch.uint8, device=hidden.device)
     _require(n_committed, "n_committed", torch.int32)
     _require(block_done, "block_done", torch.uint8)
-    p = lm_head_params(B, K, V, Hd, hidden.stride(1), weight.stride(0), tau0, alpha, r_extra_masked, r_extra_total,
-                       eos_id, tau_eos)
+    p = lm_head_params(B, K, V, Hd, hidden.stride(1), ld_w, tau0, alpha, r_extra_masked, r_extra_total,
+                       eos_id, tau_eos, 1 if packed else 0)
     need = lm_head_unmask_workspace_bytes(p)
     if workspace is None:
         workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=hidden.device)

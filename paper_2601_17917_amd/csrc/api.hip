@@ -75,10 +75,13 @@ int check_lm_head_params(const sdllm_lm_head_params* p) {
   if (p->K > 4096) return fail(SDLLM_ERR_UNSUPPORTED, "lm_head_unmask: K (%d) > 4096", p->K);
   if ((long long)p->B * p->K > 65536) return fail(SDLLM_ERR_UNSUPPORTED, "lm_head_unmask: B*K > 65536");
   if (p->Hd % 32 != 0) return fail(SDLLM_ERR_UNSUPPORTED, "lm_head_unmask: Hd (%d) must be a multiple of 32", p->Hd);
-  if (p->ld_h < p->Hd || p->ld_w < p->Hd)
+  if (p->weight_packed != 0 && p->weight_packed != 1)
+    return fail(SDLLM_ERR_INVALID_ARG, "lm_head_unmask: weight_packed must be 0 or 1");
+  const bool row_major = p->weight_packed == 0;      // ld_w is ignored for a packed weight
+  if (p->ld_h < p->Hd || (row_major && p->ld_w < p->Hd))
     return fail(SDLLM_ERR_INVALID_ARG, "lm_head_unmask: ld_h (%lld) and ld_w (%lld) must be >= Hd (%d)",
                 (long long)p->ld_h, (long long)p->ld_w, p->Hd);
-  if (p->ld_h % 8 != 0 || p->ld_w % 8 != 0)
+  if (p->ld_h % 8 != 0 || (row_major && p->ld_w % 8 != 0))
     return fail(SDLLM_ERR_INVALID_ARG, "lm_head_unmask: ld_h and ld_w must be multiples of 8 elements (16 bytes)");
   if ((long long)p->B * p->K * p->ld_h >= (1LL << 31))
     return fail(SDLLM_ERR_UNSUPPORTED, "lm_head_unmask: B*K*ld_h must be below 2^31");
@@ -242,6 +245,24 @@ int sdllm_confidence_unmask(const sdllm_unmask_params* p, const void* logits,
   hipError_t e = sdllm::launch_unmask(*p, logits, tokens, masked, confidence, n_committed, block_done, eos_seen,
                                       workspace, (hipStream_t)stream);
   if (e != hipSuccess) return fail(SDLLM_ERR_HIP, "unmask: %s", hipGetErrorString(e));
+  return SDLLM_OK;
+}
+
+size_t sdllm_lm_head_packed_weight_bytes(int32_t V, int32_t Hd) {
+  if (V < 1 || Hd < 32 || Hd % 32 != 0) return (size_t)-1;
+  return sdllm::lm_head_packed_weight_bytes(V, Hd);
+}
+
+int sdllm_lm_head_pack_weight(int32_t V, int32_t Hd, int64_t ld_w, const void* weight, void* packed, void* stream) {
+  if (V < 1 || Hd < 32 || Hd % 32 != 0)
+    return fail(SDLLM_ERR_INVALID_ARG, "lm_head_pack_weight: need V >= 1 and Hd a positive multiple of 32");
+  if (ld_w < Hd || ld_w % 8 != 0)
+    return fail(SDLLM_ERR_INVALID_ARG, "lm_head_pack_weight: ld_w (%lld) must be >= Hd (%d) and a multiple of 8", (long long)ld_w, Hd);
+  if (!weight || !packed) return fail(SDLLM_ERR_INVALID_ARG, "lm_head_pack_weight: weight and packed must not be NULL");
+  if (((uintptr_t)weight | (uintptr_t)packed) & 15)
+    return fail(SDLLM_ERR_INVALID_ARG, "lm_head_pack_weight: weight / packed is not 16-byte aligned");
+  hipError_t e = sdllm::launch_lm_head_pack_weight(V, Hd, ld_w, weight, packed, (hipStream_t)stream);
+  if (e != hipSuccess) return fail(SDLLM_ERR_HIP, "lm_head_pack_weight: %s", hipGetErrorString(e));
   return SDLLM_OK;
 }
 

@@ -48,6 +48,8 @@ hipError_t launch_unmask(const sdllm_unmask_params& p, const void* logits, int32
 // ---- vocabulary projection fused into the unmask ----
 void lm_head_plan(const sdllm_lm_head_params& p, sdllm_lm_head_plan* plan);
 size_t lm_head_workspace_bytes(const sdllm_lm_head_params& p);
+size_t lm_head_packed_weight_bytes(int V, int Hd);
+hipError_t launch_lm_head_pack_weight(int V, int Hd, long long ld_w, const void* weight, void* packed, hipStream_t stream);
 hipError_t launch_lm_head_unmask(const sdllm_lm_head_params& p, const void* hidden, const void* weight,
                                  int32_t* tokens, uint8_t* masked, float* confidence, int32_t* n_committed,
                                  uint8_t* block_done, uint8_t* eos_seen, void* workspace, hipStream_t stream);

@@ -38,7 +38,7 @@ constexpr int kLmStageBytes = 32768;      // one LDS stage of hidden rows
 
 struct LmHeadArgs {
   const uint16_t* hidden;     // [rows_total][ld_h]
-  const uint16_t* weight;     // [V][ld_w]
+  const uint16_t* weight;     // [V][ld_w], or the packed image [ceil(V/16)][Hd/32][64 lanes][8] (packed != 0)
   const uint8_t* masked;      // [rows_total]
   Partial* partials;          // [rows_total][ntile]
   long long ld_h, ld_w;       // elements
@@ -51,6 +51,8 @@ struct LmHeadArgs {
   // a position's triples are [ntile_out] (the largest tile count among the call's launches); the launch that
   // runs writes its ntile of them and neutral triples into the rest (slot tile + j ntile from workgroup tile)
   int ntile_out;
+  int packed;                 // weight is the packed image: the A operand of 16-row block nb and k-step ks is
+                              // the kilobyte at ((nb * Hd/32 + ks) * 64 + lane) * 8 elements
 };
 
 __device__ __forceinline__ void store_partial(const LmHeadArgs& a, int row, int tile, const Partial& p) {
@@ -176,11 +178,17 @@ __global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB, PF_>::MIN_WAVES)) voi
     return min(ch * S::KSTEPS + ss, NK - 1);
   };
   auto chunk_at = [&](int c) { int ch = c + c0; ch -= (ch >= NCH) ? NCH : 0; return ch; };   // c < NCH
-  const uint16_t* wrow[WNB];
+  const uint16_t* wrow[WNB];                                   // this lane's operand piece of k-step 0
+  const int wks = a.packed ? 512 : 32;                         // elements from one k-step's piece to the next
 #pragma unroll
   for (int ib = 0; ib < WNB; ++ib) {
-    const int n = min(tile * S::BN + (wave * WNB + ib) * 16 + l16, a.V - 1);   // rows past V: any valid row
-    wrow[ib] = a.weight + (long long)n * a.ld_w + 8 * q;
+    if (a.packed) {
+      const int nb = min(tile * (S::BN / 16) + wave * WNB + ib, (a.V + 15) / 16 - 1);   // blocks past V: the last one
+      wrow[ib] = a.weight + ((long long)nb * NK * 64 + lane) * 8;
+    } else {
+      const int n = min(tile * S::BN + (wave * WNB + ib) * 16 + l16, a.V - 1);   // rows past V: any valid row
+      wrow[ib] = a.weight + (long long)n * a.ld_w + 8 * q;
+    }
   }
   // staging: this thread moves piece `pc` of rows srow0 + ROWS_PER_PASS * i
   const int pc = tid % S::PIECES, srow0 = tid / S::PIECES;
@@ -206,7 +214,7 @@ __global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB, PF_>::MIN_WAVES)) voi
 #pragma unroll
   for (int s = 0; s < S::PF; ++s)
 #pragma unroll
-    for (int ib = 0; ib < WNB; ++ib) abuf[s][ib] = load_w(wrow[ib] + 32 * kstep_at(s));
+    for (int ib = 0; ib < WNB; ++ib) abuf[s][ib] = load_w(wrow[ib] + wks * kstep_at(s));
   // A chunk's pieces past Hd are staged as zeros and its k-steps past Hd are computed like the others
   // (finite W times zero adds nothing): the loop body has no branch, so the compiler's wait counters
   // see one straight line and keep the W loads PF steps ahead.
@@ -272,7 +280,7 @@ __global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB, PF_>::MIN_WAVES)) voi
 #pragma unroll
           for (int ib = 0; ib < WNB; ++ib) aop[ib] = abuf[slot_a][ib];
 #pragma unroll
-          for (int ib = 0; ib < WNB; ++ib) abuf[slot_a][ib] = load_w(wrow[ib] + 32 * kstep_at(g + S::PF));
+          for (int ib = 0; ib < WNB; ++ib) abuf[slot_a][ib] = load_w(wrow[ib] + wks * kstep_at(g + S::PF));
 #pragma unroll
           for (int jb = 0; jb < S::JB; ++jb) {
             const int t = ks * S::JB + jb, tn = t + S::DB;
@@ -318,7 +326,7 @@ __global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB, PF_>::MIN_WAVES)) voi
 #pragma unroll
         for (int ib = 0; ib < WNB; ++ib) aop[ib] = abuf[slot_a][ib];
 #pragma unroll
-        for (int ib = 0; ib < WNB; ++ib) abuf[slot_a][ib] = load_w(wrow[ib] + 32 * kstep_at(g + S::PF));
+        for (int ib = 0; ib < WNB; ++ib) abuf[slot_a][ib] = load_w(wrow[ib] + wks * kstep_at(g + S::PF));
 #pragma unroll
         for (int jb = 0; jb < S::JB; ++jb) {
           const bf16x8 bop = *reinterpret_cast<const bf16x8*>(
@@ -771,7 +779,9 @@ __device__ __forceinline__ void lm_dma16(unsigned lds_addr, const void* vaddr) {
                  :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(vaddr) : "memory", "m0");
 }
 
-template <int TT, int RB>
+// PACKED: W is the packed image; a transfer is then one operand tile (16 rows x one k-step, a contiguous
+// kilobyte), the ring holds the tiles as they are and an A operand is read lane by lane, without a swizzle.
+template <int TT, int RB, bool PACKED>
 __global__ __launch_bounds__(kLmThreads) void lm_head_dma_kernel(LmHeadArgs a) {
   static_assert(TT >= 1 && TT <= kDmTTMax && (RB == 1 || RB == 2), "shape");
   constexpr int ROWS = kLmWaves * RB * 16;                                   // positions per workgroup
@@ -824,25 +834,36 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_dma_kernel(LmHeadArgs a) {
 
   // W transfer j (0..3) of this wave fills rows 8 wave + 2 j + half of a sub-tile; LDS slot s of row r
   // holds piece s ^ (r & 15)
-  const unsigned char* wrow[kDmWT];                // row 8 wave + 2 j + half of the workgroup's first sub-tile
   unsigned wpiece[kDmWT];
 #pragma unroll
   for (int j = 0; j < kDmWT; ++j) {
     const int r = 8 * wave + 2 * j + half;
     wpiece[j] = (unsigned)(slot ^ (r & 15));
-    wrow[j] = nullptr;
   }
   const long long vrow0 = (long long)tile * (TT * kDmSub) + 8 * wave + half;
-  auto issue_w = [&](int u) {                      // step u of the walk (clamped to the last one) into stage u % 4
+  const int NKS = a.Hd / 32, NB = (a.V + 15) / 16;             // k-steps, 16-row blocks (packed image)
+  auto issue_w = [&](int u) {                      // step u of the walk (clamped to the last one) into stage u % 5
     const int uc = min(u, NU - 1);
     const int kc = uc / TT, t = uc - kc * TT;
-    const unsigned kb = (unsigned)(chunk_at(kc) * kDmKC);
     const unsigned st = lds0 + (unsigned)(u % kDmNST) * kDmStage + wave * (kDmWT * 1024);
+    if constexpr (PACKED) {
+      // transfer j of this wave is tile x = 4 wave + j of the 16 in a step: vocabulary block x / 8, k-step x % 8
+      const int ks0 = chunk_at(kc) * kDmKS;
 #pragma unroll
-    for (int j = 0; j < kDmWT; ++j) {
-      const long long n = min(vrow0 + t * kDmSub + 2 * j, (long long)a.V - 1);   // rows past V: any valid row
-      const unsigned k = min(kb + 8 * wpiece[j], klast);                          // pieces past Hd: any valid piece
-      lm_dma16<true>(st + j * 1024, a.weight + n * a.ld_w + k);
+      for (int j = 0; j < kDmWT; ++j) {
+        const int x = kDmWT * wave + j;
+        const int nb = min((tile * TT + t) * 2 + x / kDmKS, NB - 1);           // blocks past V: the last one
+        const int ks = min(ks0 + x % kDmKS, NKS - 1);                           // k-steps past Hd: the last one
+        lm_dma16<true>(st + j * 1024, a.weight + (((long long)nb * NKS + ks) * 64 + lane) * 8);
+      }
+    } else {
+      const unsigned kb = (unsigned)(chunk_at(kc) * kDmKC);
+#pragma unroll
+      for (int j = 0; j < kDmWT; ++j) {
+        const long long n = min(vrow0 + t * kDmSub + 2 * j, (long long)a.V - 1);   // rows past V: any valid row
+        const unsigned k = min(kb + 8 * wpiece[j], klast);                          // pieces past Hd: any valid piece
+        lm_dma16<true>(st + j * 1024, a.weight + n * a.ld_w + k);
+      }
     }
   };
   // hidden transfer j (0..BT-1) fills rows 2 j + half of this wave's region (row = rb * 16 + position in block)
@@ -909,9 +930,14 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_dma_kernel(LmHeadArgs a) {
       bf16x8 aop[kDmKS][2];
 #pragma unroll
       for (int ks = 0; ks < kDmKS; ++ks) {
-        const unsigned po = (unsigned)(l16 * (kDmKC * 2) + (((4 * ks + q) ^ l16) << 4));
-        aop[ks][0] = *reinterpret_cast<const bf16x8*>(cur + po);
-        aop[ks][1] = *reinterpret_cast<const bf16x8*>(cur + 16 * (kDmKC * 2) + po);
+        if constexpr (PACKED) {
+          aop[ks][0] = *reinterpret_cast<const bf16x8*>(cur + ks * 1024 + lane * 16);
+          aop[ks][1] = *reinterpret_cast<const bf16x8*>(cur + (kDmKS + ks) * 1024 + lane * 16);
+        } else {
+          const unsigned po = (unsigned)(l16 * (kDmKC * 2) + (((4 * ks + q) ^ l16) << 4));
+          aop[ks][0] = *reinterpret_cast<const bf16x8*>(cur + po);
+          aop[ks][1] = *reinterpret_cast<const bf16x8*>(cur + 16 * (kDmKC * 2) + po);
+        }
       }
       __builtin_amdgcn_sched_barrier(0);           // (the scheduler would sink the reads back between the MFMAs)
 #pragma unroll
@@ -971,9 +997,172 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_dma_kernel(LmHeadArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// The packed image of W: one wave per operand tile (16 vocabulary rows x one k-step = one kilobyte).
+__global__ __launch_bounds__(kLmThreads) void lm_head_pack_kernel(const uint16_t* __restrict__ W, long long ld_w,
+                                                                  int V, int NK, long long ntiles, u32x4* __restrict__ out) {
+  const int lane = threadIdx.x & 63;
+  const long long g = (long long)blockIdx.x * kLmWaves + (threadIdx.x >> 6);     // tile: block g / NK, k-step g % NK
+  if (g >= ntiles) return;
+  const long long nb = g / NK;
+  const int ks = (int)(g - nb * NK);
+  const long long row = min(nb * 16 + (lane & 15), (long long)V - 1);             // rows past V repeat the last row
+  out[g * 64 + lane] = *reinterpret_cast<const u32x4*>(W + row * ld_w + ks * 32 + 8 * (lane >> 4));
+}
+
+// Stream shape for at most 32 positions over a packed W.  Nothing is shared between the waves but the list of
+// masked rows: a wave owns TT 16-row vocabulary blocks and both row blocks of positions, loads its A operands
+// straight from the image (every load of a wave is one contiguous kilobyte, nontemporal, two k-steps ahead in
+// registers) and keeps the B operands of a chunk of 8 k-steps in registers, the next chunk's beside them.  No
+// LDS and no barrier in the loop; the compiler's wait counts see one straight line per chunk.
+constexpr int kPkKS = 8;                       // k-steps per chunk of B operands
+constexpr int kPkPF = 2;                       // k-steps of A operands in flight per wave
+constexpr int kPkTTMax = 10;
+
+template <int TT>
+__global__ __launch_bounds__(kLmThreads) void lm_head_packed_kernel(LmHeadArgs a) {
+  static_assert(TT >= 1 && TT <= kPkTTMax && kPkKS % kPkPF == 0, "shape");
+  __shared__ int row_of[32];                     // compacted row ids (-1 = none)
+  __shared__ Partial red[kLmWaves][32];
+  __shared__ int wsum[kLmWaves];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int tile = blockIdx.x;                   // < a.ntile by the grid size
+
+  {
+    const int total = lm_masked_count(a, wsum);
+    if (total < a.min_masked || total > a.max_masked) return;
+  }
+  int running = 0;
+  for (int base = 0; base < a.rows_total; base += kLmThreads) {
+    const int i = base + tid;
+    const bool f = i < a.rows_total && a.masked[i] != 0;
+    const unsigned long long bal = __ballot(f);
+    const int rank = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) wsum[wave] = __popcll(bal);
+    __syncthreads();
+    int pre = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kLmWaves; ++w) { const int c = wsum[w]; pre += (w < wave) ? c : 0; tot += c; }
+    const int ci = running + pre + rank;
+    if (f && ci < 32) row_of[ci] = i;
+    running += tot;
+    __syncthreads();
+  }
+  const int n_valid = min(running, 32);            // uniform
+  if (n_valid <= 0) return;
+  if (tid < 32 && tid >= n_valid) row_of[tid] = -1;
+  __syncthreads();
+
+  const int NK = a.Hd / 32;                        // k-steps
+  const int NCH = (NK + kPkKS - 1) / kPkKS;        // chunks
+  const int NB = (a.V + 15) / 16;                  // 16-row blocks of the image
+  const int q = lane >> 4, l16 = lane & 15;
+  const int c0 = tile % NCH;                       // this workgroup's rotation of the chunk order
+  auto chunk_at = [&](int c) { int ch = min(c, NCH - 1) + c0; return ch - ((ch >= NCH) ? NCH : 0); };
+  auto kstep_at = [&](int s) {                     // k-step at position s of the walk (past the end: the last position)
+    const int sc = min(s, NCH * kPkKS - 1);
+    const int cc = sc / kPkKS, ss = sc - cc * kPkKS;
+    return min(chunk_at(cc) * kPkKS + ss, NK - 1); // k-steps past Hd: the last one (its B operands are zeros)
+  };
+  // A operands: block nb0 + t of the image, this lane's 16 bytes of every k-step 512 elements apart
+  const int nb0 = (tile * kLmWaves + wave) * TT;
+  const uint16_t* wblk[TT];
+#pragma unroll
+  for (int t = 0; t < TT; ++t) wblk[t] = a.weight + ((long long)min(nb0 + t, NB - 1) * NK * 64 + lane) * 8;
+  auto load_a = [&](int s, bf16x8 (&dst)[TT]) {
+    const long long off = (long long)kstep_at(s) * 512;
+#pragma unroll
+    for (int t = 0; t < TT; ++t)
+      dst[t] = __builtin_bit_cast(bf16x8, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wblk[t] + off)));
+  };
+  // B operands: hidden row of position rb * 16 + l16, elements 8 q .. 8 q + 7 of every k-step of a chunk
+  const uint16_t* hrow[2];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) hrow[rb] = a.hidden + (long long)max(row_of[rb * 16 + l16], 0) * a.ld_h + 8 * q;
+  auto load_b = [&](int c, bf16x8 (&dst)[kPkKS][2]) {            // chunk at walk position c; zeros past Hd
+    const int k0 = chunk_at(c) * kPkKS;
+#pragma unroll
+    for (int ks = 0; ks < kPkKS; ++ks) {
+      const unsigned keep = (k0 + ks < NK) ? 0xffffffffu : 0u;
+      const int kk = min(k0 + ks, NK - 1);
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(hrow[rb] + 32 * kk);
+        dst[ks][rb] = __builtin_bit_cast(bf16x8, v & u32x4{keep, keep, keep, keep});
+      }
+    }
+  };
+
+  f32x4 acc[TT][2];
+#pragma unroll
+  for (int t = 0; t < TT; ++t) { acc[t][0] = f32x4{0.f, 0.f, 0.f, 0.f}; acc[t][1] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+  bf16x8 abuf[kPkPF][TT];
+  bf16x8 bcur[kPkKS][2], bnext[kPkKS][2];
+  load_b(0, bcur);
+#pragma unroll
+  for (int s = 0; s < kPkPF; ++s) load_a(s, abuf[s]);
+
+  for (int kc = 0; kc < NCH; ++kc) {
+    load_b(kc + 1, bnext);                         // older than every A load below: it is back before they are
+#pragma unroll
+    for (int ks = 0; ks < kPkKS; ++ks) {
+      bf16x8 acur[TT];
+#pragma unroll
+      for (int t = 0; t < TT; ++t) acur[t] = abuf[ks % kPkPF][t];
+      load_a(kc * kPkKS + ks + kPkPF, abuf[ks % kPkPF]);
+#pragma unroll
+      for (int t = 0; t < TT; ++t) {
+        acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(acur[t], bcur[ks][0], acc[t][0], 0, 0, 0);
+        acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(acur[t], bcur[ks][1], acc[t][1], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int ks = 0; ks < kPkKS; ++ks) { bcur[ks][0] = bnext[ks][0]; bcur[ks][1] = bnext[ks][1]; }
+  }
+
+  // ---- row reduction: this lane holds, for position rb * 16 + l16, the ids (nb0 + t) * 16 + 4 q + r
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+    float m = kNegBig; int idx = 0x7fffffff;
+#pragma unroll
+    for (int t = 0; t < TT; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int n = (nb0 + t) * 16 + 4 * q + r;
+        float v = acc[t][rb][r];
+        if (n >= a.V) v = -INFINITY;
+        acc[t][rb][r] = v;
+        if (v > m) { m = v; idx = n; }               // ascending ids, strict: the lowest id keeps a tie
+      }
+    const float ml = m * kLog2e;
+    float s = 0.f;
+#pragma unroll
+    for (int t = 0; t < TT; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) s += fast_exp2(fmaf(acc[t][rb][r], kLog2e, -ml));
+#pragma unroll
+    for (int off = 16; off <= 32; off <<= 1) {
+      const float m2 = __shfl_xor(m, off); const float s2 = __shfl_xor(s, off); const int i2 = __shfl_xor(idx, off);
+      merge_partial(m, s, idx, m2, s2, i2);
+    }
+    if (q == 0) red[wave][rb * 16 + l16] = Partial{m, s, idx};
+  }
+  __syncthreads();
+  if (tid < 32 && row_of[tid] >= 0) {
+    Partial p = red[0][tid];                         // waves hold ascending vocabulary ranges
+#pragma unroll
+    for (int w = 1; w < kLmWaves; ++w) merge_partial(p.m, p.s, p.idx, red[w][tid].m, red[w][tid].s, red[w][tid].idx);
+    store_partial(a, row_of[tid], tile, p);
+  }
+}
+
 // ---- host side ----
-// The kernel shapes, by the masked counts they serve: up to 32 (stream, B operands in registers), up to 64
-// (stream, hidden chunk in LDS), up to 128 (stream, global -> LDS transfers), any (256-row chunks).
+// The kernel shapes, by the masked counts they serve.  Row-major W: up to 32 (stream, B operands in
+// registers), up to 64 (stream, hidden chunk in LDS), up to 128 (stream, global -> LDS transfers), any (256-row
+// chunks).  Packed W: up to 32 (operands straight from the image), up to 64 and up to 128 (global -> LDS
+// transfers of operand tiles), any (256-row chunks).
 enum { kShape32 = 0, kShape64, kShape128, kShapeRows, kNumShapes };
 constexpr int kShapeMax[kNumShapes] = {32, kSt2Rows, 128, INT_MAX};
 
@@ -984,11 +1173,13 @@ constexpr int kShapeMax[kNumShapes] = {32, kSt2Rows, 128, INT_MAX};
 constexpr int kStTTs[] = {2, 4, 8, 12, 16, 20};
 constexpr int kSt2TTs[] = {2, 4, 8, 10, 12, 16};
 constexpr int kDmTTs[] = {1, 2, 3, 4, 6, 8, 10, 16};
+constexpr int kPkTTs[] = {1, 2, 4, 6, 8, 10};      // 16-row blocks per wave: 64 rows per workgroup each
+constexpr int kPkSub = kLmWaves * 16;
 static_assert(kStSub == kDmSub, "one sub-tile size for the tile-size choice");
 
 template <size_t N>
-static int stream_tt(int V, const int (&tts)[N]) {
-  const int nsub = (V + kStSub - 1) / kStSub;
+static int stream_tt(int V, const int (&tts)[N], int sub = kStSub) {
+  const int nsub = (V + sub - 1) / sub;
   int best = tts[0];
   long long best_cost = LLONG_MAX;
   for (int tt : tts) {
@@ -1001,20 +1192,27 @@ static int stream_tt(int V, const int (&tts)[N]) {
 
 // top: the shape for B x K positions all masked; the shapes below it are launched too and serve the smaller
 // masked counts; ntile_out is the largest tile count among the launched shapes.
-struct LmPlan { int top, nchunk, tt[kNumShapes], bn[kNumShapes], ntile[kNumShapes], ntile_out; };
+struct LmPlan { int top, nchunk, packed, tt[kNumShapes], bn[kNumShapes], ntile[kNumShapes], ntile_out; };
 
 static LmPlan lm_plan(const sdllm_lm_head_params& p) {
   const long long rows = (long long)p.B * p.K;
   LmPlan pl;
-  pl.tt[kShape32] = stream_tt(p.V, kStTTs);
-  pl.tt[kShape64] = stream_tt(p.V, kSt2TTs);
+  pl.packed = p.weight_packed;
+  int sub[kNumShapes] = {kStSub, kStSub, kStSub, 256};
+  if (pl.packed) {
+    pl.tt[kShape32] = stream_tt(p.V, kPkTTs, kPkSub); sub[kShape32] = kPkSub;
+    pl.tt[kShape64] = stream_tt(p.V, kDmTTs);
+  } else {
+    pl.tt[kShape32] = stream_tt(p.V, kStTTs);
+    pl.tt[kShape64] = stream_tt(p.V, kSt2TTs);
+  }
   pl.tt[kShape128] = stream_tt(p.V, kDmTTs);
-  pl.tt[kShapeRows] = 256 / kStSub;       // 256-row tiles (also for a half-empty chunk: it beat 128-row tiles)
+  pl.tt[kShapeRows] = 1;                  // 256-row tiles (also for a half-empty chunk: it beat 128-row tiles)
   pl.top = 0;
   while (rows > kShapeMax[pl.top]) ++pl.top;
   pl.ntile_out = 0;
   for (int i = 0; i < kNumShapes; ++i) {
-    pl.bn[i] = pl.tt[i] * kStSub;
+    pl.bn[i] = pl.tt[i] * sub[i];
     pl.ntile[i] = (p.V + pl.bn[i] - 1) / pl.bn[i];
     if (i <= pl.top) pl.ntile_out = std::max(pl.ntile_out, pl.ntile[i]);
   }
@@ -1022,11 +1220,16 @@ static LmPlan lm_plan(const sdllm_lm_head_params& p) {
   return pl;
 }
 
-static size_t lm_lds_bytes(int shape) {
+constexpr size_t dma_lds_bytes(int rb) {
+  return (size_t)kDmNST * kDmStage + (size_t)kLmWaves * (rb * 16 * kDmKC * 2) + (size_t)kLmWaves * rb * 16 * sizeof(int);
+}
+
+static size_t lm_lds_bytes(int shape, int packed) {
   switch (shape) {
-    case kShape32: return 2 * (size_t)kStStage + 32 * sizeof(int) + (size_t)kLmWaves * 16 * sizeof(Partial);
-    case kShape64: return 2 * (size_t)kStStage + kSt2Hid + kSt2Rows * sizeof(int) + (size_t)kLmWaves * 32 * sizeof(Partial);
-    case kShape128: return (size_t)kDmNST * kDmStage + (size_t)kLmWaves * (2 * 16 * kDmKC * 2) + 128 * sizeof(int);
+    case kShape32: return packed ? 0 : 2 * (size_t)kStStage + 32 * sizeof(int) + (size_t)kLmWaves * 16 * sizeof(Partial);
+    case kShape64: return packed ? dma_lds_bytes(1)
+                                 : 2 * (size_t)kStStage + kSt2Hid + kSt2Rows * sizeof(int) + (size_t)kLmWaves * 32 * sizeof(Partial);
+    case kShape128: return dma_lds_bytes(2);
     default: return (size_t)3 * kLmStageBytes + 256 * sizeof(int) + (size_t)kLmWaves * 256 * sizeof(Partial);   // LmShape::NST
   }
 }
@@ -1038,7 +1241,7 @@ void lm_head_plan(const sdllm_lm_head_params& p, sdllm_lm_head_plan* plan) {
   plan->vocab_rows_per_tile = pl.bn[t]; plan->vocab_tiles = pl.ntile[t];
   plan->row_chunks = pl.nchunk;
   plan->workgroups = t != kShapeRows ? pl.ntile[t] : ((pl.ntile[t] + kNumXCDs - 1) / kNumXCDs) * pl.nchunk * kNumXCDs;
-  plan->lds_bytes = (int32_t)lm_lds_bytes(t);
+  plan->lds_bytes = (int32_t)lm_lds_bytes(t, pl.packed);
   plan->triples_per_position = pl.ntile_out;
 }
 
@@ -1046,10 +1249,23 @@ size_t lm_head_workspace_bytes(const sdllm_lm_head_params& p) {
   return (size_t)p.B * p.K * lm_plan(p).ntile_out * sizeof(Partial);
 }
 
+size_t lm_head_packed_weight_bytes(int V, int Hd) {
+  return (size_t)((V + 15) / 16) * (size_t)(Hd / 32) * 1024;
+}
+
+hipError_t launch_lm_head_pack_weight(int V, int Hd, long long ld_w, const void* weight, void* packed, hipStream_t stream) {
+  const int NK = Hd / 32;
+  const long long ntiles = (long long)((V + 15) / 16) * NK;
+  const long long grid = (ntiles + kLmWaves - 1) / kLmWaves;
+  if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(lm_head_pack_kernel, dim3((unsigned)grid), dim3(kLmThreads), 0, stream,
+                     (const uint16_t*)weight, ld_w, V, NK, ntiles, (u32x4*)packed);
+  return hipGetLastError();
+}
+
 // one launch; the kernel's opt-in to more than 64 KiB of dynamic LDS is set once
-static hipError_t launch_kernel(void (*kernel)(LmHeadArgs), bool& attr_set, int shape, unsigned grid,
+static hipError_t launch_kernel(void (*kernel)(LmHeadArgs), bool& attr_set, size_t lds, unsigned grid,
                                 const LmHeadArgs& r, hipStream_t stream) {
-  const size_t lds = lm_lds_bytes(shape);
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -1063,53 +1279,76 @@ static hipError_t launch_kernel(void (*kernel)(LmHeadArgs), bool& attr_set, int 
 template <int TT>
 static hipError_t launch_stream32(const LmHeadArgs& r, hipStream_t stream) {
   static bool attr_set = false;
-  return launch_kernel(lm_head_stream_kernel<TT>, attr_set, kShape32, (unsigned)r.ntile, r, stream);
+  return launch_kernel(lm_head_stream_kernel<TT>, attr_set, lm_lds_bytes(kShape32, 0), (unsigned)r.ntile, r, stream);
 }
 template <int TT>
 static hipError_t launch_stream64(const LmHeadArgs& r, hipStream_t stream) {
   static bool attr_set = false;
-  return launch_kernel(lm_head_stream64_kernel<TT>, attr_set, kShape64, (unsigned)r.ntile, r, stream);
+  return launch_kernel(lm_head_stream64_kernel<TT>, attr_set, lm_lds_bytes(kShape64, 0), (unsigned)r.ntile, r, stream);
 }
 template <int TT>
-static hipError_t launch_stream128(const LmHeadArgs& r, hipStream_t stream) {
+static hipError_t launch_packed32(const LmHeadArgs& r, hipStream_t stream) {
   static bool attr_set = false;
-  return launch_kernel(lm_head_dma_kernel<TT, 2>, attr_set, kShape128, (unsigned)r.ntile, r, stream);
+  return launch_kernel(lm_head_packed_kernel<TT>, attr_set, 0, (unsigned)r.ntile, r, stream);
+}
+template <int TT, int RB, bool PACKED>
+static hipError_t launch_dma(const LmHeadArgs& r, hipStream_t stream) {
+  static bool attr_set = false;
+  return launch_kernel(lm_head_dma_kernel<TT, RB, PACKED>, attr_set, dma_lds_bytes(RB), (unsigned)r.ntile, r, stream);
+}
+template <int RB, bool PACKED>
+static hipError_t launch_dma_tt(int tt, const LmHeadArgs& r, hipStream_t stream) {
+  switch (tt) {                        // kDmTTs
+    case 1: return launch_dma<1, RB, PACKED>(r, stream);
+    case 2: return launch_dma<2, RB, PACKED>(r, stream);
+    case 3: return launch_dma<3, RB, PACKED>(r, stream);
+    case 4: return launch_dma<4, RB, PACKED>(r, stream);
+    case 6: return launch_dma<6, RB, PACKED>(r, stream);
+    case 8: return launch_dma<8, RB, PACKED>(r, stream);
+    case 10: return launch_dma<10, RB, PACKED>(r, stream);
+    case 16: return launch_dma<16, RB, PACKED>(r, stream);
+  }
+  return hipErrorInvalidValue;
 }
 static hipError_t launch_rows(const LmHeadArgs& r, hipStream_t stream) {
   static_assert(LmShape<256, 4, 4>::NST == 3 && LmShape<256, 4, 4>::BN == 256, "lm_lds_bytes, lm_plan");
   static bool attr_set = false;
   const unsigned grid = (unsigned)(((r.ntile + kNumXCDs - 1) / kNumXCDs) * r.nchunk * kNumXCDs);
-  return launch_kernel(lm_head_rows_kernel<256, 4, 4>, attr_set, kShapeRows, grid, r, stream);
+  return launch_kernel(lm_head_rows_kernel<256, 4, 4>, attr_set, lm_lds_bytes(kShapeRows, 0), grid, r, stream);
 }
 
 static hipError_t launch_shape(int shape, int tt, const LmHeadArgs& r, hipStream_t stream) {
   switch (shape) {
-    case kShape32: switch (tt) {       // kStTTs
-      case 2: return launch_stream32<2>(r, stream);
-      case 4: return launch_stream32<4>(r, stream);
-      case 8: return launch_stream32<8>(r, stream);
-      case 12: return launch_stream32<12>(r, stream);
-      case 16: return launch_stream32<16>(r, stream);
-      case 20: return launch_stream32<20>(r, stream);
-    } break;
-    case kShape64: switch (tt) {       // kSt2TTs
-      case 2: return launch_stream64<2>(r, stream);
-      case 4: return launch_stream64<4>(r, stream);
-      case 8: return launch_stream64<8>(r, stream);
-      case 10: return launch_stream64<10>(r, stream);
-      case 12: return launch_stream64<12>(r, stream);
-      case 16: return launch_stream64<16>(r, stream);
-    } break;
-    case kShape128: switch (tt) {      // kDmTTs
-      case 1: return launch_stream128<1>(r, stream);
-      case 2: return launch_stream128<2>(r, stream);
-      case 3: return launch_stream128<3>(r, stream);
-      case 4: return launch_stream128<4>(r, stream);
-      case 6: return launch_stream128<6>(r, stream);
-      case 8: return launch_stream128<8>(r, stream);
-      case 10: return launch_stream128<10>(r, stream);
-      case 16: return launch_stream128<16>(r, stream);
-    } break;
+    case kShape32:
+      if (r.packed) switch (tt) {      // kPkTTs
+        case 1: return launch_packed32<1>(r, stream);
+        case 2: return launch_packed32<2>(r, stream);
+        case 4: return launch_packed32<4>(r, stream);
+        case 6: return launch_packed32<6>(r, stream);
+        case 8: return launch_packed32<8>(r, stream);
+        case 10: return launch_packed32<10>(r, stream);
+      } else switch (tt) {             // kStTTs
+        case 2: return launch_stream32<2>(r, stream);
+        case 4: return launch_stream32<4>(r, stream);
+        case 8: return launch_stream32<8>(r, stream);
+        case 12: return launch_stream32<12>(r, stream);
+        case 16: return launch_stream32<16>(r, stream);
+        case 20: return launch_stream32<20>(r, stream);
+      }
+      break;
+    case kShape64:
+      if (r.packed) return launch_dma_tt<1, true>(tt, r, stream);
+      switch (tt) {                    // kSt2TTs
+        case 2: return launch_stream64<2>(r, stream);
+        case 4: return launch_stream64<4>(r, stream);
+        case 8: return launch_stream64<8>(r, stream);
+        case 10: return launch_stream64<10>(r, stream);
+        case 12: return launch_stream64<12>(r, stream);
+        case 16: return launch_stream64<16>(r, stream);
+      }
+      break;
+    case kShape128:
+      return r.packed ? launch_dma_tt<2, true>(tt, r, stream) : launch_dma_tt<2, false>(tt, r, stream);
     case kShapeRows: return launch_rows(r, stream);
   }
   return hipErrorInvalidValue;      // not reached: lm_plan picks from the same lists
@@ -1124,7 +1363,7 @@ hipError_t launch_lm_head_unmask(const sdllm_lm_head_params& p, const void* hidd
   r.partials = (Partial*)workspace;
   r.ld_h = p.ld_h; r.ld_w = p.ld_w;
   r.rows_total = p.B * p.K; r.V = p.V; r.Hd = p.Hd;
-  r.nchunk = pl.nchunk; r.ntile_out = pl.ntile_out;
+  r.nchunk = pl.nchunk; r.ntile_out = pl.ntile_out; r.packed = pl.packed;
   hipError_t e = hipSuccess;
   // every shape up to the one that B x K needs: the smaller ones take the call when few enough positions are
   // still masked (the later steps of a block); each launch exits unless the masked count is in its range

@@ -37,7 +37,7 @@ def test_struct_layouts_match_header():
     assert sd.AppendParams.cache_layer_stride.offset == 32
     assert ctypes.sizeof(sd.AttnPlan) == 16
     assert ctypes.sizeof(sd.LmHeadPlan) == 28
-    assert ctypes.sizeof(sd.LmHeadParams) == 56
+    assert ctypes.sizeof(sd.LmHeadParams) == 64
     assert sd.LmHeadParams.ld_h.offset == 16 and sd.LmHeadParams.tau0.offset == 32
 
 
@@ -272,4 +272,43 @@ def test_lm_head_plan_is_consistent(lib, B, K, V, Hd):
         assert pl.workgroups < pl.vocab_tiles * pl.row_chunks + 8 * pl.row_chunks
     assert pl.triples_per_position >= pl.vocab_tiles
     assert 64 * 1024 <= pl.lds_bytes <= 160 * 1024
+    assert sd.lm_head_unmask_workspace_bytes(p) == rows * pl.triples_per_position * 12
+
+
+def test_lm_head_packed_weight_host_side(lib):
+    # size of the packed image: whole 16-row blocks x whole k-steps of one kilobyte each
+    assert sd.lm_head_packed_weight_bytes(126464, 4096) == (126464 // 16) * (4096 // 32) * 1024
+    assert sd.lm_head_packed_weight_bytes(17, 64) == 2 * 2 * 1024
+    big = ctypes.c_size_t(-1).value
+    assert lib.sdllm_lm_head_packed_weight_bytes(0, 64) == big and lib.sdllm_lm_head_packed_weight_bytes(5, 48) == big
+    vp = ctypes.c_void_p
+    assert lib.sdllm_lm_head_pack_weight(0, 64, 64, vp(4096), vp(8192), None) == sd.ERR_INVALID_ARG
+    assert lib.sdllm_lm_head_pack_weight(10, 48, 64, vp(4096), vp(8192), None) == sd.ERR_INVALID_ARG
+    assert lib.sdllm_lm_head_pack_weight(10, 64, 60, vp(4096), vp(8192), None) == sd.ERR_INVALID_ARG
+    assert lib.sdllm_lm_head_pack_weight(10, 64, 64, None, vp(8192), None) == sd.ERR_INVALID_ARG
+    assert lib.sdllm_lm_head_pack_weight(10, 64, 64, vp(4100), vp(8192), None) == sd.ERR_INVALID_ARG
+    # the layout flag: only 0 and 1; a packed weight needs no row stride
+    p = sd.lm_head_params(2, 32, 1000, 64, 64, 64, 0.9, 0.3, weight_packed=2)
+    assert lib.sdllm_plan_lm_head(ctypes.byref(p), ctypes.byref(sd.LmHeadPlan())) == sd.ERR_INVALID_ARG
+    p = sd.lm_head_params(2, 32, 1000, 64, 64, 0, 0.9, 0.3, weight_packed=1)
+    assert lib.sdllm_plan_lm_head(ctypes.byref(p), ctypes.byref(sd.LmHeadPlan())) == 0
+    p = sd.lm_head_params(2, 32, 1000, 64, 64, 0, 0.9, 0.3, weight_packed=0)
+    assert lib.sdllm_plan_lm_head(ctypes.byref(p), ctypes.byref(sd.LmHeadPlan())) == sd.ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("B,K,V", [(1, 32, 126464), (1, 32, 152064), (2, 32, 126464), (4, 32, 152064), (1, 8, 100),
+                                   (3, 32, 5000), (9, 32, 700)])
+def test_lm_head_plan_for_a_packed_weight(lib, B, K, V):
+    p = sd.lm_head_params(B, K, V, 256, 256, 0, 0.9, 0.3, weight_packed=1)
+    pl = sd.plan_lm_head(p)
+    rows = B * K
+    assert pl.vocab_tiles * pl.vocab_rows_per_tile >= V > (pl.vocab_tiles - 1) * pl.vocab_rows_per_tile
+    if rows <= 32:
+        assert pl.vocab_rows_per_tile // 64 in (1, 2, 4, 6, 8, 10) and pl.lds_bytes == 0   # operands straight from the image
+        assert pl.vocab_rows_per_tile == {126464: 512, 152064: 640}.get(V, pl.vocab_rows_per_tile)
+    elif rows <= 128:
+        assert pl.vocab_rows_per_tile // 32 in (1, 2, 3, 4, 6, 8, 10, 16) and 64 * 1024 <= pl.lds_bytes <= 160 * 1024
+    else:
+        assert pl.vocab_rows_per_tile == 256
+    assert pl.triples_per_position >= pl.vocab_tiles
     assert sd.lm_head_unmask_workspace_bytes(p) == rows * pl.triples_per_position * 12

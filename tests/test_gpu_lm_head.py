@@ -21,8 +21,12 @@ pytestmark = pytest.mark.gpu
 CONF_RTOL = 2e-4
 
 
-def run_gpu(sd, hidden, weight, tokens, masked, tau0, alpha, eos_id=-1, tau_eos=None, eos_seen=None, extra=(0, 0)):
-    """hidden / weight: device bf16 tensors (possibly strided views)."""
+def run_gpu(sd, hidden, weight, tokens, masked, tau0, alpha, eos_id=-1, tau_eos=None, eos_seen=None, extra=(0, 0),
+            packed=False):
+    """hidden / weight: device bf16 tensors (possibly strided views); packed: the projection goes through
+    sdllm_lm_head_pack_weight first and the call reads the packed image."""
+    if packed:
+        weight = sd.lm_head_pack_weight(weight)
     tk = torch.from_numpy(tokens.astype(np.int32)).cuda()
     mk = torch.from_numpy(masked.astype(np.uint8)).cuda()
     B, K = tokens.shape
@@ -120,9 +124,10 @@ def _oracle(h, W, tokens, masked, tau0, alpha, **kw):
     (4, 600, 64, 300),        # 2400 positions: ten passes of the mask scan, ten row chunks, two triples per position
     (2, 600, 64, 20000),      # 79 triples per position and more positions than the commit kernel has lanes to spare
 ])
-def test_lm_head_shapes(gpu_lib, B, K, Hd, V):
+@pytest.mark.parametrize("packed", [False, True])
+def test_lm_head_shapes(gpu_lib, B, K, Hd, V, packed):
     h, W, tokens, masked, hd, Wd = _host_case(B, K, Hd, V, seed=B * 1000 + K + Hd + V)
-    got = run_gpu(gpu_lib, hd, Wd, tokens, masked, 0.7, 0.3)
+    got = run_gpu(gpu_lib, hd, Wd, tokens, masked, 0.7, 0.3, packed=packed)
     want = _oracle(h, W, tokens, masked, 0.7, 0.3)
     n_gap, n_band, skipped = compare(got, want, tokens, masked)
     print(f"B{B} K{K} Hd{Hd} V{V}: gap<1e-3={n_gap} in-band={n_band} skipped_seqs={skipped} "
@@ -130,7 +135,7 @@ def test_lm_head_shapes(gpu_lib, B, K, Hd, V):
     assert skipped <= 1
 
 
-_TILE_CASES = [3000, 12000, 20000, 30000, 45000, 50000, 60000, 80000, 90000, 126464, 152064]
+_TILE_CASES = [3000, 12000, 20000, 30000, 45000, 50000, 60000, 80000, 90000, 100000, 126464, 152064]
 
 
 def test_tile_cases_cover_every_compiled_stream_kernel(gpu_lib):
@@ -141,16 +146,20 @@ def test_tile_cases_cover_every_compiled_stream_kernel(gpu_lib):
     seen128 = {gpu_lib.plan_lm_head(gpu_lib.lm_head_params(4, 32, V, 64, 64, 64, 0.9, 0.3)).vocab_rows_per_tile // 32
                for V in _TILE_CASES}
     assert seen32 == {2, 4, 8, 12, 16, 20} and seen64 == {2, 4, 8, 10, 12, 16} and seen128 == {1, 2, 3, 4, 6, 8, 10, 16}
+    packed = lambda B, V: gpu_lib.plan_lm_head(gpu_lib.lm_head_params(B, 32, V, 64, 64, 0, 0.9, 0.3, weight_packed=1))
+    assert {packed(1, V).vocab_rows_per_tile // 64 for V in _TILE_CASES} == {1, 2, 4, 6, 8, 10}
+    assert {packed(2, V).vocab_rows_per_tile // 32 for V in _TILE_CASES} == {1, 2, 3, 4, 6, 8, 10, 16}
 
 
 @pytest.mark.parametrize("V", _TILE_CASES)
 @pytest.mark.parametrize("B", [1, 2, 4])
-def test_lm_head_every_vocabulary_tile_size(gpu_lib, B, V):
+@pytest.mark.parametrize("packed", [False, True])
+def test_lm_head_every_vocabulary_tile_size(gpu_lib, B, V, packed):
     # the stream kernels are compiled for a list of tile sizes and the vocabulary size picks one: every one of
     # them runs here (narrow hidden width, so that the oracle stays cheap), about 24, 48 and 96 masked positions
     K, Hd = 32, 64
     h, W, tokens, masked, hd, Wd = _host_case(B, K, Hd, V, seed=V + B, frac=0.75, std=1.0)
-    got = run_gpu(gpu_lib, hd, Wd, tokens, masked, 0.3, 0.3)
+    got = run_gpu(gpu_lib, hd, Wd, tokens, masked, 0.3, 0.3, packed=packed)
     want = _oracle(h, W, tokens, masked, 0.3, 0.3)
     n_gap, n_band, skipped = compare(got, want, tokens, masked)
     assert skipped <= 1 and n_gap <= masked.sum() // 2      # most positions have a clear arg-max to compare
@@ -158,7 +167,8 @@ def test_lm_head_every_vocabulary_tile_size(gpu_lib, B, V):
 
 @pytest.mark.parametrize("B,K", [(2, 32), (4, 32), (5, 32), (9, 64)])
 @pytest.mark.parametrize("n_masked", [1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 160])
-def test_lm_head_shape_follows_the_masked_count(gpu_lib, B, K, n_masked):
+@pytest.mark.parametrize("packed", [False, True])
+def test_lm_head_shape_follows_the_masked_count(gpu_lib, B, K, n_masked, packed):
     # the masked count is device data: every shape that B x K admits is launched and the one whose range holds
     # the count does the work; counts on both sides of each boundary, spread over the sequences, with V chosen so
     # that the narrower tiles of the wide shape leave an odd number of triple slots per position
@@ -171,7 +181,7 @@ def test_lm_head_shape_follows_the_masked_count(gpu_lib, B, K, n_masked):
     masked.reshape(-1)[flat] = 1
     tokens.reshape(-1)[flat] = wl.MASK_TOKEN
     assert int(masked.sum()) == n_masked
-    got = run_gpu(gpu_lib, hd, Wd, tokens, masked, 0.7, 0.3)
+    got = run_gpu(gpu_lib, hd, Wd, tokens, masked, 0.7, 0.3, packed=packed)
     want = _oracle(h, W, tokens, masked, 0.7, 0.3)
     n_gap, n_band, skipped = compare(got, want, tokens, masked)
     assert skipped <= 1
@@ -180,9 +190,10 @@ def test_lm_head_shape_follows_the_masked_count(gpu_lib, B, K, n_masked):
 @pytest.mark.parametrize("B,K,Hd,V,ld_h,ld_w", [(2, 16, 64, 200, 72, 80), (2, 32, 320, 1000, 328, 384),
                                                  (4, 32, 320, 1000, 328, 384),
                                                  (3, 32, 320, 1000, 328, 384)])
-def test_lm_head_row_strides_and_poisoned_padding(gpu_lib, B, K, Hd, V, ld_h, ld_w):
+@pytest.mark.parametrize("packed", [False, True])
+def test_lm_head_row_strides_and_poisoned_padding(gpu_lib, B, K, Hd, V, ld_h, ld_w, packed):
     h, W, tokens, masked, hd, Wd = _host_case(B, K, Hd, V, seed=77, ld_h=ld_h, ld_w=ld_w)
-    got = run_gpu(gpu_lib, hd, Wd, tokens, masked, 0.6, 0.2)
+    got = run_gpu(gpu_lib, hd, Wd, tokens, masked, 0.6, 0.2, packed=packed)
     assert np.isfinite(got["confidence"]).all()
     compare(got, _oracle(h, W, tokens, masked, 0.6, 0.2), tokens, masked)
 
@@ -248,12 +259,28 @@ def test_lm_head_most_positions(gpu_lib, n_masked):
     assert skipped <= 2
 
 
-def _full_size(gpu_lib, name, seqs=None, B=None):
+@pytest.mark.parametrize("V,Hd,ld_w", [(1, 32, 32), (16, 64, 64), (17, 96, 104), (1000, 544, 552), (5003, 4096, 4096)])
+def test_pack_weight_is_the_stated_permutation(gpu_lib, V, Hd, ld_w):
+    # image[nb][ks][lane][e] = W[min(16 nb + lane % 16, V - 1)][32 ks + 8 (lane / 16) + e], bit for bit
+    g = np.random.Generator(np.random.Philox(key=V * 7 + Hd))
+    Wp = g.integers(0, 1 << 16, size=(V, ld_w), dtype=np.uint16)
+    Wd = to_dev(Wp)[:, :Hd]
+    packed = gpu_lib.lm_head_pack_weight(Wd)
+    torch.cuda.synchronize()
+    got = packed.data.view(torch.int16).cpu().numpy().view(np.uint16)
+    NB, NK = (V + 15) // 16, Hd // 32
+    assert packed.V == V and packed.Hd == Hd and got.shape == (NB * NK * 512,)
+    nb, ks, lane, e = np.meshgrid(np.arange(NB), np.arange(NK), np.arange(64), np.arange(8), indexing="ij")
+    want = Wp[np.minimum(16 * nb + lane % 16, V - 1), 32 * ks + 8 * (lane // 16) + e]
+    assert (got.reshape(NB, NK, 64, 8) == want).all()
+
+
+def _full_size(gpu_lib, name, seqs=None, B=None, packed=False):
     w = wl.WORKLOADS[name]
     if B is not None:
         w = dataclasses.replace(w, B=B)
     t = wl.make_lm_head_inputs_device(w, seed=0)
-    got = run_gpu(gpu_lib, t["hidden"], t["lm_weight"], t["tokens"], t["masked"], w.tau0, w.alpha)
+    got = run_gpu(gpu_lib, t["hidden"], t["lm_weight"], t["tokens"], t["masked"], w.tau0, w.alpha, packed=packed)
     # the oracle sees the same bits: copy the operands back (bf16 -> fp32 is exact)
     h = t["hidden"].float().cpu().numpy()
     W = t["lm_weight"].float().cpu().numpy()
@@ -268,31 +295,36 @@ def _full_size(gpu_lib, name, seqs=None, B=None):
     return skipped, want
 
 
-def test_lm_head_cfg2_full_size(gpu_lib):
-    skipped, want = _full_size(gpu_lib, "cfg2")
+@pytest.mark.parametrize("packed", [False, True])
+def test_lm_head_cfg2_full_size(gpu_lib, packed):
+    skipped, want = _full_size(gpu_lib, "cfg2", packed=packed)
     assert skipped == 0 and want["n_committed"][0] >= 1
 
 
-def test_lm_head_cfg2_two_sequences_full_size(gpu_lib):
+@pytest.mark.parametrize("packed", [False, True])
+def test_lm_head_cfg2_two_sequences_full_size(gpu_lib, packed):
     # 64 positions: the stream shape that keeps the hidden chunk in LDS, at the full vocabulary and width
-    skipped, _ = _full_size(gpu_lib, "cfg2", B=2)
+    skipped, _ = _full_size(gpu_lib, "cfg2", B=2, packed=packed)
     assert skipped == 0
 
 
-def test_lm_head_cfg2_four_sequences_full_size(gpu_lib):
+@pytest.mark.parametrize("packed", [False, True])
+def test_lm_head_cfg2_four_sequences_full_size(gpu_lib, packed):
     # 128 positions: the stream shape fed by global -> LDS transfers, at the full vocabulary and width
-    skipped, _ = _full_size(gpu_lib, "cfg2", B=4)
+    skipped, _ = _full_size(gpu_lib, "cfg2", B=4, packed=packed)
     assert skipped <= 1
 
 
-def test_lm_head_cfg3A_full_size(gpu_lib):
+@pytest.mark.parametrize("packed", [False, True])
+def test_lm_head_cfg3A_full_size(gpu_lib, packed):
     # 256 masked rows = two row chunks per vocabulary tile; the oracle projects every row (a few tens of seconds)
-    skipped, _ = _full_size(gpu_lib, "cfg3A")
+    skipped, _ = _full_size(gpu_lib, "cfg3A", packed=packed)
     assert skipped <= 1
 
 
-def test_lm_head_cfg4boost_sampled_sequences(gpu_lib):
+@pytest.mark.parametrize("packed", [False, True])
+def test_lm_head_cfg4boost_sampled_sequences(gpu_lib, packed):
     # 16 x 32 positions, a different masked count per sequence (rows compacted across sequences), V = 152064,
     # Hd = 3584 (seven LDS chunks); the oracle runs on four of the sixteen sequences
-    skipped, _ = _full_size(gpu_lib, "cfg4boost", seqs=[0, 5, 10, 15])
+    skipped, _ = _full_size(gpu_lib, "cfg4boost", seqs=[0, 5, 10, 15], packed=packed)
     assert skipped <= 1
