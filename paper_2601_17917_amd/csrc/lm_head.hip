@@ -1080,17 +1080,24 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_packed_kernel(LmHeadArgs a
   const uint16_t* hrow[2];
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb) hrow[rb] = a.hidden + (long long)max(row_of[rb * 16 + l16], 0) * a.ld_h + 8 * q;
-  auto load_b = [&](int c, bf16x8 (&dst)[kPkKS][2]) {            // chunk at walk position c; zeros past Hd
+  // (loaded as they are; k-steps past Hd are zeroed when the chunk becomes the current one: a mask applied at
+  // the load would make the compiler wait for it there, behind every A load in flight)
+  auto load_b = [&](int c, u32x4 (&dst)[kPkKS][2]) {             // chunk at walk position c
+    const int k0 = chunk_at(c) * kPkKS;
+#pragma unroll
+    for (int ks = 0; ks < kPkKS; ++ks) {
+      const int kk = min(k0 + ks, NK - 1);
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) dst[ks][rb] = *reinterpret_cast<const u32x4*>(hrow[rb] + 32 * kk);
+    }
+  };
+  auto take_b = [&](int c, const u32x4 (&src)[kPkKS][2], bf16x8 (&dst)[kPkKS][2]) {   // zeros past Hd
     const int k0 = chunk_at(c) * kPkKS;
 #pragma unroll
     for (int ks = 0; ks < kPkKS; ++ks) {
       const unsigned keep = (k0 + ks < NK) ? 0xffffffffu : 0u;
-      const int kk = min(k0 + ks, NK - 1);
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb) {
-        const u32x4 v = *reinterpret_cast<const u32x4*>(hrow[rb] + 32 * kk);
-        dst[ks][rb] = __builtin_bit_cast(bf16x8, v & u32x4{keep, keep, keep, keep});
-      }
+      for (int rb = 0; rb < 2; ++rb) dst[ks][rb] = __builtin_bit_cast(bf16x8, src[ks][rb] & u32x4{keep, keep, keep, keep});
     }
   };
 
@@ -1098,10 +1105,12 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_packed_kernel(LmHeadArgs a
 #pragma unroll
   for (int t = 0; t < TT; ++t) { acc[t][0] = f32x4{0.f, 0.f, 0.f, 0.f}; acc[t][1] = f32x4{0.f, 0.f, 0.f, 0.f}; }
   bf16x8 abuf[kPkPF][TT];
-  bf16x8 bcur[kPkKS][2], bnext[kPkKS][2];
-  load_b(0, bcur);
+  bf16x8 bcur[kPkKS][2];
+  u32x4 bnext[kPkKS][2];
+  load_b(0, bnext);
 #pragma unroll
   for (int s = 0; s < kPkPF; ++s) load_a(s, abuf[s]);
+  take_b(0, bnext, bcur);
 
   for (int kc = 0; kc < NCH; ++kc) {
     load_b(kc + 1, bnext);                         // older than every A load below: it is back before they are
@@ -1118,8 +1127,7 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_packed_kernel(LmHeadArgs a
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-#pragma unroll
-    for (int ks = 0; ks < kPkKS; ++ks) { bcur[ks][0] = bnext[ks][0]; bcur[ks][1] = bnext[ks][1]; }
+    take_b(kc + 1, bnext, bcur);
   }
 
   // ---- row reduction: this lane holds, for position rb * 16 + l16, the ids (nb0 + t) * 16 + 4 q + r
