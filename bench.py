@@ -321,24 +321,31 @@ def main():
         lm = wl.make_lm_head_inputs_device(w, args.seed)
         tok0 = torch.from_numpy(lm["tokens"]).cuda(); msk0 = torch.from_numpy(lm["masked"]).cuda()
         tok, msk = tok0.clone(), msk0.clone()
-        lm_call = sd.bind_lm_head_unmask(lm["hidden"], lm["lm_weight"], tok, msk, w.tau0, w.alpha)
-
-        def lm_fresh():
-            tok.copy_(tok0); msk.copy_(msk0)
-            lm_call()
 
         def lm_restore():
             tok.copy_(tok0); msk.copy_(msk0)
 
-        t_lm = time_kernel(lm_fresh, iters=20) - time_kernel(lm_restore, iters=20)
         lm_rows = int((lm["masked"] != 0).sum())
         lm_bytes = w.V * w.Hd * 2 + lm_rows * w.Hd * 2
         lm_flops = 2.0 * lm_rows * w.V * w.Hd
-        kernels["lm_head_unmask_call"] = {
-            "ms": t_lm, "gbs": lm_bytes / t_lm / 1e6, "frac_hbm_peak": lm_bytes / t_lm / 1e6 / HBM_PEAK_GBS,
-            "tflops": lm_flops / t_lm / 1e9, "frac_mfma_peak": lm_flops / t_lm / 1e9 / MFMA_BF16_PEAK_TFLOPS,
-            "masked_rows": lm_rows, "hidden": w.Hd, "in_timed_step": False}
-        del lm, lm_call
+
+        def time_lm(weight):
+            lm_call = sd.bind_lm_head_unmask(lm["hidden"], weight, tok, msk, w.tau0, w.alpha)
+
+            def lm_fresh():
+                tok.copy_(tok0); msk.copy_(msk0)
+                lm_call()
+
+            t_lm = time_kernel(lm_fresh, iters=20) - time_kernel(lm_restore, iters=20)
+            return {"ms": t_lm, "gbs": lm_bytes / t_lm / 1e6, "frac_hbm_peak": lm_bytes / t_lm / 1e6 / HBM_PEAK_GBS,
+                    "tflops": lm_flops / t_lm / 1e9, "frac_mfma_peak": lm_flops / t_lm / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+                    "masked_rows": lm_rows, "hidden": w.Hd, "in_timed_step": False}
+
+        kernels["lm_head_unmask_call"] = time_lm(lm["lm_weight"])
+        # the same call over the image that sdllm_lm_head_pack_weight writes once for a model weight
+        packed_w = sd.lm_head_pack_weight(lm["lm_weight"])
+        kernels["lm_head_unmask_call_packed_weight"] = time_lm(packed_w)
+        del lm, packed_w
     # ---- what plain kernels reach on this machine (library diagnostics): the practical ceilings next to the
     # published peaks the fractions are quoted against
     buf = torch.empty((1 << 31,), dtype=torch.uint8, device="cuda").random_(0, 256)
