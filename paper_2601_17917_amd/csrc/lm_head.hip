@@ -109,7 +109,11 @@ struct LmShape {
   }
 };
 
-__device__ __forceinline__ bf16x8 load_w(const uint16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
+template <bool NT = false>
+__device__ __forceinline__ bf16x8 load_w(const uint16_t* p) {
+  if constexpr (NT) return __builtin_bit_cast(bf16x8, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p)));
+  else return *reinterpret_cast<const bf16x8*>(p);
+}
 
 // acc += A B, with the accumulator either left to the compiler or pinned to the accumulation registers
 template <bool ACC_IN_AGPR>
@@ -118,7 +122,9 @@ __device__ __forceinline__ void mfma_acc(f32x4& acc, const bf16x8& a, const bf16
   else acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc, 0, 0, 0);
 }
 
-template <int BM, int WNB, int PF_>
+// PACKED: W is the packed image (a lane's operand pieces of consecutive k-steps are 1 KB apart, a wave's load is
+// one contiguous kilobyte that no other load touches: nontemporal)
+template <int BM, int WNB, int PF_, bool PACKED>
 __global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB, PF_>::MIN_WAVES)) void lm_head_rows_kernel(LmHeadArgs a) {
   using S = LmShape<BM, WNB, PF_>;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
@@ -179,10 +185,10 @@ __global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB, PF_>::MIN_WAVES)) voi
   };
   auto chunk_at = [&](int c) { int ch = c + c0; ch -= (ch >= NCH) ? NCH : 0; return ch; };   // c < NCH
   const uint16_t* wrow[WNB];                                   // this lane's operand piece of k-step 0
-  const int wks = a.packed ? 512 : 32;                         // elements from one k-step's piece to the next
+  constexpr int wks = PACKED ? 512 : 32;                       // elements from one k-step's piece to the next
 #pragma unroll
   for (int ib = 0; ib < WNB; ++ib) {
-    if (a.packed) {
+    if constexpr (PACKED) {
       const int nb = min(tile * (S::BN / 16) + wave * WNB + ib, (a.V + 15) / 16 - 1);   // blocks past V: the last one
       wrow[ib] = a.weight + ((long long)nb * NK * 64 + lane) * 8;
     } else {
@@ -214,7 +220,7 @@ __global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB, PF_>::MIN_WAVES)) voi
 #pragma unroll
   for (int s = 0; s < S::PF; ++s)
 #pragma unroll
-    for (int ib = 0; ib < WNB; ++ib) abuf[s][ib] = load_w(wrow[ib] + wks * kstep_at(s));
+    for (int ib = 0; ib < WNB; ++ib) abuf[s][ib] = load_w<PACKED>(wrow[ib] + wks * kstep_at(s));
   // A chunk's pieces past Hd are staged as zeros and its k-steps past Hd are computed like the others
   // (finite W times zero adds nothing): the loop body has no branch, so the compiler's wait counters
   // see one straight line and keep the W loads PF steps ahead.
@@ -280,7 +286,7 @@ __global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB, PF_>::MIN_WAVES)) voi
 #pragma unroll
           for (int ib = 0; ib < WNB; ++ib) aop[ib] = abuf[slot_a][ib];
 #pragma unroll
-          for (int ib = 0; ib < WNB; ++ib) abuf[slot_a][ib] = load_w(wrow[ib] + wks * kstep_at(g + S::PF));
+          for (int ib = 0; ib < WNB; ++ib) abuf[slot_a][ib] = load_w<PACKED>(wrow[ib] + wks * kstep_at(g + S::PF));
 #pragma unroll
           for (int jb = 0; jb < S::JB; ++jb) {
             const int t = ks * S::JB + jb, tn = t + S::DB;
@@ -326,7 +332,7 @@ __global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB, PF_>::MIN_WAVES)) voi
 #pragma unroll
         for (int ib = 0; ib < WNB; ++ib) aop[ib] = abuf[slot_a][ib];
 #pragma unroll
-        for (int ib = 0; ib < WNB; ++ib) abuf[slot_a][ib] = load_w(wrow[ib] + wks * kstep_at(g + S::PF));
+        for (int ib = 0; ib < WNB; ++ib) abuf[slot_a][ib] = load_w<PACKED>(wrow[ib] + wks * kstep_at(g + S::PF));
 #pragma unroll
         for (int jb = 0; jb < S::JB; ++jb) {
           const bf16x8 bop = *reinterpret_cast<const bf16x8*>(
@@ -1320,9 +1326,10 @@ static hipError_t launch_dma_tt(int tt, const LmHeadArgs& r, hipStream_t stream)
 }
 static hipError_t launch_rows(const LmHeadArgs& r, hipStream_t stream) {
   static_assert(LmShape<256, 4, 4>::NST == 3 && LmShape<256, 4, 4>::BN == 256, "lm_lds_bytes, lm_plan");
-  static bool attr_set = false;
+  static bool attr_set[2] = {false, false};
   const unsigned grid = (unsigned)(((r.ntile + kNumXCDs - 1) / kNumXCDs) * r.nchunk * kNumXCDs);
-  return launch_kernel(lm_head_rows_kernel<256, 4, 4>, attr_set, lm_lds_bytes(kShapeRows, 0), grid, r, stream);
+  if (r.packed) return launch_kernel(lm_head_rows_kernel<256, 4, 4, true>, attr_set[1], lm_lds_bytes(kShapeRows, 1), grid, r, stream);
+  return launch_kernel(lm_head_rows_kernel<256, 4, 4, false>, attr_set[0], lm_lds_bytes(kShapeRows, 0), grid, r, stream);
 }
 
 static hipError_t launch_shape(int shape, int tt, const LmHeadArgs& r, hipStream_t stream) {
