@@ -17,11 +17,14 @@
 //     lane exchanges, then across the four waves through LDS.
 //   * Row chunks of one vocabulary tile get workgroup ids that are equal mod 8 and adjacent in
 //     dispatch order: same XCD, same L2, so W comes from HBM once.
-//   * Shapes: with 256 rows per chunk (more than 64 positions) lm_head_rows_kernel is bound by the
-//     matrix pipe (one wave per SIMD, accumulators in the accumulation registers, B operands through a
-//     register ring fed across chunk boundaries).  Calls of at most 64 positions are a read of W and
-//     take the two stream kernels further down, which turn the roles around: W goes through LDS in
-//     1 KB row pieces, the hidden operands stay in registers (up to 32 positions) or in LDS (33..64).
+//   * Shapes: with 256 rows per chunk (more than 128 masked positions) lm_head_rows_kernel is bound by
+//     the matrix pipe (one wave per SIMD, accumulators in the accumulation registers, B operands through
+//     a register ring fed across chunk boundaries).  Calls with at most 128 masked positions are a read
+//     of W and take the stream kernels further down, which turn the roles around: the hidden operands
+//     stay in registers and W goes through LDS (1 KB row pieces through registers up to 64 positions,
+//     global -> LDS transfers up to 128), or, when W is the packed image, comes straight from it.
+//   * The masked count is device data: the host launches every shape that B x K admits and each launch
+//     exits unless the count is in its range.
 #include "common.h"
 #include "unmask_common.h"
 #include <climits>
@@ -235,7 +238,8 @@ __global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB, PF_>::MIN_WAVES)) voi
     }
   };
   stage_now(0, stage);
-  if constexpr (S::WIDE) stage_now(1, stage + kLmStageBytes);
+  static_assert(S::WIDE, "only the 256-row shape is built: fewer positions take the stream kernels");
+  stage_now(1, stage + kLmStageBytes);
   __syncthreads();
 
   const int NCHU = (NCH + S::U - 1) / S::U * S::U;      // chunks past NCH see zeros
@@ -312,44 +316,6 @@ __global__ __launch_bounds__(kLmThreads, (LmShape<BM, WNB, PF_>::MIN_WAVES)) voi
     // the accumulators written by the last matrix instructions are read by vector instructions next; the
     // compiler does not see an MFMA inside the asm statement, so the required wait states are spelled out
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
-  } else {
-    // ---- main loop, narrow shapes: two LDS stages, the kernel is a stream of W
-    for (int c = 0; c < NCHU; ++c) {
-      const unsigned char* cur = stage + (c & 1) * kLmStageBytes;
-      unsigned char* nxt = stage + ((c + 1) & 1) * kLmStageBytes;
-      const bool more = c + 1 < NCH;
-      const unsigned k = (unsigned)(chunk_at(more ? c + 1 : 0) * S::KC) + 8u * pc;
-      const unsigned kc = min(k, klast);
-      u32x4 hreg[S::NPASS];
-#pragma unroll
-      for (int i = 0; i < S::NPASS; ++i) hreg[i] = *reinterpret_cast<const u32x4*>(a.hidden + (hoff[i] + kc));
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int ks = 0; ks < S::KSTEPS; ++ks) {
-        const int g = c * S::KSTEPS + ks;
-        const int slot_a = ks % S::PF;
-        bf16x8 aop[WNB];
-#pragma unroll
-        for (int ib = 0; ib < WNB; ++ib) aop[ib] = abuf[slot_a][ib];
-#pragma unroll
-        for (int ib = 0; ib < WNB; ++ib) abuf[slot_a][ib] = load_w<PACKED>(wrow[ib] + wks * kstep_at(g + S::PF));
-#pragma unroll
-        for (int jb = 0; jb < S::JB; ++jb) {
-          const bf16x8 bop = *reinterpret_cast<const bf16x8*>(
-              cur + boff + jb * 16 * S::KC * 2 + (unsigned)(S::swz(l16, 4 * ks + q) << 4));
-#pragma unroll
-          for (int ib = 0; ib < WNB; ++ib) mfma_acc<false>(acc[ib][jb], aop[ib], bop);
-        }
-        // keep the k-steps in the written order: left alone, the scheduler gathers the W loads of a whole
-        // chunk at its end and the stream runs dry in between
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      const unsigned keep = (more && k < (unsigned)a.Hd) ? 0xffffffffu : 0u;
-#pragma unroll
-      for (int i = 0; i < S::NPASS; ++i)
-        *reinterpret_cast<u32x4*>(nxt + soff[i]) = hreg[i] & u32x4{keep, keep, keep, keep};
-      __syncthreads();
-    }
   }
 
   // ---- row reduction of the tile: in-lane over this lane's vocabulary ids (ascending), then over the
