@@ -1172,7 +1172,10 @@ static int stream_tt(int V, const int (&tts)[N], int sub = kStSub) {
 
 // top: the shape for B x K positions all masked; the shapes below it are launched too and serve the smaller
 // masked counts; ntile_out is the largest tile count among the launched shapes.
-struct LmPlan { int top, nchunk, packed, tt[kNumShapes], bn[kNumShapes], ntile[kNumShapes], ntile_out; };
+// first: the smallest shape launched.  Over a packed W the 64-position kernel streams as fast as the
+// 32-position one (161 against 167 us for 126464 x 4096), so where both would be launched the former serves
+// 1..64 masked positions and the call has one idle launch less.
+struct LmPlan { int first, top, nchunk, packed, tt[kNumShapes], bn[kNumShapes], ntile[kNumShapes], ntile_out; };
 
 static LmPlan lm_plan(const sdllm_lm_head_params& p) {
   const long long rows = (long long)p.B * p.K;
@@ -1190,11 +1193,12 @@ static LmPlan lm_plan(const sdllm_lm_head_params& p) {
   pl.tt[kShapeRows] = 1;                  // 256-row tiles (also for a half-empty chunk: it beat 128-row tiles)
   pl.top = 0;
   while (rows > kShapeMax[pl.top]) ++pl.top;
+  pl.first = (pl.packed && pl.top > kShape32) ? kShape64 : kShape32;
   pl.ntile_out = 0;
   for (int i = 0; i < kNumShapes; ++i) {
     pl.bn[i] = pl.tt[i] * sub[i];
     pl.ntile[i] = (p.V + pl.bn[i] - 1) / pl.bn[i];
-    if (i <= pl.top) pl.ntile_out = std::max(pl.ntile_out, pl.ntile[i]);
+    if (i >= pl.first && i <= pl.top) pl.ntile_out = std::max(pl.ntile_out, pl.ntile[i]);
   }
   pl.nchunk = pl.top == kShapeRows ? (int)((rows + 255) / 256) : 1;
   return pl;
@@ -1348,9 +1352,9 @@ hipError_t launch_lm_head_unmask(const sdllm_lm_head_params& p, const void* hidd
   hipError_t e = hipSuccess;
   // every shape up to the one that B x K needs: the smaller ones take the call when few enough positions are
   // still masked (the later steps of a block); each launch exits unless the masked count is in its range
-  for (int i = 0; i <= pl.top && e == hipSuccess; ++i) {
+  for (int i = pl.first; i <= pl.top && e == hipSuccess; ++i) {
     r.ntile = pl.ntile[i];
-    r.min_masked = i == 0 ? 1 : kShapeMax[i - 1] + 1;
+    r.min_masked = i == pl.first ? 1 : kShapeMax[i - 1] + 1;
     r.max_masked = i == pl.top ? INT_MAX : kShapeMax[i];
     e = launch_shape(i, pl.tt[i], r, stream);
   }
