@@ -12,7 +12,8 @@
  *   sdllm_kv_append          copy the finished block's K/V into the prefix cache
  *   sdllm_rope_gathered      rotary embedding of the pruned rows with their original position ids
  *   sdllm_suffix_keep_indices  (host) which suffix rows the attenuation-guided rule keeps
- *   sdllm_probe_*            diagnostics: read / copy / matrix-instruction ceilings of the device
+ *   sdllm_init               (optional) one-time set-up on the current device, so that later calls only launch
+ * Diagnostics that are not part of the decode step (device ceilings) are declared in sdllm_diag.h.
  *
  * Conventions common to all calls
  *   - Every buffer is CALLER-ALLOCATED DEVICE memory unless said otherwise; the library
@@ -30,6 +31,10 @@
  *     host before any HIP call, so it works on a machine without a GPU.  A human-readable
  *     message for the calling thread's last failure is available from sdllm_last_error().
  *   - Concurrent calls are allowed when they use different workspaces and outputs.
+ *   - A call's launch plan is a pure function of its parameter struct: nothing is read from the process
+ *     environment.
+ *   - Every call except sdllm_validate_keep_idx may be recorded into a HIP graph (stream capture): after
+ *     sdllm_init() on the device a call consists of kernel launches only (no memset, no copy, no attribute call).
  */
 #ifndef SDLLM_H
 #define SDLLM_H
@@ -41,7 +46,7 @@
 extern "C" {
 #endif
 
-#define SDLLM_VERSION 100
+#define SDLLM_VERSION 200
 
 enum {
   SDLLM_OK = 0,
@@ -52,6 +57,12 @@ enum {
 };
 
 enum { SDLLM_FP32 = 0, SDLLM_BF16 = 1 };
+
+/* One-time set-up on the CURRENT device (optional; every call does what it needs on first use).  Opts every kernel
+ * of the library in to its LDS size and looks up the library's device-resident scratch array, so that the calls
+ * that follow consist of kernel launches only -- what a caller recording them into a HIP graph needs.  Idempotent,
+ * thread-safe, once per device.  Errors: HIP. */
+int sdllm_init(void);
 
 /* ---------------------------------------------------------------------------------------
  * Attention over the pruned sequence  x~ = prefix U current U kept-suffix  (paper Eq. 8).
@@ -102,6 +113,12 @@ int sdllm_block_attention(const sdllm_attn_params* p,
                           void* out,
                           void* workspace, size_t workspace_bytes, void* stream);
 
+/* Debug check of sdllm_block_attention's precondition on keep_idx (the index set of Eq. 7 as the device sees it):
+ * copies the n_keep entries to the host, SYNCHRONISES `stream`, and verifies that they are strictly increasing and
+ * lie in [0, S).  Not for the decode loop and not capturable.  keep_idx may be NULL iff n_keep == 0.
+ * Returns SDLLM_OK, or INVALID_ARG with the first offending entry in sdllm_last_error(), or HIP. */
+int sdllm_validate_keep_idx(const int32_t* keep_idx, int32_t n_keep, int32_t S, void* stream);
+
 /* ---------------------------------------------------------------------------------------
  * Confidence-aware unmasking of the active block.
  *   For every masked position i (paper Eq. 4):  xhat_i = argmax_j z_ij (lowest id on ties),
@@ -141,6 +158,8 @@ size_t sdllm_unmask_workspace_bytes(const sdllm_unmask_params* p);
  *               other entries untouched
  *   n_committed [B] int32 out      block_done [B] uint8 out
  *   eos_seen    [B] uint8 in/out, optional (NULL ok)
+ * Logits outside the method's domain (NaN, +inf): the position's confidence is NaN, it never passes the threshold
+ * and ranks last for the fallback; a row without any finite logit has xhat = 0.  Every store stays in bounds.
  */
 int sdllm_confidence_unmask(const sdllm_unmask_params* p,
                             const void* logits,
@@ -317,23 +336,6 @@ typedef struct sdllm_attn_plan {
 } sdllm_attn_plan;
 
 int sdllm_plan_attention(const sdllm_attn_params* p, sdllm_attn_plan* plan);
-
-/* ---------------------------------------------------------------------------------------
- * Device ceilings (diagnostics; not part of the decode step): what plain kernels reach on the
- * device, to read the roofline fractions of the hot-path kernels against.
- *   sdllm_probe_read       streams `bytes` (multiple of 16, > 0) of src once; sink: >= 4 bytes of
- *                          device memory that is practically never written
- *   sdllm_probe_copy       dst <- src, `bytes` (multiple of 16, > 0), bit for bit; no overlap
- *   sdllm_probe_mfma_bf16  2 workgroups of 4 waves per CU, each wave `iters` (>= 1) rounds of 8 independent
- *                          v_mfma_f32_16x16x32_bf16; operand_kind 0 = smooth small operand values,
- *                          1 = pseudo-random sign / exponent / mantissa bits (more power per
- *                          instruction, lower sustained clock).  *flops (HOST, optional) receives the
- *                          floating-point operations of one launch.
- * All three only enqueue one kernel on `stream`.  Errors: INVALID_ARG, HIP.
- * ------------------------------------------------------------------------------------- */
-int sdllm_probe_read(const void* src, size_t bytes, void* sink, void* stream);
-int sdllm_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
-int sdllm_probe_mfma_bf16(int32_t iters, int32_t operand_kind, void* sink, void* stream, double* flops);
 
 const char* sdllm_status_string(int status);
 const char* sdllm_last_error(void); /* calling thread's last failure text ("" if none) */

@@ -23,7 +23,7 @@ EXPORTED_SYMBOLS = (
     "sdllm_lm_head_pack_weight", "sdllm_lm_head_packed_weight_bytes",
     "sdllm_kv_append", "sdllm_suffix_keep_indices", "sdllm_rope_gathered",
     "sdllm_probe_read", "sdllm_probe_copy", "sdllm_probe_mfma_bf16",
-    "sdllm_status_string", "sdllm_last_error", "sdllm_version",
+    "sdllm_status_string", "sdllm_last_error", "sdllm_version", "sdllm_init", "sdllm_validate_keep_idx",
 )
 
 
@@ -95,6 +95,10 @@ def load_library(path: Optional[str] = None):
     lib = ctypes.CDLL(path)
     vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
     lib.sdllm_version.restype = i32
+    lib.sdllm_init.restype = i32
+    lib.sdllm_init.argtypes = []
+    lib.sdllm_validate_keep_idx.restype = i32
+    lib.sdllm_validate_keep_idx.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, vp]
     lib.sdllm_last_error.restype = ctypes.c_char_p
     lib.sdllm_status_string.restype = ctypes.c_char_p
     lib.sdllm_status_string.argtypes = [i32]
@@ -168,6 +172,20 @@ def _require(t, name, dtype=None):
         raise SdllmError(ERR_INVALID_ARG, f"{name} must be contiguous")
     if dtype is not None and t.dtype != dtype:
         raise SdllmError(ERR_INVALID_ARG, f"{name} must have dtype {dtype}, has {t.dtype}")
+
+
+def init():
+    """sdllm_init on the current device: every kernel opt-in done, so that later calls only launch."""
+    _check(load_library().sdllm_init())
+
+
+def validate_keep_idx(keep_idx, S: int, stream=None):
+    """sdllm_validate_keep_idx (debug; synchronises): raises SdllmError unless keep_idx is strictly increasing
+    within [0, S)."""
+    import torch
+    _require(keep_idx, "keep_idx", torch.int32)
+    n = 0 if keep_idx is None else int(keep_idx.shape[0])
+    _check(load_library().sdllm_validate_keep_idx(_ptr(keep_idx), n, S, _stream(stream)))
 
 
 # ---------------------------------------------------------------------------------------------
@@ -391,14 +409,29 @@ def kv_append(*args, **kw):
     return bind_kv_append(*args, **kw)()
 
 
+def _require_layers(t, name, dtype):
+    """A [L, ...] tensor whose layers are contiguous blocks a constant distance apart (stride(0) may exceed the
+    dense size: layers padded or interleaved with other data)."""
+    if not t.is_cuda:
+        raise SdllmError(ERR_INVALID_ARG, f"{name} must be a device tensor")
+    if t.dtype != dtype:
+        raise SdllmError(ERR_INVALID_ARG, f"{name} must have dtype {dtype}, has {t.dtype}")
+    if not t[0].is_contiguous() or (t.shape[0] > 1 and t.stride(0) < t[0].numel()):
+        raise SdllmError(ERR_INVALID_ARG, f"{name}: every layer must be contiguous and layers must not overlap")
+
+
 def bind_kv_append(k_caches, v_caches, k_blocks, v_blocks, prefix_len: int, do_append=None, stream=None) -> BoundCall:
     import torch
     L, B, Hkv, cap, D = k_caches.shape
     K = k_blocks.shape[3]
     for name, t in (("k_caches", k_caches), ("v_caches", v_caches), ("k_blocks", k_blocks), ("v_blocks", v_blocks)):
-        _require(t, name, k_caches.dtype)
+        _require_layers(t, name, k_caches.dtype)
     _require(do_append, "do_append", torch.uint8)
-    p = AppendParams(_dtype_code(k_caches), L, B, Hkv, D, K, prefix_len, cap, 0, 0)
+    if L > 1 and (v_caches.stride(0) != k_caches.stride(0) or v_blocks.stride(0) != k_blocks.stride(0)):
+        raise SdllmError(ERR_INVALID_ARG, "kv_append: K and V tensors must share their layer strides")
+    cls = k_caches.stride(0) if L > 1 else 0           # 0 = dense (a single layer has no stride to speak of)
+    bls = k_blocks.stride(0) if L > 1 else 0
+    p = AppendParams(_dtype_code(k_caches), L, B, Hkv, D, K, prefix_len, cap, cls, bls)
     args = (ctypes.byref(p), _ptr(k_caches), _ptr(v_caches), _ptr(k_blocks), _ptr(v_blocks), _ptr(do_append),
             _stream(stream))
     keep = (p, k_caches, v_caches, k_blocks, v_blocks, do_append)

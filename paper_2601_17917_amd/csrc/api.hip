@@ -5,6 +5,7 @@
 #include <cstdarg>
 #include <cstring>
 #include <cmath>
+#include <vector>
 
 namespace {
 
@@ -139,6 +140,13 @@ extern "C" {
 
 int sdllm_version(void) { return SDLLM_VERSION; }
 
+int sdllm_init(void) {
+  hipError_t e = sdllm::prepare_attention_bf16();
+  if (e == hipSuccess) e = sdllm::prepare_lm_head();
+  if (e != hipSuccess) return fail(SDLLM_ERR_HIP, "init: %s", hipGetErrorString(e));
+  return SDLLM_OK;
+}
+
 const char* sdllm_last_error(void) { return g_err; }
 
 const char* sdllm_status_string(int status) {
@@ -206,6 +214,26 @@ int sdllm_block_attention(const sdllm_attn_params* p,
                                               k_suffix, v_suffix, keep_idx, out, need ? workspace : nullptr,
                                               (hipStream_t)stream);
   if (e != hipSuccess) return fail(SDLLM_ERR_HIP, "attention (bf16): %s", hipGetErrorString(e));
+  return SDLLM_OK;
+}
+
+int sdllm_validate_keep_idx(const int32_t* keep_idx, int32_t n_keep, int32_t S, void* stream) {
+  if (n_keep < 0 || S < 0 || n_keep > S)
+    return fail(SDLLM_ERR_INVALID_ARG, "validate_keep_idx: need 0 <= n_keep (%d) <= S (%d)", n_keep, S);
+  if (n_keep == 0) return SDLLM_OK;
+  if (!keep_idx) return fail(SDLLM_ERR_INVALID_ARG, "validate_keep_idx: keep_idx is NULL with n_keep > 0");
+  std::vector<int32_t> host((size_t)n_keep);
+  hipError_t e = hipMemcpyAsync(host.data(), keep_idx, (size_t)n_keep * sizeof(int32_t), hipMemcpyDeviceToHost,
+                                (hipStream_t)stream);
+  if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+  if (e != hipSuccess) return fail(SDLLM_ERR_HIP, "validate_keep_idx: %s", hipGetErrorString(e));
+  for (int32_t j = 0; j < n_keep; ++j) {
+    if (host[j] < 0 || host[j] >= S)
+      return fail(SDLLM_ERR_INVALID_ARG, "validate_keep_idx: keep_idx[%d] = %d is outside [0, %d)", j, host[j], S);
+    if (j > 0 && host[j] <= host[j - 1])
+      return fail(SDLLM_ERR_INVALID_ARG, "validate_keep_idx: keep_idx[%d] = %d does not exceed keep_idx[%d] = %d",
+                  j, host[j], j - 1, host[j - 1]);
+  }
   return SDLLM_OK;
 }
 

@@ -20,7 +20,6 @@
 //   Online softmax in the log2 domain; a split writes (unnormalised O, m, l) and a second
 //   kernel merges the splits in a fixed order (deterministic, no atomics).
 #include "common.h"
-#include <cstdlib>
 
 namespace sdllm {
 
@@ -589,8 +588,6 @@ AttnPlan plan_attention_bf16(const sdllm_attn_params& p) {
   const int g = p.Hq / p.Hkv;
   const long long Rtot = (long long)g * (p.K + p.n_keep);
   const long long Nkv = (long long)p.prefix_len + p.K + p.n_keep;
-  // tuning knob for sweeps (read once): SDLLM_ATTN_RB = 1|2
-  static const int env_rb = [] { const char* e = getenv("SDLLM_ATTN_RB"); return e ? atoi(e) : 0; }();
   // 32 query rows per wave (128 per workgroup) pay off only when many query rows share one K/V
   // stream (dense suffix); measured: 1024 rows -> 1.4x faster, 448 rows (GQA 7:1) -> 8 % slower
   pl.rb = Rtot >= 512 ? 2 : 1;
@@ -598,7 +595,6 @@ AttnPlan plan_attention_bf16(const sdllm_attn_params& p) {
   // one workgroup only, which lets the transfers carry the nontemporal hint (32 layers x 5248 keys, 128 rows:
   // 2650 -> 2510 us per step; with 1312 keys the extra key splits it takes cost more than it gains)
   if (Rtot > 64 && Rtot <= 128 && Nkv >= 64 * kKeyTile) pl.rb = 2;
-  if (env_rb == 1 || env_rb == 2) pl.rb = env_rb;
   // Two ring stages, two workgroups per CU.  Deeper rings (3, 4 stages: one workgroup per CU) were
   // measured and are slower at every shape: with one wave per SIMD the per-tile latencies of the
   // MFMA / softmax / LDS chain are exposed, and those, not the K/V stream, bound the loop.
@@ -637,17 +633,33 @@ size_t attention_bf16_workspace_bytes(const sdllm_attn_params& p, const AttnPlan
 }
 
 template <int D, int RB, bool ONCE>
+static hipError_t opt_in_main() {
+  static LdsOptIn st;
+  return ensure_lds_opt_in(reinterpret_cast<const void*>(&attn_bf16_kernel<D, RB, ONCE>), Shape<D>::LDS_BYTES, st);
+}
+
+template <int D, int RB, bool ONCE>
 static hipError_t launch_main(const AttnArgs& a, const AttnPlan& pl, hipStream_t stream) {
   constexpr size_t lds_bytes = Shape<D>::LDS_BYTES;
-  static bool attr_set = false;                     // benign race: the call is idempotent
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<D, RB, ONCE>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  hipError_t e = opt_in_main<D, RB, ONCE>();
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL((attn_bf16_kernel<D, RB, ONCE>), dim3(pl.workgroups), dim3(256), lds_bytes, stream, a);
   return hipGetLastError();
+}
+
+template <int D>
+static hipError_t prepare_d() {
+  hipError_t e = opt_in_main<D, 1, false>();
+  if (e == hipSuccess) e = opt_in_main<D, 1, true>();
+  if (e == hipSuccess) e = opt_in_main<D, 2, false>();
+  if (e == hipSuccess) e = opt_in_main<D, 2, true>();
+  return e;
+}
+
+hipError_t prepare_attention_bf16() {
+  hipError_t e = prepare_d<128>();
+  if (e == hipSuccess) e = prepare_d<64>();
+  return e;
 }
 
 template <int D>

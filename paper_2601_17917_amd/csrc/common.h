@@ -4,12 +4,32 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <atomic>
 #include "sdllm.h"
+#include "sdllm_diag.h"
 
 namespace sdllm {
 
 constexpr int kNumCUs = 256;   // MI355X: 8 XCDs x 32 CUs
 constexpr int kNumXCDs = 8;
+
+// Opt-in of a kernel to its dynamic LDS size: done once per (kernel, device), safe when several threads
+// make their first call at the same time (the runtime call is idempotent; the bit only saves repeating it).
+// sdllm_init() runs every opt-in of the library for the current device, so that the calls that follow only launch.
+struct LdsOptIn { std::atomic<unsigned long long> done{0}; };
+inline hipError_t ensure_lds_opt_in(const void* kernel, size_t bytes, LdsOptIn& st) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const unsigned long long bit = 1ULL << (dev & 63);
+  if (st.done.load(std::memory_order_acquire) & bit) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e != hipSuccess) return e;
+  st.done.fetch_or(bit, std::memory_order_release);
+  return hipSuccess;
+}
+hipError_t prepare_attention_bf16();   // every opt-in of the module, for the current device
+hipError_t prepare_lm_head();
 
 // ---- attention launch plan (host, pure function of the parameters) ----
 struct AttnPlan {

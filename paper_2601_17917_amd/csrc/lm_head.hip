@@ -1247,38 +1247,35 @@ hipError_t launch_lm_head_pack_weight(int V, int Hd, long long ld_w, const void*
   return hipGetLastError();
 }
 
-// one launch; the kernel's opt-in to more than 64 KiB of dynamic LDS is set once
-static hipError_t launch_kernel(void (*kernel)(LmHeadArgs), bool& attr_set, size_t lds, unsigned grid,
+// One launch, or (r.hidden == nullptr: the preparation pass of sdllm_init) only the kernel's opt-in to its
+// dynamic LDS size on the current device.
+static hipError_t launch_kernel(void (*kernel)(LmHeadArgs), LdsOptIn& st, size_t lds, unsigned grid,
                                 const LmHeadArgs& r, hipStream_t stream) {
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  hipError_t e = ensure_lds_opt_in(reinterpret_cast<const void*>(kernel), lds, st);
+  if (e != hipSuccess || r.hidden == nullptr) return e;
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(kLmThreads), lds, stream, r);
   return hipGetLastError();
 }
 
 template <int TT>
 static hipError_t launch_stream32(const LmHeadArgs& r, hipStream_t stream) {
-  static bool attr_set = false;
-  return launch_kernel(lm_head_stream_kernel<TT>, attr_set, lm_lds_bytes(kShape32, 0), (unsigned)r.ntile, r, stream);
+  static LdsOptIn st;
+  return launch_kernel(lm_head_stream_kernel<TT>, st, lm_lds_bytes(kShape32, 0), (unsigned)r.ntile, r, stream);
 }
 template <int TT>
 static hipError_t launch_stream64(const LmHeadArgs& r, hipStream_t stream) {
-  static bool attr_set = false;
-  return launch_kernel(lm_head_stream64_kernel<TT>, attr_set, lm_lds_bytes(kShape64, 0), (unsigned)r.ntile, r, stream);
+  static LdsOptIn st;
+  return launch_kernel(lm_head_stream64_kernel<TT>, st, lm_lds_bytes(kShape64, 0), (unsigned)r.ntile, r, stream);
 }
 template <int TT>
 static hipError_t launch_packed32(const LmHeadArgs& r, hipStream_t stream) {
-  static bool attr_set = false;
-  return launch_kernel(lm_head_packed_kernel<TT>, attr_set, 0, (unsigned)r.ntile, r, stream);
+  static LdsOptIn st;
+  return launch_kernel(lm_head_packed_kernel<TT>, st, 0, (unsigned)r.ntile, r, stream);
 }
 template <int TT, int RB, bool PACKED>
 static hipError_t launch_dma(const LmHeadArgs& r, hipStream_t stream) {
-  static bool attr_set = false;
-  return launch_kernel(lm_head_dma_kernel<TT, RB, PACKED>, attr_set, dma_lds_bytes(RB), (unsigned)r.ntile, r, stream);
+  static LdsOptIn st;
+  return launch_kernel(lm_head_dma_kernel<TT, RB, PACKED>, st, dma_lds_bytes(RB), (unsigned)r.ntile, r, stream);
 }
 template <int RB, bool PACKED>
 static hipError_t launch_dma_tt(int tt, const LmHeadArgs& r, hipStream_t stream) {
@@ -1296,10 +1293,10 @@ static hipError_t launch_dma_tt(int tt, const LmHeadArgs& r, hipStream_t stream)
 }
 static hipError_t launch_rows(const LmHeadArgs& r, hipStream_t stream) {
   static_assert(LmShape<256, 4, 4>::NST == 3 && LmShape<256, 4, 4>::BN == 256, "lm_lds_bytes, lm_plan");
-  static bool attr_set[2] = {false, false};
+  static LdsOptIn st[2];
   const unsigned grid = (unsigned)(((r.ntile + kNumXCDs - 1) / kNumXCDs) * r.nchunk * kNumXCDs);
-  if (r.packed) return launch_kernel(lm_head_rows_kernel<256, 4, 4, true>, attr_set[1], lm_lds_bytes(kShapeRows, 1), grid, r, stream);
-  return launch_kernel(lm_head_rows_kernel<256, 4, 4, false>, attr_set[0], lm_lds_bytes(kShapeRows, 0), grid, r, stream);
+  if (r.packed) return launch_kernel(lm_head_rows_kernel<256, 4, 4, true>, st[1], lm_lds_bytes(kShapeRows, 1), grid, r, stream);
+  return launch_kernel(lm_head_rows_kernel<256, 4, 4, false>, st[0], lm_lds_bytes(kShapeRows, 0), grid, r, stream);
 }
 
 static hipError_t launch_shape(int shape, int tt, const LmHeadArgs& r, hipStream_t stream) {
@@ -1337,6 +1334,23 @@ static hipError_t launch_shape(int shape, int tt, const LmHeadArgs& r, hipStream
     case kShapeRows: return launch_rows(r, stream);
   }
   return hipErrorInvalidValue;      // not reached: lm_plan picks from the same lists
+}
+
+// Every kernel shape and tile size the plan can pick, for both weight layouts: opt-ins only, nothing is launched.
+hipError_t prepare_lm_head() {
+  LmHeadArgs r{};
+  r.hidden = nullptr; r.ntile = 1; r.nchunk = 1;
+  hipError_t e = hipSuccess;
+  for (int packed = 0; packed <= 1 && e == hipSuccess; ++packed) {
+    r.packed = packed;
+    if (packed) { for (int tt : kPkTTs) if (e == hipSuccess) e = launch_shape(kShape32, tt, r, nullptr); }
+    else        { for (int tt : kStTTs) if (e == hipSuccess) e = launch_shape(kShape32, tt, r, nullptr); }
+    if (packed) { for (int tt : kDmTTs) if (e == hipSuccess) e = launch_shape(kShape64, tt, r, nullptr); }
+    else        { for (int tt : kSt2TTs) if (e == hipSuccess) e = launch_shape(kShape64, tt, r, nullptr); }
+    for (int tt : kDmTTs) if (e == hipSuccess) e = launch_shape(kShape128, tt, r, nullptr);
+    if (e == hipSuccess) e = launch_shape(kShapeRows, 1, r, nullptr);
+  }
+  return e;
 }
 
 hipError_t launch_lm_head_unmask(const sdllm_lm_head_params& p, const void* hidden, const void* weight,

@@ -12,7 +12,6 @@
 // the L2 of an XCD on every workgroup and cost several times the second launch.)
 #include "common.h"
 #include "unmask_common.h"
-#include <cstdlib>
 
 namespace sdllm {
 
@@ -191,10 +190,11 @@ __device__ __forceinline__ void commit_sequence(const UnmaskArgs& a, int b, floa
         c = 1.0f / s;
         my_masked++;
         if (a.confidence) a.confidence[pos] = c;
-        xhat_s[i] = idx;
-        // the selection below works on a strictly positive finite number: a row of NaN logits (garbage
-        // in) ranks last instead of leaving the fallback without a candidate
-        if (!(c > 0.f)) c = 1e-38f;
+        // a row without any finite logit has no arg-max: id 0 stands in, so that a committed id is always < V
+        xhat_s[i] = (unsigned)idx < (unsigned)a.V ? idx : 0;
+        // the selection below works on a strictly positive NORMAL number (it survives a flush of denormals):
+        // a row of NaN logits (garbage in) ranks last instead of leaving the fallback without a candidate
+        if (!(c > 0.f)) c = 1.17549435e-38f;
       }
       conf_s[i] = c;
     }
@@ -240,12 +240,14 @@ __device__ __forceinline__ void commit_sequence(const UnmaskArgs& a, int b, floa
     if (ncommit == 0) {                     // fallback: single most confident masked position
       for (int w = 1; w < THREADS / 64; ++w)
         if (best_c[w] > bc || (best_c[w] == bc && best_i[w] < bi)) { bc = best_c[w]; bi = best_i[w]; }
-      const long long pos = (long long)b * K + bi;
-      const int xhat = xhat_s[bi];
-      a.tokens[pos] = xhat;
-      a.masked[pos] = 0;
-      ncommit = 1;
-      if (a.eos_id >= 0 && xhat == a.eos_id && bc >= a.tau_eos) eos_hit = 1;
+      if (bi < K) {                         // always true with m_b > 0; no store can leave the block regardless
+        const long long pos = (long long)b * K + bi;
+        const int xhat = xhat_s[bi];
+        a.tokens[pos] = xhat;
+        a.masked[pos] = 0;
+        ncommit = 1;
+        if (a.eos_id >= 0 && xhat == a.eos_id && bc >= a.tau_eos) eos_hit = 1;
+      }
     }
     a.n_committed[b] = ncommit;
     a.block_done[b] = (m_b - ncommit == 0) ? 1 : 0;
@@ -286,9 +288,6 @@ hipError_t launch_unmask_commit(const UnmaskArgs& args, int B, hipStream_t strea
 }
 
 int unmask_splits(const sdllm_unmask_params& p) {
-  // tuning knob for sweeps: SDLLM_UNMASK_SPLITS=n forces the split count (read once)
-  static const int forced = [] { const char* e = getenv("SDLLM_UNMASK_SPLITS"); return e ? atoi(e) : 0; }();
-  if (forced >= 1 && forced <= 64) return forced;
   const int N = p.dtype == SDLLM_FP32 ? 4 : 8;
   const long long nvec = ((long long)p.V + N - 1) / N;
   // aim at >= 8 workgroups per CU over the rows, but keep >= 2 main-loop iterations per split

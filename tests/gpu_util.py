@@ -21,3 +21,16 @@ def attn_to_dev(t):
 
 def attn_to_f64(t):
     return {k: (wl.to_f64(v) if k != "keep_idx" else v) for k, v in t.items()}
+
+
+def attention_error_ratio(got, want, want_abs):
+    """Largest |got - want| over the element-wise bound that follows from the kernel's bf16 arithmetic.
+
+    The probabilities enter the P V product rounded to bf16 (relative error <= 2^-9 each) and the result is
+    rounded to bf16 once more, everything else is fp32: for output element (row, d)
+        |err| <= 2^-9 * (A + 2 |o|),   A = sum_j p_j |v_jd| / sum_j p_j,
+    (the attention output over |V|, `want_abs`: the oracle run on the absolute values of V), plus the fp32
+    accumulation, which the 5 % margin and the 1e-6 floor cover.  A key that is dropped or counted twice moves an
+    element by p_j |v_jd|, which for most d is several times this bound.  Returns the worst ratio (<= 1 passes)."""
+    bound = 2.0 ** -9 * (want_abs + 2.0 * np.abs(want)) * 1.05 + 1e-6
+    return float((np.abs(got - want) / bound).max())

@@ -20,13 +20,18 @@ def lib():
 
 
 def test_exports_every_declared_symbol(lib):
-    header = open(os.path.join(ROOT, "include", "sdllm.h")).read()
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(sdllm_[a-z0-9_]+)\s*\(", header))
+    import glob
+    declared = set()
+    for path in sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))):
+        header = re.sub(r"/\*.*?\*/", "", open(path).read(), flags=re.S)
+        declared |= set(re.findall(r"\b(sdllm_[a-z0-9_]+)\s*\(", header))
     assert declared == set(sd.EXPORTED_SYMBOLS)
     for name in declared:
         assert getattr(lib, name) is not None
-    assert lib.sdllm_version() == 100
+    assert lib.sdllm_version() == 200
+    # the method's header carries no diagnostics
+    main = open(os.path.join(ROOT, "include", "sdllm.h")).read()
+    assert "sdllm_probe_" not in re.sub(r"/\*.*?\*/", "", main, flags=re.S)
 
 
 def test_struct_layouts_match_header():
@@ -227,6 +232,32 @@ def test_rope_null_and_misaligned(lib):
     assert lib.sdllm_rope_gathered(ctypes.byref(p), *bad, None) == sd.ERR_INVALID_ARG
     assert lib.sdllm_rope_gathered(None, *ok, None) == sd.ERR_INVALID_ARG
     assert ctypes.sizeof(sd.RopeParams) == 40
+
+
+def test_validate_keep_idx_host_side(lib):
+    vp = ctypes.c_void_p
+    assert lib.sdllm_validate_keep_idx(None, 0, 10, None) == sd.SDLLM_OK            # empty list: nothing to read
+    assert lib.sdllm_validate_keep_idx(None, 3, 10, None) == sd.ERR_INVALID_ARG
+    assert lib.sdllm_validate_keep_idx(vp(4096), 11, 10, None) == sd.ERR_INVALID_ARG  # more kept rows than the suffix has
+    assert lib.sdllm_validate_keep_idx(vp(4096), -1, 10, None) == sd.ERR_INVALID_ARG
+
+
+def test_plans_do_not_depend_on_the_environment(lib):
+    """A call's launch plan is a pure function of its parameters: the tuning variables earlier builds read
+    from the environment change nothing."""
+    import subprocess, sys
+    code = ("import ctypes, paper_2601_17917_amd as sd\n"
+            "p = sd.attn_params(sd.BF16, 8, 32, 32, 128, 1024, 2048, 32, 992, 32)\n"
+            "pl = sd.plan_attention(p)\n"
+            "u = sd.unmask_params(sd.BF16, 8, 32, 126464, 126464, 0.9, 0.3)\n"
+            "print(pl.kv_splits, pl.rows_per_workgroup, pl.workgroups, sd.unmask_workspace_bytes(u))")
+    outs = []
+    for env in ({}, {"SDLLM_ATTN_RB": "2", "SDLLM_UNMASK_SPLITS": "3"}):
+        r = subprocess.run([sys.executable, "-c", code], cwd=ROOT, capture_output=True, text=True,
+                           env={**os.environ, **env})
+        assert r.returncode == 0, r.stderr
+        outs.append(r.stdout)
+    assert outs[0] == outs[1]
 
 
 def test_probe_validation(lib):

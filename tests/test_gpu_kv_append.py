@@ -43,15 +43,67 @@ def test_append_do_append_flags(gpu_lib):
     assert (_bits(kc) == want_k).all() and (_bits(vc) == want_v).all()
 
 
-def test_append_cfg5_shape_sampled(gpu_lib):
-    """Full-size launch (32 layers x 4 x 32 heads x 64 rows x 128): the oracle copy is cheap, so compare all."""
-    L, B, Hkv, D, K, cap, P = 32, 4, 32, 128, 64, 256, 128      # cap reduced; the launch geometry depends on K, not cap
-    t = wl.make_append_inputs("bf16", L, B, Hkv, D, K, cap, seed=5)
-    kc, vc, kb, vb = (to_dev(t[k]) for k in ("k_caches", "v_caches", "k_blocks", "v_blocks"))
+CANARY = 0x7FC1          # a NaN bit pattern no seeded draw produces
+
+
+def test_append_cfg5_real_capacity(gpu_lib):
+    """The long-context stack at its real size: 32 layers x 4 x 32 heads, cap = 6144 rows, P = 5120, K = 64 --
+    two 6.4 GB caches, destination offsets far beyond 4 GiB.  The caches start as a canary pattern; afterwards
+    (i) a seeded sample of (layer, batch, head) runs -- first and last of each included -- is compared with the
+    oracle on slices copied back, neighbours on both sides included; (ii) over the WHOLE cache exactly the
+    appended rows differ from the canary and they equal the blocks bit for bit."""
+    L, B, Hkv, D, K, cap, P = 32, 4, 32, 128, 64, 6144, 5120
+    t = wl.make_append_inputs("bf16", L, B, Hkv, D, K, K, seed=5)          # only the blocks are used
+    kb, vb = to_dev(t["k_blocks"]), to_dev(t["v_blocks"])
+    kc = torch.full((L, B, Hkv, cap, D), CANARY, dtype=torch.int16, device="cuda").view(torch.bfloat16)
+    vc = torch.full((L, B, Hkv, cap, D), CANARY, dtype=torch.int16, device="cuda").view(torch.bfloat16)
+    assert kc.numel() * 2 > (6 << 30)
+    gpu_lib.kv_append(kc, vc, kb, vb, P)
+    torch.cuda.synchronize()
+    rng = np.random.Generator(np.random.Philox(key=6144))
+    sample = {(0, 0, 0), (L - 1, B - 1, Hkv - 1), (L - 1, 0, 0), (0, B - 1, Hkv - 1), (21, 2, 31), (22, 0, 0)}
+    while len(sample) < 40:
+        sample.add((int(rng.integers(L)), int(rng.integers(B)), int(rng.integers(Hkv))))
+    lo, hi = P - 3, P + K + 3
+    for (l, b, h) in sorted(sample):
+        for cache, blocks, host_blocks in ((kc, kb, t["k_blocks"]), (vc, vb, t["v_blocks"])):
+            got = _bits(cache[l, b, h, lo:hi])
+            before = np.full((1, 1, 1, hi - lo, D), CANARY, dtype=np.uint16)
+            want, _ = oracle_append(before, before.copy(), host_blocks[l:l + 1, b:b + 1, h:h + 1],
+                                    host_blocks[l:l + 1, b:b + 1, h:h + 1], P - lo)
+            assert (got == want[0, 0, 0]).all(), (l, b, h)
+    for cache, blocks in ((kc, kb), (vc, vb)):
+        ci = cache.view(torch.int16)
+        assert torch.equal(ci[:, :, :, P:P + K], blocks.view(torch.int16))
+        touched = int((ci != CANARY).sum())
+        assert touched == int((blocks.view(torch.int16) != CANARY).sum()) == L * B * Hkv * K * D
+
+
+def test_append_padded_layer_strides(gpu_lib):
+    """Layers that are not densely packed: cache layers 4096 elements apart beyond the dense size, block layers
+    64 beyond.  The padding holds a canary and must be untouched; the layers themselves match the oracle."""
+    L, B, Hkv, D, K, cap, P = 3, 2, 3, 128, 32, 100, 37
+    t = wl.make_append_inputs("bf16", L, B, Hkv, D, K, cap, seed=8)
+    dense_c, dense_b = B * Hkv * cap * D, B * Hkv * K * D
+    pad_c, pad_b = 4096, 64
+    bufs = {}
+    for name, dense, pad in (("k_caches", dense_c, pad_c), ("v_caches", dense_c, pad_c),
+                             ("k_blocks", dense_b, pad_b), ("v_blocks", dense_b, pad_b)):
+        flat = torch.full((L, dense + pad), CANARY, dtype=torch.int16, device="cuda")
+        flat[:, :dense] = torch.from_numpy(t[name].view(np.int16).reshape(L, dense)).cuda()
+        bufs[name] = flat
+    def view(name, shape):
+        return bufs[name].view(torch.bfloat16)[:, :int(np.prod(shape))].unflatten(1, shape)
+
+    kc, vc = view("k_caches", (B, Hkv, cap, D)), view("v_caches", (B, Hkv, cap, D))
+    kb, vb = view("k_blocks", (B, Hkv, K, D)), view("v_blocks", (B, Hkv, K, D))
+    assert kc.stride(0) == dense_c + pad_c and kb.stride(0) == dense_b + pad_b and not kc.is_contiguous()
     gpu_lib.kv_append(kc, vc, kb, vb, P)
     torch.cuda.synchronize()
     want_k, want_v = oracle_append(t["k_caches"], t["v_caches"], t["k_blocks"], t["v_blocks"], P)
-    assert (_bits(kc) == want_k).all() and (_bits(vc) == want_v).all()
+    assert (_bits(kc.contiguous()) == want_k).all() and (_bits(vc.contiguous()) == want_v).all()
+    for name, dense in (("k_caches", dense_c), ("v_caches", dense_c), ("k_blocks", dense_b), ("v_blocks", dense_b)):
+        assert bool((bufs[name][:, dense:] == CANARY).all()), name
 
 
 def test_append_rejects_overflow(gpu_lib):

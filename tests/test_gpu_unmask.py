@@ -248,6 +248,9 @@ def test_unmask_non_finite_logits_stay_in_bounds(gpu_lib):
         assert newly.sum() == 1
         assert (got["masked"][b][masked[b] == 0] == 0).all()
     assert got["masked"][0, 0] == 0             # all-NaN sequence: the lowest masked position is taken
+    assert got["tokens"][0, 0] == 0             # a row without any finite logit commits id 0 (a valid id)
+    newly_all = (masked != 0) & (got["masked"] == 0)
+    assert ((got["tokens"][newly_all] >= 0) & (got["tokens"][newly_all] < V)).all()
     assert (got["block_done"] == 0).all()
     # the sequence with -inf entries is inside the domain: compare it with the oracle
     want = oracle_unmask(wl.to_f64(logits[2:3]), tokens[2:3], masked[2:3], 2.0, 0.0)
