@@ -169,6 +169,26 @@ int sdllm_confidence_unmask(const sdllm_unmask_params* p,
                             uint8_t* eos_seen,
                             void* workspace, size_t workspace_bytes, void* stream);
 
+/* sdllm_confidence_unmask for callers that cannot allocate device memory or carry a workspace around: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, same kernels, same
+ * results bit for bit; the per-row partial results live in a device-resident array of the library itself
+ * (SDLLM_NOALLOC_SCRATCH_BYTES, present once on every GPU the library runs on until the process ends) instead of
+ * a caller workspace.  The call allocates nothing and frees nothing.
+ *   Limit: sdllm_unmask_workspace_bytes(p) <= SDLLM_NOALLOC_SCRATCH_BYTES, else SDLLM_ERR_UNSUPPORTED (nothing is
+ *   launched).  1 MiB holds 87381 partial triples: e.g. 512 rows x 64 vocabulary splits.
+ *   All calls on one GPU share that GPU's array: calls that may overlap in time on one GPU (different streams,
+ *   different threads) race on it and must be serialised by the caller.  Nothing needs clearing between calls
+ *   (every slot that is read was written by the same call), so a smaller call after a larger one is fine.
+ * Errors: INVALID_ARG, UNSUPPORTED, HIP. */
+#define SDLLM_NOALLOC_SCRATCH_BYTES (1u << 20)
+int sdllm_confidence_unmask_noalloc(const sdllm_unmask_params* p,
+                                    const void* logits,
+                                    int32_t* tokens, uint8_t* masked,
+                                    float* confidence,
+                                    int32_t* n_committed, uint8_t* block_done,
+                                    uint8_t* eos_seen,
+                                    void* stream);
+
 /* ---------------------------------------------------------------------------------------
  * Vocabulary projection fused into the unmask.  Paper Eq. 3 produces the logits z = f_theta(x); the
  * last map of f_theta is the projection of the final hidden state onto the vocabulary,

@@ -24,6 +24,7 @@ EXPORTED_SYMBOLS = (
     "sdllm_kv_append", "sdllm_suffix_keep_indices", "sdllm_rope_gathered",
     "sdllm_probe_read", "sdllm_probe_copy", "sdllm_probe_mfma_bf16",
     "sdllm_status_string", "sdllm_last_error", "sdllm_version", "sdllm_init", "sdllm_validate_keep_idx",
+    "sdllm_confidence_unmask_noalloc",
 )
 
 
@@ -112,6 +113,8 @@ def load_library(path: Optional[str] = None):
     lib.sdllm_unmask_workspace_bytes.argtypes = [ctypes.POINTER(UnmaskParams)]
     lib.sdllm_confidence_unmask.restype = i32
     lib.sdllm_confidence_unmask.argtypes = [ctypes.POINTER(UnmaskParams)] + [vp] * 7 + [vp, sz, vp]
+    lib.sdllm_confidence_unmask_noalloc.restype = i32
+    lib.sdllm_confidence_unmask_noalloc.argtypes = [ctypes.POINTER(UnmaskParams)] + [vp] * 7 + [vp]
     lib.sdllm_lm_head_unmask_workspace_bytes.restype = sz
     lib.sdllm_lm_head_unmask_workspace_bytes.argtypes = [ctypes.POINTER(LmHeadParams)]
     lib.sdllm_plan_lm_head.restype = i32
@@ -305,6 +308,41 @@ def bind_confidence_unmask(logits, tokens, masked, tau0: float, alpha: float, V:
             _ptr(block_done), _ptr(eos_seen), _ptr(workspace), ws_bytes, _stream(stream))
     keep = (p, logits, tokens, masked, confidence, n_committed, block_done, eos_seen, workspace)
     return BoundCall(load_library().sdllm_confidence_unmask, args, keep, (n_committed, block_done))
+
+
+NOALLOC_SCRATCH_BYTES = 1 << 20
+
+
+def confidence_unmask_noalloc(*args, **kw):
+    """sdllm_confidence_unmask_noalloc: same operation and results as confidence_unmask; the partial results live in
+    the library's own device-resident scratch (no workspace, nothing allocated by the call when n_committed and
+    block_done are passed).  Signature: see bind_confidence_unmask_noalloc."""
+    return bind_confidence_unmask_noalloc(*args, **kw)()
+
+
+def bind_confidence_unmask_noalloc(logits, tokens, masked, tau0: float, alpha: float, V: Optional[int] = None,
+                                   confidence=None, n_committed=None, block_done=None, eos_seen=None, eos_id: int = -1,
+                                   tau_eos: Optional[float] = None, r_extra_masked: int = 0, r_extra_total: int = 0,
+                                   stream=None) -> BoundCall:
+    import torch
+    B, K, ld = logits.shape
+    V = ld if V is None else V
+    _require(logits, "logits")
+    _require(tokens, "tokens", torch.int32)
+    _require(masked, "masked", torch.uint8)
+    _require(confidence, "confidence", torch.float32)
+    _require(eos_seen, "eos_seen", torch.uint8)
+    if n_committed is None:
+        n_committed = torch.empty((B,), dtype=torch.int32, device=logits.device)
+    if block_done is None:
+        block_done = torch.empty((B,), dtype=torch.uint8, device=logits.device)
+    _require(n_committed, "n_committed", torch.int32)
+    _require(block_done, "block_done", torch.uint8)
+    p = unmask_params(_dtype_code(logits), B, K, V, ld, tau0, alpha, r_extra_masked, r_extra_total, eos_id, tau_eos)
+    args = (ctypes.byref(p), _ptr(logits), _ptr(tokens), _ptr(masked), _ptr(confidence), _ptr(n_committed),
+            _ptr(block_done), _ptr(eos_seen), _stream(stream))
+    keep = (p, logits, tokens, masked, confidence, n_committed, block_done, eos_seen)
+    return BoundCall(load_library().sdllm_confidence_unmask_noalloc, args, keep, (n_committed, block_done))
 
 
 # ---------------------------------------------------------------------------------------------

@@ -6,6 +6,7 @@
 #include <cstring>
 #include <cmath>
 #include <vector>
+#include <atomic>
 
 namespace {
 
@@ -134,6 +135,30 @@ int check_rope_params(const sdllm_rope_params* p) {
   return SDLLM_OK;
 }
 
+// ---- the device-resident scratch of sdllm_confidence_unmask_noalloc.  Every GPU the library runs on holds its
+// own copy of the array at its own address; in host code the array's name is only a handle for the symbol
+// lookup, never an address: the per-device address found below is what kernels and runtime calls are given.
+static __device__ __align__(256) unsigned char scratch[SDLLM_NOALLOC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+hipError_t scratch_of_current_device(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (ptr == nullptr) {                      // first use on this device (two threads may both look it up: same answer)
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (ptr == nullptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+  }
+  *out = ptr;
+  return hipSuccess;
+}
+
 }  // namespace
 
 extern "C" {
@@ -143,6 +168,8 @@ int sdllm_version(void) { return SDLLM_VERSION; }
 int sdllm_init(void) {
   hipError_t e = sdllm::prepare_attention_bf16();
   if (e == hipSuccess) e = sdllm::prepare_lm_head();
+  void* ptr = nullptr;
+  if (e == hipSuccess) e = scratch_of_current_device(&ptr);
   if (e != hipSuccess) return fail(SDLLM_ERR_HIP, "init: %s", hipGetErrorString(e));
   return SDLLM_OK;
 }
@@ -273,6 +300,27 @@ int sdllm_confidence_unmask(const sdllm_unmask_params* p, const void* logits,
   hipError_t e = sdllm::launch_unmask(*p, logits, tokens, masked, confidence, n_committed, block_done, eos_seen,
                                       workspace, (hipStream_t)stream);
   if (e != hipSuccess) return fail(SDLLM_ERR_HIP, "unmask: %s", hipGetErrorString(e));
+  return SDLLM_OK;
+}
+
+int sdllm_confidence_unmask_noalloc(const sdllm_unmask_params* p, const void* logits,
+                                    int32_t* tokens, uint8_t* masked, float* confidence,
+                                    int32_t* n_committed, uint8_t* block_done, uint8_t* eos_seen, void* stream) {
+  int rc = check_unmask_params(p);
+  if (rc != SDLLM_OK) return rc;
+  if (!logits || !tokens || !masked || !n_committed || !block_done)
+    return fail(SDLLM_ERR_INVALID_ARG, "unmask_noalloc: logits, tokens, masked, n_committed, block_done must not be NULL");
+  if (!aligned16(logits)) return fail(SDLLM_ERR_INVALID_ARG, "unmask_noalloc: logits is not 16-byte aligned");
+  const size_t need = sdllm::unmask_workspace_bytes(*p);
+  if (need > (size_t)SDLLM_NOALLOC_SCRATCH_BYTES)
+    return fail(SDLLM_ERR_UNSUPPORTED, "unmask_noalloc: %zu bytes of partial results exceed the library's %u-byte scratch "
+                "(B*K = %lld rows); use sdllm_confidence_unmask with a workspace", need,
+                (unsigned)SDLLM_NOALLOC_SCRATCH_BYTES, (long long)p->B * p->K);
+  void* ptr = nullptr;
+  hipError_t e = scratch_of_current_device(&ptr);
+  if (e != hipSuccess) return fail(SDLLM_ERR_HIP, "unmask_noalloc: scratch lookup: %s", hipGetErrorString(e));
+  e = sdllm::launch_unmask(*p, logits, tokens, masked, confidence, n_committed, block_done, eos_seen, ptr, (hipStream_t)stream);
+  if (e != hipSuccess) return fail(SDLLM_ERR_HIP, "unmask_noalloc: %s", hipGetErrorString(e));
   return SDLLM_OK;
 }
 

@@ -260,6 +260,23 @@ def test_plans_do_not_depend_on_the_environment(lib):
     assert outs[0] == outs[1]
 
 
+def test_noalloc_unmask_validates_and_rejects_sizes_beyond_its_scratch(lib):
+    """The entry point that allocates nothing checks everything on the host before any HIP call: the same argument
+    rules as sdllm_confidence_unmask, plus the limit of its device-resident scratch."""
+    vp = ctypes.c_void_p
+    ok = sd.unmask_params(sd.BF16, 8, 32, 126464, 126464, 0.9, 0.3)
+    assert lib.sdllm_unmask_workspace_bytes(ctypes.byref(ok)) <= sd.NOALLOC_SCRATCH_BYTES
+    args = [vp(4096), vp(4096), vp(4096), None, vp(4096), vp(4096), None, None]
+    bad = list(args); bad[0] = None
+    assert lib.sdllm_confidence_unmask_noalloc(ctypes.byref(ok), *bad) == sd.ERR_INVALID_ARG      # logits NULL
+    bad = list(args); bad[0] = vp(4104)
+    assert lib.sdllm_confidence_unmask_noalloc(ctypes.byref(ok), *bad) == sd.ERR_INVALID_ARG      # misaligned logits
+    big = sd.unmask_params(sd.BF16, 64, 4096, 126464, 126464, 0.9, 0.3)       # 262144 rows: more triples than 1 MiB holds
+    assert lib.sdllm_unmask_workspace_bytes(ctypes.byref(big)) > sd.NOALLOC_SCRATCH_BYTES
+    assert lib.sdllm_confidence_unmask_noalloc(ctypes.byref(big), *args) == sd.ERR_UNSUPPORTED
+    assert b"scratch" in lib.sdllm_last_error()
+
+
 def test_probe_validation(lib):
     vp = ctypes.c_void_p
     assert lib.sdllm_probe_read(vp(4096), 0, vp(4096), None) == sd.ERR_INVALID_ARG
