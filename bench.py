@@ -9,7 +9,9 @@ figures of the dominant kernel (HIP events inside the timed region) and the CPU 
 this machine's host cores as a baseline.  Outside the timed step it also reports per-kernel timings, the fused
 vocabulary projection + unmask call, and what plain read / copy / matrix-instruction kernels reach on the box.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5] [--graph]
+
+The default workload is the largest single-GPU one: the 32-layer long-context stack (cfg5).
 """
 from __future__ import annotations
 
@@ -28,6 +30,9 @@ import workloads as wl  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+# vector-ALU issue slots the unmask rows kernel spends per logit (from its instruction mix per 32 logits of a lane:
+# see the kernel's header comment), v_exp_f32 weighted 2.4
+UNMASK_VALU_SLOTS_PER_ELEMENT = {"bf16": (164 + 33 * 2.4) / 32.0, "fp32": (132 + 33 * 2.4) / 32.0}
 
 
 def parse_args():
@@ -35,14 +40,18 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--workload", default="cfg2", choices=[k for k in wl.WORKLOADS if k != "small_bf16"])
+    ap.add_argument("--workload", default="cfg5", choices=[k for k in wl.WORKLOADS if k != "small_bf16"])
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="leave the per-kernel HIP events out of the timed region (roofline.achieved = null)")
-    ap.add_argument("--event-every", type=int, default=8,
-                    help="bracket the dominant kernel with HIP events on every n-th timed step (an event pair costs "
-                         "about as much as a small kernel, so bracketing every step would distort the step time)")
+    ap.add_argument("--event-every", type=int, default=0,
+                    help="bracket the calls of a step with HIP events on every n-th timed step (0 = every step for the "
+                         "multi-layer stack, whose step is milliseconds long; every 8th for the single-layer workloads, "
+                         "where an event costs about as much as a small kernel and would distort the step time)")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the step (state restore + every call) as ONE captured HIP graph instead of launching it "
+                         "eagerly; the JSON line then describes the graph replays (per-call events are not taken)")
     ap.add_argument("--no-lm-head", action="store_true",
                     help="skip the per-kernel figure of the fused vocabulary projection + unmask (it draws the "
                          "V x Hd projection, about 1 GB, on the device)")
@@ -116,18 +125,36 @@ class Step:
             self.k_blocks, self.v_blocks = t["k_block"][None], t["v_block"][None]
 
         # marshal every call once: in the loop a call is one foreign-function call
-        nk = w.n_keep
-        self.attention = [sd.bind_block_attention(
-            t["q_block"], t["q_suffix"] if nk else None, t["k_cache"], t["v_cache"], t["k_block"], t["v_block"],
-            t["k_suffix"] if nk else None, t["v_suffix"] if nk else None, t["keep_idx"] if nk else None, w.P,
-            out=self.out, kv_splits=kv_splits, workspace=self.attn_ws) for t in self.layers]
-        self.unmask = [sd.bind_confidence_unmask(
-            self.logits, self.tokens[i], self.masked[i], w.tau0, w.alpha, n_committed=self.n_committed[i],
-            block_done=self.block_done[i], eos_seen=self.eos_seen, workspace=self.unmask_ws) for i in range(n_states)]
+        self.kv_splits = kv_splits
+        self.attention = self._bind_attention(None)
+        self.unmask = [self._bind_unmask(i, None) for i in range(n_states)]
         self.append = sd.bind_kv_append(self.k_caches, self.v_caches, self.k_blocks, self.v_blocks, w.P)
         torch.cuda.synchronize()
 
+    def _bind_attention(self, stream):
+        sd, w, nk = self.sd, self.w, self.w.n_keep
+        return [sd.bind_block_attention(
+            t["q_block"], t["q_suffix"] if nk else None, t["k_cache"], t["v_cache"], t["k_block"], t["v_block"],
+            t["k_suffix"] if nk else None, t["v_suffix"] if nk else None, t["keep_idx"] if nk else None, w.P,
+            out=self.out, kv_splits=self.kv_splits, workspace=self.attn_ws, stream=stream) for t in self.layers]
+
+    def _bind_unmask(self, i, stream):
+        sd, w = self.sd, self.w
+        return sd.bind_confidence_unmask(
+            self.logits, self.tokens[i], self.masked[i], w.tau0, w.alpha, n_committed=self.n_committed[i],
+            block_done=self.block_done[i], eos_seen=self.eos_seen, workspace=self.unmask_ws, stream=stream)
+
+    def bind_on(self, stream):
+        """The calls of one step on state slot 0, bound to `stream` (for stream capture)."""
+        attn = self._bind_attention(stream)
+        attn = attn[:1] if self.w.n_layers == 1 else attn
+        return attn + [self._bind_unmask(0, stream),
+                       self.sd.bind_kv_append(self.k_caches, self.v_caches, self.k_blocks, self.v_blocks, self.w.P,
+                                              stream=stream)]
+
     def run(self, i: int, events=None):
+        """One step on state slot i.  `events`: five HIP events recorded on the launch stream around the layer-0
+        attention call, the remaining layers, the unmask call and the append call."""
         if self.w.n_layers == 1:
             calls = (self.attention[i % self.copies],)
         else:
@@ -138,11 +165,16 @@ class Step:
             events[1].record()
             for call in calls[1:]:
                 call()
+            events[2].record()
+            self.unmask[i]()
+            events[3].record()
+            self.append()
+            events[4].record()
         else:
             for call in calls:
                 call()
-        self.unmask[i]()
-        self.append()
+            self.unmask[i]()
+            self.append()
 
 
 def time_kernel(fn, iters=50, warm=5):
@@ -157,6 +189,23 @@ def time_kernel(fn, iters=50, warm=5):
     e1.record()
     torch.cuda.synchronize()
     return e0.elapsed_time(e1) / iters     # ms per call, back-to-back launches
+
+
+def time_call_with_events(prepare, call, iters=50, warm=5):
+    """Mean HIP-event time (ms) of `call()` alone: `prepare()` (untimed; e.g. restoring the state the call
+    mutates) runs before every call, the event pair brackets only the call on the stream it is launched on."""
+    import torch
+    pairs = []
+    for it in range(warm + iters):
+        prepare()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        call()
+        e1.record()
+        if it >= warm:
+            pairs.append((e0, e1))
+    torch.cuda.synchronize()
+    return float(np.mean([a.elapsed_time(b) for a, b in pairs]))
 
 
 def cpu_baseline(w: wl.Workload, seed: int):
@@ -208,6 +257,19 @@ def cpu_baseline(w: wl.Workload, seed: int):
     rows_s = int((u["masked"][:b_u] != 0).sum())
     t_unmask = t_unmask_sample * masked_rows / max(rows_s, 1)
     committed_s = int(res["n_committed"].sum())
+    # exclusion counts of the parity rule on the sampled sequences (the oracle's view): positions whose top-2
+    # probability gap is under 1e-3, positions within 1e-3 of the threshold, sequences whose fallback is ambiguous
+    was = u["masked"][:b_u] != 0
+    n_gap = int((np.nan_to_num(res["gap"], nan=1.0)[was] < 1e-3).sum())
+    band = was & (np.abs(np.nan_to_num(res["confidence"]) - np.nan_to_num(res["tau"])[:, None]) < 1e-3)
+    n_amb = 0
+    for b in range(b_u):
+        c = np.sort(res["confidence"][b][was[b]])[::-1]
+        if res["fallback"][b] and c.size > 1 and (c[0] - c[1]) <= 1e-6 * c[0]:
+            n_amb += 1
+    exclusions = {"sequences_checked": b_u, "masked_positions_checked": int(was.sum()), "top2_gap_lt_1e-3": n_gap,
+                  "within_1e-3_of_threshold": int(band.sum()), "fallback_ambiguous_sequences": n_amb,
+                  "oracle_tokens": res["tokens"], "oracle_masked": res["masked"], "band": band}
     note.append(f"unmask: {b_u} of {w.B} sequences ({rows_s} of {masked_rows} masked rows)" + (", scaled" if b_u < w.B else ""))
     # --- append: one layer, scaled
     a = wl.make_append_inputs(w.dtype, 1, w.B, w.Hkv, w.D, w.K, w.P + w.K, seed)
@@ -218,7 +280,7 @@ def cpu_baseline(w: wl.Workload, seed: int):
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     return {"t_step_s": t_attn + t_unmask + t_append, "t_attention_s": t_attn, "t_unmask_s": t_unmask,
             "t_append_s": t_append, "cores": threads, "sample": "; ".join(note),
-            "committed_sample": committed_s, "b_u": b_u}
+            "committed_sample": committed_s, "b_u": b_u, "exclusions": exclusions}
 
 
 def main():
@@ -237,19 +299,46 @@ def main():
     K, W = args.steps, args.warmup
     st = Step(sd, w, args.seed, K + W, args.kv_splits, args.kv_copies)
 
-    for i in range(W):
-        st.run(i)
-    torch.cuda.synchronize()
-    use_ev = not args.no_kernel_events
-    every = max(1, args.event_every)
-    evs = {i: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-           for i in range(0, K, every)} if use_ev else {}
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(K):
-        st.run(W + i, evs.get(i))
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    sd.init()                             # every kernel opt-in done: the calls below only launch
+    use_ev = not args.no_kernel_events and not args.graph
+    every = args.event_every if args.event_every > 0 else (1 if w.n_layers > 1 else 8)
+    if args.graph:
+        # the whole step as one graph: restore the state slot the unmask mutates (two small copy kernels), then
+        # every call.  All replays work on slot 0, so every replay does the same work.
+        tok0, msk0 = st.tokens[0].clone(), st.masked[0].clone()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            calls = st.bind_on(side)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            graph.capture_begin()
+            st.tokens[0].copy_(tok0); st.masked[0].copy_(msk0)
+            for call in calls:
+                call()
+            graph.capture_end()
+        torch.cuda.synchronize()
+        for i in range(W):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(K):
+            graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        st.n_committed[W:] = st.n_committed[0]
+        evs = {}
+    else:
+        for i in range(W):
+            st.run(i)
+        torch.cuda.synchronize()
+        evs = {i: [torch.cuda.Event(enable_timing=True) for _ in range(5)] for i in range(0, K, every)} if use_ev else {}
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(K):
+            st.run(W + i, evs.get(i))
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / K
 
     committed = st.n_committed[W:].sum(dim=1).cpu().numpy()
@@ -258,7 +347,10 @@ def main():
     value = committed_per_step / (ms_per_step * 1e-3)
 
     # ---- dominant kernel: the attention call of layer 0 (main kernel + split merge), events inside the timed region
-    attn_ms_ev = float(np.mean([a.elapsed_time(b) for a, b in evs.values()])) if use_ev else None
+    def ev_mean(a, b):
+        return float(np.mean([e[a].elapsed_time(e[b]) for e in evs.values()])) if use_ev else None
+
+    attn_ms_ev, unmask_ms_ev, append_ms_ev = ev_mean(0, 1), ev_mean(2, 3), ev_mean(3, 4)
     attn_bytes = w.attn_bytes()
     attn_flops = w.attn_flops()
     intensity = attn_flops / attn_bytes
@@ -272,18 +364,13 @@ def main():
         rot[0] += 1
 
     t_attn = time_kernel(attention_rotating)
-    fresh = (st.tokens[0].clone(), st.masked[0].clone())
+    # the unmask call alone: HIP events around the real call, the state slot restored (untimed) before every call
+    tok_fresh, msk_fresh = to_dev(st.host_unmask["tokens"]), to_dev(st.host_unmask["masked"])
 
-    def unmask_fresh():                                 # restore the state slot, then unmask it again
-        st.tokens[1].copy_(fresh[0]); st.masked[1].copy_(fresh[1])
-        st.unmask[1]()
+    def restore_slot():
+        st.tokens[1].copy_(tok_fresh); st.masked[1].copy_(msk_fresh)
 
-    def restore_only():
-        st.tokens[1].copy_(fresh[0]); st.masked[1].copy_(fresh[1])
-
-    st.tokens[0].copy_(to_dev(st.host_unmask["tokens"])); st.masked[0].copy_(to_dev(st.host_unmask["masked"]))
-    fresh = (st.tokens[0].clone(), st.masked[0].clone())
-    t_unm = time_kernel(unmask_fresh) - time_kernel(restore_only)
+    t_unm = time_call_with_events(restore_slot, st.unmask[1])
     t_app = time_kernel(st.append)
     # RoPE of the pruned q and k rows (the step before the attention call; NOT part of the timed step):
     # in place on copies, q and k back to back
@@ -331,12 +418,7 @@ def main():
 
         def time_lm(weight):
             lm_call = sd.bind_lm_head_unmask(lm["hidden"], weight, tok, msk, w.tau0, w.alpha)
-
-            def lm_fresh():
-                tok.copy_(tok0); msk.copy_(msk0)
-                lm_call()
-
-            t_lm = time_kernel(lm_fresh, iters=20) - time_kernel(lm_restore, iters=20)
+            t_lm = time_call_with_events(lm_restore, lm_call, iters=20)
             return {"ms": t_lm, "gbs": lm_bytes / t_lm / 1e6, "frac_hbm_peak": lm_bytes / t_lm / 1e6 / HBM_PEAK_GBS,
                     "tflops": lm_flops / t_lm / 1e9, "frac_mfma_peak": lm_flops / t_lm / 1e9 / MFMA_BF16_PEAK_TFLOPS,
                     "masked_rows": lm_rows, "hidden": w.Hd, "in_timed_step": False}
@@ -371,21 +453,48 @@ def main():
         ach = attn_flops / dur / 1e9 if dur else None
         roof = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": ach / MFMA_BF16_PEAK_TFLOPS if ach else None, "traffic": None}
-    # HBM traffic of the same call measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, scaled by what
-    # the counters read for the kv_append copy of known size); stored with its provenance under profiles/
+    # HBM traffic of the same call from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, scaled by what the
+    # counters read for the kv_append copy of known size): read from the committed profile, NOT measured in this run
     try:
         with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
-            tr = json.load(f)["workloads"].get(w.name)
+            prof = json.load(f)
+        tr = prof["workloads"].get(w.name)
         if tr is not None:
             roof["traffic"] = tr["attention_call_bytes"]
             roof["traffic_unit"] = "bytes per launch (read + write, main kernel + split merge)"
+            roof["traffic_source"] = ("profiles/hbm_traffic.json (rocprofv3 --pmc runs of this bench, "
+                                      f"{prof.get('measured_with', 'kernels as committed with the file')}); "
+                                      "not measured in this run")
     except (OSError, KeyError, ValueError):
         pass
     roof["measured_ceiling"] = ceilings["read_gbs"] if bound == "hbm" else ceilings["mfma_bf16_tflops_random_operands"]
     roof["frac_of_measured_ceiling"] = (roof["achieved"] / roof["measured_ceiling"]) if roof["achieved"] else None
-    roof.update({"kernel": "sdllm_block_attention (attn_bf16_kernel + attn_combine_kernel)" if w.dtype == "bf16"
+    roof.update({"kernel": "sdllm_block_attention, one layer (attn_bf16_kernel + attn_combine_kernel)" if w.dtype == "bf16"
                  else "sdllm_block_attention (attention_f32_kernel)",
-                 "launch_ms": dur, "algorithmic_bytes": attn_bytes, "algorithmic_flops": attn_flops})
+                 "launch_ms": dur, "algorithmic_bytes": attn_bytes, "algorithmic_flops": attn_flops,
+                 "frac_mfma_peak": (attn_flops / dur / 1e9 / MFMA_BF16_PEAK_TFLOPS) if dur and w.dtype == "bf16" else None,
+                 "events": f"HIP events around the layer-0 call on {len(evs)} of {K} timed steps" if use_ev else None})
+    # the other two calls of the step, each bracketed by HIP events inside the timed region (same steps)
+    elems = masked_rows * w.V
+    # plain-ALU roof of the row reduction: vector-ALU issue slots per logit (a wave-wide instruction occupies its
+    # SIMD for 4 cycles; v_exp_f32 is counted at the 2.4 slots it measures against an FMA on this chip) over
+    # 256 CUs x 4 SIMDs at 2.4 GHz
+    slots = UNMASK_VALU_SLOTS_PER_ELEMENT[w.dtype]
+    alu_ms = elems * slots / 64.0 * 4.0 / (256 * 4 * 2.4e9) * 1e3
+    others = []
+    if unmask_ms_ev:
+        g = unmask_bytes / unmask_ms_ev / 1e6
+        others.append({"kernel": "sdllm_confidence_unmask (unmask_rows_kernel + unmask_commit_kernel)", "bound": "hbm",
+                       "achieved": g, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": g / HBM_PEAK_GBS,
+                       "launch_ms": unmask_ms_ev, "algorithmic_bytes": unmask_bytes, "masked_rows": masked_rows,
+                       "alu_roof": {"valu_slots_per_logit": slots, "logits": elems, "roof_ms": alu_ms,
+                                    "frac_of_alu_roof": alu_ms / unmask_ms_ev}})
+    if append_ms_ev:
+        g = append_bytes / append_ms_ev / 1e6
+        others.append({"kernel": "sdllm_kv_append (kv_append_kernel, all layers, K and V)", "bound": "hbm",
+                       "achieved": g, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": g / HBM_PEAK_GBS,
+                       "launch_ms": append_ms_ev, "algorithmic_bytes": append_bytes})
+    roof["others"] = others
 
     out = {
         "metric": "committed tokens/sec per decode step", "value": value, "unit": "tokens/s",
@@ -393,7 +502,9 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} Hq/Hkv={w.Hq}/{w.Hkv} D={w.D} P={w.P} K={w.K} S={w.S} kept={w.n_keep} "
                                f"V={w.V} layers={w.n_layers} tau0={w.tau0} alpha={w.alpha}",
-                   "committed_tokens_per_step": committed_per_step, "seed": args.seed},
+                   "committed_tokens_per_step": committed_per_step, "seed": args.seed,
+                   "launch": "one captured HIP graph per step (state restore + every call)" if args.graph
+                   else "eager, pre-marshalled C-ABI calls"},
         "roofline": roof,
         "kernels": kernels,
         "device_ceilings": ceilings,
@@ -401,6 +512,15 @@ def main():
     if not args.no_cpu_baseline:
         cb = cpu_baseline(w, args.seed)
         # committed tokens per step are the same on both sides (checked by the parity tests)
+        ex = cb["exclusions"]
+        # the first timed step's state against the oracle on the sampled sequences (positions in the threshold band
+        # excluded, as the parity rule says)
+        b_u, keep = ex["sequences_checked"], ~ex.pop("band")
+        slot = 0 if args.graph else W
+        got_t, got_m = st.tokens[slot, :b_u].cpu().numpy(), st.masked[slot, :b_u].cpu().numpy()
+        ex["gpu_matches_oracle_outside_band"] = bool((got_t[keep] == ex.pop("oracle_tokens")[keep]).all()
+                                                     and (got_m[keep] == ex.pop("oracle_masked")[keep]).all())
+        out["exclusions"] = ex
         out["cpu_baseline"] = {"value": committed_per_step / cb["t_step_s"], "unit": "tokens/s", "cores": cb["cores"],
                                "kind": "oracle", "sample": cb["sample"], "step_seconds": cb["t_step_s"],
                                "attention_s": cb["t_attention_s"], "unmask_s": cb["t_unmask_s"], "append_s": cb["t_append_s"]}

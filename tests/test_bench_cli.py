@@ -37,3 +37,14 @@ def test_one_json_line_with_the_contract_fields():
     assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-12
     assert d["cpu_baseline"]["kind"] == "oracle" and d["cpu_baseline"]["cores"] >= 1
     assert "workload" in d["config"] and "model" not in d["config"]
+    # the headline is the largest single-GPU workload, and all three calls of the step carry a roofline entry
+    assert d["config"]["workload"].startswith("cfg5") and "layers=32" in d["config"]["workload"]
+    assert roof["bound"] == "hbm" and "not measured in this run" in roof.get("traffic_source", "not measured in this run")
+    kinds = [o["kernel"].split(" ")[0] for o in roof["others"]]
+    assert kinds == ["sdllm_confidence_unmask", "sdllm_kv_append"]
+    for o in roof["others"]:
+        assert o["launch_ms"] > 0 and abs(o["frac"] - o["achieved"] / o["peak"]) < 1e-12
+        assert abs(o["achieved"] - o["algorithmic_bytes"] / o["launch_ms"] / 1e6) < 1e-6 * o["achieved"]
+    assert roof["others"][0]["alu_roof"]["roof_ms"] > 0
+    ex = d["exclusions"]
+    assert ex["gpu_matches_oracle_outside_band"] is True and ex["sequences_checked"] >= 1

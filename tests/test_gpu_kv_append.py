@@ -57,7 +57,7 @@ def test_append_cfg5_real_capacity(gpu_lib):
     kb, vb = to_dev(t["k_blocks"]), to_dev(t["v_blocks"])
     kc = torch.full((L, B, Hkv, cap, D), CANARY, dtype=torch.int16, device="cuda").view(torch.bfloat16)
     vc = torch.full((L, B, Hkv, cap, D), CANARY, dtype=torch.int16, device="cuda").view(torch.bfloat16)
-    assert kc.numel() * 2 > (6 << 30)
+    assert kc.numel() * 2 >= (6 << 30)          # offsets far beyond 4 GiB
     gpu_lib.kv_append(kc, vc, kb, vb, P)
     torch.cuda.synchronize()
     rng = np.random.Generator(np.random.Philox(key=6144))
