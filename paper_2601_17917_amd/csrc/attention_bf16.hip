@@ -20,6 +20,7 @@
 //   Online softmax in the log2 domain; a split writes (unnormalised O, m, l) and a second
 //   kernel merges the splits in a fixed order (deterministic, no atomics).
 #include "common.h"
+#include <type_traits>
 
 namespace sdllm {
 
@@ -30,6 +31,8 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 constexpr int kKeyTile = 64;
+constexpr int kDeepStages = 3;    // ring depth of the launches that have one workgroup per CU ...
+constexpr bool kTwoGroups = true; // ... unless they run two 4-wave groups per workgroup
 constexpr float kLog2eA = 1.4426950408889634f;
 constexpr float kNegBigA = -3.0e38f;
 
@@ -131,8 +134,9 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
-// Compile-time shape constants shared by the helpers below
-template <int D> struct Shape {
+// Compile-time shape constants shared by the helpers below (NST = stages of the K/V ring in LDS; NG = 4-wave
+// groups of the workgroup, each of which has a key tile of its own in every stage)
+template <int D, int NST = 2, int NG = 1> struct Shape {
   static constexpr int CPR = D / 8;                // 16-byte chunks per row
   static constexpr int RPI = 64 / CPR;             // rows covered by one wave-wide transfer
   static constexpr int IPT = 16 / RPI;             // transfers per wave per tile per tensor (a wave loads 16 rows)
@@ -141,11 +145,15 @@ template <int D> struct Shape {
   static constexpr int NDB = D / 16;               // 16-wide d blocks of the output
   static constexpr int ROWB = D * 2;               // bytes per row
   static constexpr int TILEB = kKeyTile * ROWB;    // bytes per tile per tensor
-  // LDS: [K stage 0][K stage 1][V stage 0][V stage 1]; a stage offset (TILEB) plus any row offset
-  // of a tile fits the 16-bit immediate of a DS instruction, so a lane needs one base register
-  // per d slice / d block and no address arithmetic inside the loop.
-  static constexpr int VBASE = 2 * TILEB;
-  static constexpr int LDS_BYTES = 4 * TILEB;
+  static constexpr int STAGEB = NG * TILEB;        // bytes per ring stage per tensor
+  // LDS: [K stage 0] .. [K stage NST-1][V stage 0] .. [V stage NST-1], a stage = the groups' tiles one after the
+  // other; a stage offset plus any row offset of a tile fits the 16-bit immediate of a DS instruction, so a lane
+  // needs one base register per d slice / d block and no address arithmetic inside the loop.
+  static constexpr int VBASE = NST * STAGEB;
+  static constexpr int LDS_BYTES = 2 * NST * STAGEB;
+  static_assert(NST >= 2 && NST <= 4 && (NG == 1 || NG == 2), "ring stages, wave groups");
+  static_assert((NST - 1) * STAGEB + kKeyTile * ROWB <= 65536, "stage offset as a DS immediate");
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS of a CU");
 };
 
 // Per-lane constants of the K/V stream
@@ -154,7 +162,7 @@ template <int D> struct Lane {
   // dma_slab); entries past IPT unused
   unsigned kgj[4], vgj[4];
   unsigned kro[Shape<D>::NS], vro[Shape<D>::NDB];  // LDS read bases (bytes), before compile-time offsets
-  unsigned lds_base; int wave, lane, G;
+  unsigned lds_base; int wave, grp, lane, G;        // wave: index within its 4-wave group; grp: the group
 };
 
 typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;   // scalar (constant-cache) loads
@@ -191,9 +199,9 @@ __device__ __forceinline__ SlabRanges slab_ranges(const AttnArgs& a, int wave) {
 // 16 consecutive rows of one source tensor starting at source row `row0`: scalar bases, the lane's
 // constant offsets, no per-lane address arithmetic.  The lane offsets kgj / vgj count rows from the
 // start of the tile, hence the step back by the wave's 16*wave rows.
-template <int D, bool ONCE>
+template <int D, bool ONCE, int NST, int NG>
 __device__ __forceinline__ void issue_slab(const Lane<D>& L, unsigned sk, const uint16_t* kp, const uint16_t* vp, long long row0) {
-  using S = Shape<D>;
+  using S = Shape<D, NST, NG>;
   const unsigned char* kt = reinterpret_cast<const unsigned char*>(kp) + (row0 - 16 * L.wave) * S::ROWB;
   const unsigned char* vt = reinterpret_cast<const unsigned char*>(vp) + (row0 - 16 * L.wave) * S::ROWB;
   static_assert(S::RPI * S::ROWB == 1024, "a transfer moves 1 KiB");
@@ -201,27 +209,27 @@ __device__ __forceinline__ void issue_slab(const Lane<D>& L, unsigned sk, const 
   dma_slab<S::IPT, ONCE>(sk + S::VBASE, vt, L.vgj);
 }
 
-// Puts key tile `tile` in flight into ring stage `stage`: 2 * IPT transfers per wave, which moves
-// rows 16*wave .. 16*wave+15 of the tile.  `ka` holds the keep_idx bounds of these rows on entry and
-// those of the next tile on return.
-template <int D, bool ONCE>
+// Puts key tile `tile` (a tile of this wave's group) in flight into the group's part of ring stage `stage`:
+// 2 * IPT transfers per wave, which moves rows 16*wave .. 16*wave+15 of the tile.  `ka` holds the keep_idx
+// bounds of these rows on entry and those of the group's next tile (tile + NG) on return.
+template <int D, bool ONCE, int NST, int NG>
 __device__ __forceinline__ void issue_tile(const AttnArgs& a, const Lane<D>& L, const SlabRanges& R,
                                            const uint16_t* kc, const uint16_t* vc,
                                            const uint16_t* kb, const uint16_t* vb, const uint16_t* ks, const uint16_t* vs,
                                            int tile, int stage, KeepAhead& ka) {
-  using S = Shape<D>;
-  const unsigned sk = L.lds_base + stage * S::TILEB + 16 * L.wave * S::ROWB;
+  using S = Shape<D, NST, NG>;
+  const unsigned sk = L.lds_base + stage * S::STAGEB + L.grp * S::TILEB + 16 * L.wave * S::ROWB;
   const unsigned sv = sk + S::VBASE;
   const int r0 = tile * kKeyTile + 16 * L.wave;    // uniform: first of the wave's 16 rows
   // Uniform classification of the wave's slab.  Sixteen consecutive rows of one source tensor (the
   // cache, the block, or a run of the suffix that keep_idx maps to consecutive rows: increasing
   // indices whose ends differ by 15) are one contiguous slab.
   if (tile <= R.tc) {
-    issue_slab<D, ONCE>(L, sk, kc, vc, r0);
+    issue_slab<D, ONCE, NST, NG>(L, sk, kc, vc, r0);
   } else if (tile >= R.tb0 && tile <= R.tb1) {
-    issue_slab<D, ONCE>(L, sk, kb, vb, r0 - a.P);
+    issue_slab<D, ONCE, NST, NG>(L, sk, kb, vb, r0 - a.P);
   } else if (tile >= R.ts0 && tile <= R.ts1 && ka.last - ka.first == 15) {
-    issue_slab<D, ONCE>(L, sk, ks, vs, ka.first);
+    issue_slab<D, ONCE, NST, NG>(L, sk, ks, vs, ka.first);
   } else {
     // rows from more than one place, a gap in keep_idx, the ragged tail: per-row addresses without a
     // divergent branch.  keep_idx is read through the constant address space with uniform indices
@@ -262,28 +270,28 @@ __device__ __forceinline__ void issue_tile(const AttnArgs& a, const Lane<D>& L, 
 #pragma unroll
     for (int j = 0; j < S::IPT; ++j) dma16_vaddr<ONCE>(sv + j * S::RPI * S::ROWB, vpp[j]);
   }
-  load_keep_ahead(a, L.wave, tile + 1, ka);
+  load_keep_ahead(a, L.wave, tile + NG, ka);
 }
 
 typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
 
 // V^T operand (16 d x 32 keys) of d block `db`, key half `u`, through two LDS transpose reads
-template <int D, int STAGE>
+template <int D, int STAGE, int NG>
 __device__ __forceinline__ s16x8 read_vt(const unsigned char* lds, const Lane<D>& L, int db, int u) {
-  using S = Shape<D>;
+  using S = Shape<D, 2, NG>;
   const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-      (lds_s16x4_ptr)(lds + L.vro[db] + STAGE * S::TILEB + (32 * u) * S::ROWB));
+      (lds_s16x4_ptr)(lds + L.vro[db] + STAGE * S::STAGEB + (32 * u) * S::ROWB));
   const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-      (lds_s16x4_ptr)(lds + L.vro[db] + STAGE * S::TILEB + (32 * u + 16) * S::ROWB));
+      (lds_s16x4_ptr)(lds + L.vro[db] + STAGE * S::STAGEB + (32 * u + 16) * S::ROWB));
   return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
 // One key tile (ring stage STAGE, a compile-time constant so that every LDS address is base + immediate)
-template <int D, int RB, int STAGE>
+template <int D, int RB, int STAGE, int NG>
 __device__ __forceinline__ void compute_tile(const AttnArgs& a, const Lane<D>& L, const unsigned char* lds, int t,
                                              const bf16x8 (&qreg)[RB][Shape<D>::NS], f32x4 (&o)[RB][Shape<D>::NDB],
                                              float (&m)[RB], float (&thr)[RB], float (&lsum)[RB]) {
-  using S = Shape<D>;
+  using S = Shape<D, 2, NG>;
   constexpr int NS = S::NS, NDB = S::NDB;
   constexpr bool kMfmaRowSum = (RB == 1);
   // ---- S^T = K Q^T
@@ -296,7 +304,7 @@ __device__ __forceinline__ void compute_tile(const AttnArgs& a, const Lane<D>& L
   for (int kb4 = 0; kb4 < 4; ++kb4) {
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-      const bf16x8 kop = *reinterpret_cast<const bf16x8*>(lds + L.kro[s] + STAGE * S::TILEB + kb4 * 16 * S::ROWB);
+      const bf16x8 kop = *reinterpret_cast<const bf16x8*>(lds + L.kro[s] + STAGE * S::STAGEB + kb4 * 16 * S::ROWB);
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
         sacc[rb][kb4] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, qreg[rb][s], sacc[rb][kb4], 0, 0, 0);
@@ -310,7 +318,7 @@ __device__ __forceinline__ void compute_tile(const AttnArgs& a, const Lane<D>& L
 #pragma unroll
   for (int u = 0; u < NPRE; ++u)
 #pragma unroll
-    for (int db = 0; db < NDB; ++db) vpre[u][db] = read_vt<D, STAGE>(lds, L, db, u);
+    for (int db = 0; db < NDB; ++db) vpre[u][db] = read_vt<D, STAGE, NG>(lds, L, db, u);
 
   // ---- online softmax (log2 domain: p = exp2(s * scale_log2 - m)); keys past Nkv only exist in the last tile
   const int key0 = t * kKeyTile;
@@ -401,7 +409,7 @@ __device__ __forceinline__ void compute_tile(const AttnArgs& a, const Lane<D>& L
   for (int u = 0; u < 2; ++u) {
 #pragma unroll
     for (int db = 0; db < NDB; ++db) {
-      const s16x8 vop = (u < NPRE) ? vpre[u < NPRE ? u : 0][db] : read_vt<D, STAGE>(lds, L, db, u);
+      const s16x8 vop = (u < NPRE) ? vpre[u < NPRE ? u : 0][db] : read_vt<D, STAGE, NG>(lds, L, db, u);
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
         o[rb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vop),
@@ -411,9 +419,19 @@ __device__ __forceinline__ void compute_tile(const AttnArgs& a, const Lane<D>& L
   }
 }
 
-template <int D, int RB, bool ONCE>
-__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
-  using S = Shape<D>;
+// NST ring stages: NST - 1 tiles per group are in flight ahead of the one being computed.  Two stages (64 KiB for
+// D = 128) let two workgroups share a CU, i.e. two tiles in flight per CU; where a launch has at most one workgroup
+// per CU anyway (one query tile per K/V head on a long key stream) a deeper ring keeps as many bytes in flight from a
+// single workgroup.
+// NG groups of 4 waves.  With NG = 2 the two groups own the SAME query rows and alternate key tiles of the split
+// (group g takes tiles t0 + g, t0 + g + 2, ...), each with its own part of every ring stage, and merge their
+// (O, m, l) through LDS at the end.  A launch that has one workgroup per CU then runs two waves per SIMD -- one
+// wave's MFMA chain fills the gaps of the other's softmax and LDS waits -- without the second split's partial
+// results going through HBM.  Measured on 32 layers x 5248 keys x 128 rows with the transfers removed: the tile
+// arithmetic alone takes 55 us with one wave per SIMD, as long as the K/V stream alone (57 us).
+template <int D, int RB, bool ONCE, int NST, int NG>
+__global__ __launch_bounds__(256 * NG, (NG == 2 || NST > 2) ? 1 : 2) void attn_bf16_kernel(AttnArgs a) {
+  using S = Shape<D, NST, NG>;
   constexpr int CPR = S::CPR, RPI = S::RPI, IPT = S::IPT, R256 = S::R256, NS = S::NS, NDB = S::NDB, ROWB = S::ROWB;
   // LDS rows are unpadded (a transfer writes 1 KiB contiguous); bank conflicts are avoided by
   // storing chunk c of row r at position c ^ f(r):  f_K(r) = (r / R256) % CPR makes the 16 rows of
@@ -432,12 +450,13 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   const int t1 = min(t0 + a.tiles_per_split, a.key_tiles);
 
   const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave_wg = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave = wave_wg & 3, wgrp = wave_wg >> 2;   // wave within its group, group within the workgroup
   const int l16 = lane & 15, G = lane >> 4;
 
   Lane<D> L;
   L.lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)lds;
-  L.wave = wave; L.lane = lane; L.G = G;
+  L.wave = wave; L.grp = wgrp; L.lane = lane; L.G = G;
   const long long bh = (long long)b * a.Hkv + kvh;
   // base pointers of this (batch, KV head); kept as separate values (in a struct the compiler turns
   // the three-way source select of the gather path into a table lookup in scratch memory)
@@ -455,22 +474,27 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   for (int j = IPT; j < 4; ++j) { L.kgj[j] = 0; L.vgj[j] = 0; }
   {
     const int fk = (D == 128) ? l16 : (l16 >> 1);
+    const unsigned gofs = (unsigned)wgrp * S::TILEB;  // the group's tile inside a stage
 #pragma unroll
-    for (int s2 = 0; s2 < NS; ++s2) L.kro[s2] = l16 * ROWB + (((4 * s2 + G) ^ fk) << 4);
+    for (int s2 = 0; s2 < NS; ++s2) L.kro[s2] = gofs + l16 * ROWB + (((4 * s2 + G) ^ fk) << 4);
     const int e4 = l16 >> 2, c4 = l16 & 3;
     const int fv = (D == 128) ? 2 * (4 * (G & 1) + e4) : 2 * (2 * (G & 1) + (e4 >> 1));
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
-      L.vro[db] = S::VBASE + (4 * G + e4) * ROWB + (((2 * db + (c4 >> 1)) ^ fv) << 4) + ((c4 & 1) << 3);
+      L.vro[db] = gofs + S::VBASE + (4 * G + e4) * ROWB + (((2 * db + (c4 >> 1)) ^ fv) << 4) + ((c4 & 1) << 3);
   }
 
-  // ---- the first tile goes in flight, then the query rows
+  // ---- the group's first NST - 1 tiles go in flight, then the query rows
+  const int tg0 = t0 + wgrp;                       // this group's tiles: tg0, tg0 + NG, ...
   const SlabRanges R = slab_ranges(a, wave);
   KeepAhead ka;
-  load_keep_ahead(a, wave, t0, ka);
-  issue_tile<D, ONCE>(a, L, R, kc, vc, kb, vb, ks, vs, t0, 0, ka);
+  load_keep_ahead(a, wave, tg0, ka);
+#pragma unroll
+  for (int j = 0; j < NST - 1; ++j)
+    if (tg0 + NG * j < t1) issue_tile<D, ONCE, NST, NG>(a, L, R, kc, vc, kb, vb, ks, vs, tg0 + NG * j, j, ka);
 
-  // ---- query rows of this wave, as MFMA B operands (lane: row l16, d = 32*s + 8*G .. +7)
+  // ---- query rows of this wave, as MFMA B operands (lane: row l16, d = 32*s + 8*G .. +7); both groups hold the
+  // same rows
   const int row_base = qt * (64 * RB) + wave * (16 * RB);
   bf16x8 qreg[RB][NS];
 #pragma unroll
@@ -494,21 +518,76 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     for (int db = 0; db < NDB; ++db) o[rb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  // Two tiles per trip so that the ring stage is a compile-time constant.  Per tile: wait for its
-  // transfers (all of this wave's outstanding ones: only that tile is in flight), barrier (every
-  // wave's part has landed and the previous tile is consumed), put the next tile in flight into the
-  // stage just freed, compute.  The query-row loads are complete after the first wait, so the
-  // compiler places no vector-memory wait of its own inside the loop.
-  for (int t = t0; t < t1; t += 2) {
-    wait_vmcnt<0>();
+  // NST steps per trip so that the ring stage is a compile-time constant; in step i every group works on its tile
+  // tg0 + NG i (a group whose tile lies past the split's end only keeps the barriers).  Per step: wait for the
+  // tile's transfers (every tile is 2 IPT transfers of this wave and transfers complete in issue order, so all but
+  // those of the NST - 2 younger tiles in flight must be done; towards the end of the split fewer are in flight),
+  // barrier (every wave's part has landed and the previous step's tiles are consumed), put the tile of step
+  // i + NST - 1 in flight into the stage just freed, compute.  The query-row loads are complete after the first
+  // wait, so the compiler places no vector-memory wait of its own inside the loop.
+  constexpr int PER_TILE = 2 * IPT;                // transfers of one wave per tile
+  // with a deeper ring the first wait of the loop leaves transfers in flight, and the query-row loads were issued
+  // after them: complete everything once here, or the compiler would wait for its loads inside the loop
+  if constexpr (NST > 2) wait_vmcnt<0>();
+  auto tile_step = [&](auto stage_c, int t) {      // t: this group's tile of the step
+    constexpr int STAGE = decltype(stage_c)::value;
+    if constexpr (NST == 2) {
+      wait_vmcnt<0>();
+    } else if constexpr (NST == 3) {
+      if (t + NG < t1) wait_vmcnt<PER_TILE>(); else wait_vmcnt<0>();
+    } else {
+      if (t + 2 * NG < t1) wait_vmcnt<2 * PER_TILE>();
+      else if (t + NG < t1) wait_vmcnt<PER_TILE>();
+      else wait_vmcnt<0>();
+    }
     __builtin_amdgcn_s_barrier();
-    if (t + 1 < t1) issue_tile<D, ONCE>(a, L, R, kc, vc, kb, vb, ks, vs, t + 1, 1, ka);
-    compute_tile<D, RB, 0>(a, L, lds, t, qreg, o, m, thr, lsum);
-    if (t + 1 >= t1) break;
-    wait_vmcnt<0>();
+    if (t + NG * (NST - 1) < t1)
+      issue_tile<D, ONCE, NST, NG>(a, L, R, kc, vc, kb, vb, ks, vs, t + NG * (NST - 1), (STAGE + NST - 1) % NST, ka);
+    if (NG == 1 || t < t1) compute_tile<D, RB, STAGE, NG>(a, L, lds, t, qreg, o, m, thr, lsum);
+  };
+  // the trip count depends on the split only (t0, t1), not on the group: every wave meets every barrier
+  for (int t = t0; t < t1; t += NG * NST) {
+    tile_step(std::integral_constant<int, 0>{}, t + wgrp);
+    if (t + NG >= t1) break;
+    tile_step(std::integral_constant<int, 1>{}, t + NG + wgrp);
+    if constexpr (NST >= 3) {
+      if (t + 2 * NG >= t1) break;
+      tile_step(std::integral_constant<int, 2>{}, t + 2 * NG + wgrp);
+    }
+    if constexpr (NST >= 4) {
+      if (t + 3 * NG >= t1) break;
+      tile_step(std::integral_constant<int, 3>{}, t + 3 * NG + wgrp);
+    }
+  }
+
+  // ---- two groups: the second hands its (O, m, l) to the first through LDS (the ring is free once every wave is
+  // past its last tile); fixed order, so the result does not depend on timing
+  if constexpr (NG == 2) {
+    constexpr int WAVE_O = RB * NDB * 64 * 16;     // bytes of one wave's accumulators, lane-contiguous 16-byte pieces
+    static_assert(4 * (WAVE_O + RB * 64 * 8) <= S::LDS_BYTES, "exchange area fits the ring");
     __builtin_amdgcn_s_barrier();
-    if (t + 2 < t1) issue_tile<D, ONCE>(a, L, R, kc, vc, kb, vb, ks, vs, t + 2, 0, ka);
-    compute_tile<D, RB, 1>(a, L, lds, t + 1, qreg, o, m, thr, lsum);
+    f32x4* xo = reinterpret_cast<f32x4*>(lds + wave * WAVE_O);
+    float2* xml = reinterpret_cast<float2*>(lds + 4 * WAVE_O + wave * (RB * 64 * 8));
+    if (wgrp == 1) {
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) xo[(rb * NDB + db) * 64 + lane] = o[rb][db];
+        xml[rb * 64 + lane] = make_float2(m[rb], lsum[rb]);
+      }
+    }
+    __syncthreads();
+    if (wgrp == 1) return;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      const float2 ml = xml[rb * 64 + lane];
+      const float M = fmaxf(m[rb], ml.x);
+      const float w0 = exp2_fast(m[rb] - M), w1 = exp2_fast(ml.x - M);
+      lsum[rb] = lsum[rb] * w0 + ml.y * w1;
+      m[rb] = M;
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) o[rb][db] = o[rb][db] * w0 + xo[(rb * NDB + db) * 64 + lane] * w1;
+    }
   }
 
   // ---- epilogue
@@ -595,10 +674,6 @@ AttnPlan plan_attention_bf16(const sdllm_attn_params& p) {
   // one workgroup only, which lets the transfers carry the nontemporal hint (32 layers x 5248 keys, 128 rows:
   // 2650 -> 2510 us per step; with 1312 keys the extra key splits it takes cost more than it gains)
   if (Rtot > 64 && Rtot <= 128 && Nkv >= 64 * kKeyTile) pl.rb = 2;
-  // Two ring stages, two workgroups per CU.  Deeper rings (3, 4 stages: one workgroup per CU) were
-  // measured and are slower at every shape: with one wave per SIMD the per-tile latencies of the
-  // MFMA / softmax / LDS chain are exposed, and those, not the K/V stream, bound the loop.
-  pl.stages = 2;
   const int rows_wg = 64 * pl.rb;
   pl.q_tiles = (int)((Rtot + rows_wg - 1) / rows_wg);
   pl.key_tiles = (int)((Nkv + kKeyTile - 1) / kKeyTile);
@@ -623,6 +698,17 @@ AttnPlan plan_attention_bf16(const sdllm_attn_params& p) {
   pl.kv_splits = (pl.key_tiles + pl.tiles_per_split - 1) / pl.tiles_per_split;   // no empty split
   const long long units = (long long)p.B * p.Hkv * pl.kv_splits;
   pl.workgroups = (int)(((units + kNumXCDs - 1) / kNumXCDs) * kNumXCDs * pl.q_tiles);
+  // Ring depth.  Two stages let two workgroups share a CU (two tiles in flight per CU).  Where the launch has at
+  // most one workgroup per CU anyway and a split is long enough to fill it, one workgroup keeps kDeepStages - 1
+  // tiles in flight by itself.
+  pl.stages = 2;
+  pl.groups = 1;
+  if (pl.workgroups <= kNumCUs) {
+    // ... or two 4-wave groups of one workgroup alternate its key tiles (two waves per SIMD, the groups' partial
+    // results merged in LDS)
+    if (kTwoGroups && pl.tiles_per_split >= 4) pl.groups = 2;
+    else if (pl.q_tiles == 1 && pl.tiles_per_split >= 2 * kDeepStages) pl.stages = kDeepStages;
+  }
   return pl;
 }
 
@@ -632,42 +718,55 @@ size_t attention_bf16_workspace_bytes(const sdllm_attn_params& p, const AttnPlan
   return rows * pl.kv_splits * (size_t)(p.D + 2) * sizeof(float);
 }
 
-template <int D, int RB, bool ONCE>
+template <int D, int RB, bool ONCE, int NST, int NG>
 static hipError_t opt_in_main() {
   static LdsOptIn st;
-  return ensure_lds_opt_in(reinterpret_cast<const void*>(&attn_bf16_kernel<D, RB, ONCE>), Shape<D>::LDS_BYTES, st);
+  return ensure_lds_opt_in(reinterpret_cast<const void*>(&attn_bf16_kernel<D, RB, ONCE, NST, NG>),
+                           Shape<D, NST, NG>::LDS_BYTES, st);
 }
 
-template <int D, int RB, bool ONCE>
-static hipError_t launch_main(const AttnArgs& a, const AttnPlan& pl, hipStream_t stream) {
-  constexpr size_t lds_bytes = Shape<D>::LDS_BYTES;
-  hipError_t e = opt_in_main<D, RB, ONCE>();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((attn_bf16_kernel<D, RB, ONCE>), dim3(pl.workgroups), dim3(256), lds_bytes, stream, a);
+// launch == false: only the kernel's LDS opt-in on the current device (the preparation pass of sdllm_init)
+template <int D, int RB, bool ONCE, int NST, int NG>
+static hipError_t launch_main(const AttnArgs& a, const AttnPlan& pl, hipStream_t stream, bool launch) {
+  constexpr size_t lds_bytes = Shape<D, NST, NG>::LDS_BYTES;
+  hipError_t e = opt_in_main<D, RB, ONCE, NST, NG>();
+  if (e != hipSuccess || !launch) return e;
+  hipLaunchKernelGGL((attn_bf16_kernel<D, RB, ONCE, NST, NG>), dim3(pl.workgroups), dim3(256 * NG), lds_bytes, stream, a);
   return hipGetLastError();
 }
 
+template <int D, int RB>
+static hipError_t launch_rb(const AttnArgs& a, const AttnPlan& pl, hipStream_t stream, bool launch) {
+  // one query tile per K/V head (and split): every K/V byte is read by one workgroup only (nontemporal hint);
+  // the deeper rings are only built for that case (the plan asks for them only there)
+  if (pl.q_tiles == 1) {
+    if (pl.groups == 2) return launch_main<D, RB, true, 2, 2>(a, pl, stream, launch);
+    if (pl.stages == 4) return launch_main<D, RB, true, 4, 1>(a, pl, stream, launch);
+    if (pl.stages == 3) return launch_main<D, RB, true, 3, 1>(a, pl, stream, launch);
+    return launch_main<D, RB, true, 2, 1>(a, pl, stream, launch);
+  }
+  if (pl.groups == 2) return launch_main<D, RB, false, 2, 2>(a, pl, stream, launch);
+  return launch_main<D, RB, false, 2, 1>(a, pl, stream, launch);
+}
+
 template <int D>
-static hipError_t prepare_d() {
-  hipError_t e = opt_in_main<D, 1, false>();
-  if (e == hipSuccess) e = opt_in_main<D, 1, true>();
-  if (e == hipSuccess) e = opt_in_main<D, 2, false>();
-  if (e == hipSuccess) e = opt_in_main<D, 2, true>();
-  return e;
+static hipError_t launch_d(const AttnArgs& a, const AttnPlan& pl, hipStream_t stream, bool launch = true) {
+  return pl.rb == 2 ? launch_rb<D, 2>(a, pl, stream, launch) : launch_rb<D, 1>(a, pl, stream, launch);
 }
 
 hipError_t prepare_attention_bf16() {
-  hipError_t e = prepare_d<128>();
-  if (e == hipSuccess) e = prepare_d<64>();
+  AttnArgs a{};
+  AttnPlan pl{};
+  hipError_t e = hipSuccess;
+  for (int rb = 1; rb <= 2; ++rb)
+    for (int q_tiles = 1; q_tiles <= 2; ++q_tiles)
+      for (int groups = 1; groups <= 2; ++groups)
+        for (int stages = 2; stages <= (q_tiles == 1 && groups == 1 ? 4 : 2); ++stages) {
+          pl.rb = rb; pl.q_tiles = q_tiles; pl.stages = stages; pl.groups = groups;
+          if (e == hipSuccess) e = launch_d<128>(a, pl, nullptr, false);
+          if (e == hipSuccess) e = launch_d<64>(a, pl, nullptr, false);
+        }
   return e;
-}
-
-template <int D>
-static hipError_t launch_d(const AttnArgs& a, const AttnPlan& pl, hipStream_t stream) {
-  // one query tile per K/V head (and split): every K/V byte is read by one workgroup only
-  if (pl.q_tiles == 1)
-    return pl.rb == 2 ? launch_main<D, 2, true>(a, pl, stream) : launch_main<D, 1, true>(a, pl, stream);
-  return pl.rb == 2 ? launch_main<D, 2, false>(a, pl, stream) : launch_main<D, 1, false>(a, pl, stream);
 }
 
 hipError_t launch_attention_bf16(const sdllm_attn_params& p, const AttnPlan& pl,
