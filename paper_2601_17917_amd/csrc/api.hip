@@ -198,7 +198,7 @@ int sdllm_plan_attention(const sdllm_attn_params* p, sdllm_attn_plan* plan) {
     return SDLLM_OK;
   }
   sdllm::AttnPlan pl = sdllm::plan_attention_bf16(*p);
-  plan->kv_splits = pl.kv_splits; plan->rows_per_workgroup = 64 * pl.rb;
+  plan->kv_splits = pl.kv_splits; plan->rows_per_workgroup = 64 * pl.rb * (pl.mode == 2 ? 2 : 1);
   plan->workgroups = pl.workgroups; plan->key_tiles_per_split = pl.tiles_per_split;
   return SDLLM_OK;
 }

@@ -33,6 +33,9 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 constexpr int kKeyTile = 64;
 constexpr int kDeepStages = 3;    // ring depth of the launches that have one workgroup per CU ...
 constexpr bool kTwoGroups = true; // ... unless they run two 4-wave groups per workgroup
+constexpr bool kShareTiles = true;   // 8-wave workgroups with row-split groups for heads with many query rows
+constexpr int kShareMinRows = 512;   // ... from this many query rows per K/V head
+constexpr int kShareStages = 3;
 constexpr float kLog2eA = 1.4426950408889634f;
 constexpr float kNegBigA = -3.0e38f;
 
@@ -209,10 +212,10 @@ __device__ __forceinline__ void issue_slab(const Lane<D>& L, unsigned sk, const 
   dma_slab<S::IPT, ONCE>(sk + S::VBASE, vt, L.vgj);
 }
 
-// Puts key tile `tile` (a tile of this wave's group) in flight into the group's part of ring stage `stage`:
-// 2 * IPT transfers per wave, which moves rows 16*wave .. 16*wave+15 of the tile.  `ka` holds the keep_idx
-// bounds of these rows on entry and those of the group's next tile (tile + NG) on return.
-template <int D, bool ONCE, int NST, int NG>
+// Puts key tile `tile` (a tile this wave's group moves) in flight into ring stage `stage` (the group's part of it
+// when a stage holds NG tiles): 2 * IPT transfers per wave, which moves rows 16*wave .. 16*wave+15 of the tile.
+// `ka` holds the keep_idx bounds of these rows on entry and those of the group's next tile (tile + STEP) on return.
+template <int D, bool ONCE, int NST, int NG, int STEP>
 __device__ __forceinline__ void issue_tile(const AttnArgs& a, const Lane<D>& L, const SlabRanges& R,
                                            const uint16_t* kc, const uint16_t* vc,
                                            const uint16_t* kb, const uint16_t* vb, const uint16_t* ks, const uint16_t* vs,
@@ -270,7 +273,7 @@ __device__ __forceinline__ void issue_tile(const AttnArgs& a, const Lane<D>& L, 
 #pragma unroll
     for (int j = 0; j < S::IPT; ++j) dma16_vaddr<ONCE>(sv + j * S::RPI * S::ROWB, vpp[j]);
   }
-  load_keep_ahead(a, L.wave, tile + NG, ka);
+  load_keep_ahead(a, L.wave, tile + STEP, ka);
 }
 
 typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
@@ -419,19 +422,25 @@ __device__ __forceinline__ void compute_tile(const AttnArgs& a, const Lane<D>& L
   }
 }
 
-// NST ring stages: NST - 1 tiles per group are in flight ahead of the one being computed.  Two stages (64 KiB for
-// D = 128) let two workgroups share a CU, i.e. two tiles in flight per CU; where a launch has at most one workgroup
-// per CU anyway (one query tile per K/V head on a long key stream) a deeper ring keeps as many bytes in flight from a
-// single workgroup.
-// NG groups of 4 waves.  With NG = 2 the two groups own the SAME query rows and alternate key tiles of the split
-// (group g takes tiles t0 + g, t0 + g + 2, ...), each with its own part of every ring stage, and merge their
-// (O, m, l) through LDS at the end.  A launch that has one workgroup per CU then runs two waves per SIMD -- one
-// wave's MFMA chain fills the gaps of the other's softmax and LDS waits -- without the second split's partial
-// results going through HBM.  Measured on 32 layers x 5248 keys x 128 rows with the transfers removed: the tile
-// arithmetic alone takes 55 us with one wave per SIMD, as long as the K/V stream alone (57 us).
-template <int D, int RB, bool ONCE, int NST, int NG>
-__global__ __launch_bounds__(256 * NG, (NG == 2 || NST > 2) ? 1 : 2) void attn_bf16_kernel(AttnArgs a) {
+// NST ring stages: NST - 1 tiles are in flight ahead of the one being computed.  Two stages (64 KiB for D = 128)
+// let two workgroups share a CU, i.e. two tiles in flight per CU; a deeper ring keeps as many bytes in flight from
+// a single workgroup.
+// MODE 0: one group of 4 waves, wave w owns query rows 16 RB w .. of the workgroup's 64 RB rows.
+// MODE 1: two groups of 4 waves own the SAME query rows and alternate key tiles of the split (group g takes tiles
+//   t0 + g, t0 + g + 2, ...), each with its own part of every ring stage, and merge their (O, m, l) through LDS at
+//   the end.  A launch that has one workgroup per CU then runs two waves per SIMD -- one wave's MFMA chain fills
+//   the gaps of the other's softmax and LDS waits -- without a second split's partial results going through HBM.
+//   Measured on 32 layers x 5248 keys x 128 rows with the transfers removed: the tile arithmetic alone takes 55 us
+//   with one wave per SIMD, as long as the K/V stream alone (57 us).
+// MODE 2: two groups of 4 waves own DIFFERENT query rows (128 RB per workgroup) and share every key tile; the
+//   groups take turns moving tiles into the ring (group g moves tiles t0 + g, t0 + g + 2, ...).  Two waves per SIMD
+//   from one workgroup, and a K/V tile is brought into LDS once per 128 RB query rows instead of once per 64 RB.
+template <int D, int RB, bool ONCE, int NST, int MODE>
+__global__ __launch_bounds__(MODE ? 512 : 256, (MODE || NST > 2) ? 1 : 2) void attn_bf16_kernel(AttnArgs a) {
+  constexpr int NG = (MODE == 1) ? 2 : 1;          // key tiles per ring stage
+  constexpr int STEP = MODE ? 2 : 1;               // distance between the tiles one group moves
   using S = Shape<D, NST, NG>;
+  static_assert(MODE == 0 || NST <= 3, "the wait below assumes at most one older tile of a group in flight");
   constexpr int CPR = S::CPR, RPI = S::RPI, IPT = S::IPT, R256 = S::R256, NS = S::NS, NDB = S::NDB, ROWB = S::ROWB;
   // LDS rows are unpadded (a transfer writes 1 KiB contiguous); bank conflicts are avoided by
   // storing chunk c of row r at position c ^ f(r):  f_K(r) = (r / R256) % CPR makes the 16 rows of
@@ -456,7 +465,7 @@ __global__ __launch_bounds__(256 * NG, (NG == 2 || NST > 2) ? 1 : 2) void attn_b
 
   Lane<D> L;
   L.lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)lds;
-  L.wave = wave; L.grp = wgrp; L.lane = lane; L.G = G;
+  L.wave = wave; L.grp = (MODE == 1) ? wgrp : 0; L.lane = lane; L.G = G;
   const long long bh = (long long)b * a.Hkv + kvh;
   // base pointers of this (batch, KV head); kept as separate values (in a struct the compiler turns
   // the three-way source select of the gather path into a table lookup in scratch memory)
@@ -474,7 +483,7 @@ __global__ __launch_bounds__(256 * NG, (NG == 2 || NST > 2) ? 1 : 2) void attn_b
   for (int j = IPT; j < 4; ++j) { L.kgj[j] = 0; L.vgj[j] = 0; }
   {
     const int fk = (D == 128) ? l16 : (l16 >> 1);
-    const unsigned gofs = (unsigned)wgrp * S::TILEB;  // the group's tile inside a stage
+    const unsigned gofs = (unsigned)L.grp * S::TILEB; // the group's tile inside a stage
 #pragma unroll
     for (int s2 = 0; s2 < NS; ++s2) L.kro[s2] = gofs + l16 * ROWB + (((4 * s2 + G) ^ fk) << 4);
     const int e4 = l16 >> 2, c4 = l16 & 3;
@@ -484,18 +493,26 @@ __global__ __launch_bounds__(256 * NG, (NG == 2 || NST > 2) ? 1 : 2) void attn_b
       L.vro[db] = gofs + S::VBASE + (4 * G + e4) * ROWB + (((2 * db + (c4 >> 1)) ^ fv) << 4) + ((c4 & 1) << 3);
   }
 
-  // ---- the group's first NST - 1 tiles go in flight, then the query rows
-  const int tg0 = t0 + wgrp;                       // this group's tiles: tg0, tg0 + NG, ...
+  // ---- the first NST - 1 steps' tiles go in flight, then the query rows
+  const int tg0 = t0 + (MODE ? wgrp : 0);          // the tiles this wave's group moves: tg0, tg0 + STEP, ...
   const SlabRanges R = slab_ranges(a, wave);
   KeepAhead ka;
   load_keep_ahead(a, wave, tg0, ka);
+  if constexpr (MODE == 2) {
 #pragma unroll
-  for (int j = 0; j < NST - 1; ++j)
-    if (tg0 + NG * j < t1) issue_tile<D, ONCE, NST, NG>(a, L, R, kc, vc, kb, vb, ks, vs, tg0 + NG * j, j, ka);
+    for (int j = 0; j < NST - 1; ++j)              // tile t0 + j belongs to group j & 1
+      if ((j & 1) == wgrp && t0 + j < t1)
+        issue_tile<D, ONCE, NST, NG, STEP>(a, L, R, kc, vc, kb, vb, ks, vs, t0 + j, j, ka);
+  } else {
+#pragma unroll
+    for (int j = 0; j < NST - 1; ++j)
+      if (tg0 + NG * j < t1) issue_tile<D, ONCE, NST, NG, STEP>(a, L, R, kc, vc, kb, vb, ks, vs, tg0 + NG * j, j, ka);
+  }
 
-  // ---- query rows of this wave, as MFMA B operands (lane: row l16, d = 32*s + 8*G .. +7); both groups hold the
-  // same rows
-  const int row_base = qt * (64 * RB) + wave * (16 * RB);
+  // ---- query rows of this wave, as MFMA B operands (lane: row l16, d = 32*s + 8*G .. +7); in MODE 1 both groups
+  // hold the same rows
+  const int row_base = (MODE == 2) ? qt * (128 * RB) + wgrp * (64 * RB) + wave * (16 * RB)
+                                   : qt * (64 * RB) + wave * (16 * RB);
   bf16x8 qreg[RB][NS];
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
@@ -526,43 +543,67 @@ __global__ __launch_bounds__(256 * NG, (NG == 2 || NST > 2) ? 1 : 2) void attn_b
   // i + NST - 1 in flight into the stage just freed, compute.  The query-row loads are complete after the first
   // wait, so the compiler places no vector-memory wait of its own inside the loop.
   constexpr int PER_TILE = 2 * IPT;                // transfers of one wave per tile
-  // with a deeper ring the first wait of the loop leaves transfers in flight, and the query-row loads were issued
-  // after them: complete everything once here, or the compiler would wait for its loads inside the loop
-  if constexpr (NST > 2) wait_vmcnt<0>();
-  auto tile_step = [&](auto stage_c, int t) {      // t: this group's tile of the step
-    constexpr int STAGE = decltype(stage_c)::value;
-    if constexpr (NST == 2) {
-      wait_vmcnt<0>();
-    } else if constexpr (NST == 3) {
-      if (t + NG < t1) wait_vmcnt<PER_TILE>(); else wait_vmcnt<0>();
-    } else {
-      if (t + 2 * NG < t1) wait_vmcnt<2 * PER_TILE>();
-      else if (t + NG < t1) wait_vmcnt<PER_TILE>();
-      else wait_vmcnt<0>();
+  // where the first wait of the loop leaves transfers in flight (a deeper ring) or is skipped by some waves (MODE 2),
+  // complete everything once here: the query-row loads were issued after the first transfers, and the compiler
+  // would otherwise wait for them inside the loop
+  if constexpr (NST > 2 || MODE == 2) wait_vmcnt<0>();
+  if constexpr (MODE == 2) {
+    // step s works on tile t0 + s in stage s % NST; the tile was moved by group s & 1, whose waves have nothing
+    // younger in flight when they wait for it (their next tile, t0 + s + 2, goes in flight during this step or later)
+    auto tile_step = [&](auto stage_c, int t) {
+      constexpr int STAGE = decltype(stage_c)::value;
+      const int par = (t - t0) & 1;
+      if (par == wgrp) wait_vmcnt<0>();
+      __builtin_amdgcn_s_barrier();
+      if (((par + NST - 1) & 1) == wgrp && t + NST - 1 < t1)
+        issue_tile<D, ONCE, NST, NG, STEP>(a, L, R, kc, vc, kb, vb, ks, vs, t + NST - 1, (STAGE + NST - 1) % NST, ka);
+      compute_tile<D, RB, STAGE, NG>(a, L, lds, t, qreg, o, m, thr, lsum);
+    };
+    for (int t = t0; t < t1; t += NST) {
+      tile_step(std::integral_constant<int, 0>{}, t);
+      if (t + 1 >= t1) break;
+      tile_step(std::integral_constant<int, 1>{}, t + 1);
+      if constexpr (NST >= 3) {
+        if (t + 2 >= t1) break;
+        tile_step(std::integral_constant<int, 2>{}, t + 2);
+      }
     }
-    __builtin_amdgcn_s_barrier();
-    if (t + NG * (NST - 1) < t1)
-      issue_tile<D, ONCE, NST, NG>(a, L, R, kc, vc, kb, vb, ks, vs, t + NG * (NST - 1), (STAGE + NST - 1) % NST, ka);
-    if (NG == 1 || t < t1) compute_tile<D, RB, STAGE, NG>(a, L, lds, t, qreg, o, m, thr, lsum);
-  };
-  // the trip count depends on the split only (t0, t1), not on the group: every wave meets every barrier
-  for (int t = t0; t < t1; t += NG * NST) {
-    tile_step(std::integral_constant<int, 0>{}, t + wgrp);
-    if (t + NG >= t1) break;
-    tile_step(std::integral_constant<int, 1>{}, t + NG + wgrp);
-    if constexpr (NST >= 3) {
-      if (t + 2 * NG >= t1) break;
-      tile_step(std::integral_constant<int, 2>{}, t + 2 * NG + wgrp);
-    }
-    if constexpr (NST >= 4) {
-      if (t + 3 * NG >= t1) break;
-      tile_step(std::integral_constant<int, 3>{}, t + 3 * NG + wgrp);
+  } else {
+    auto tile_step = [&](auto stage_c, int t) {    // t: this group's tile of the step
+      constexpr int STAGE = decltype(stage_c)::value;
+      if constexpr (NST == 2) {
+        wait_vmcnt<0>();
+      } else if constexpr (NST == 3) {
+        if (t + NG < t1) wait_vmcnt<PER_TILE>(); else wait_vmcnt<0>();
+      } else {
+        if (t + 2 * NG < t1) wait_vmcnt<2 * PER_TILE>();
+        else if (t + NG < t1) wait_vmcnt<PER_TILE>();
+        else wait_vmcnt<0>();
+      }
+      __builtin_amdgcn_s_barrier();
+      if (t + NG * (NST - 1) < t1)
+        issue_tile<D, ONCE, NST, NG, STEP>(a, L, R, kc, vc, kb, vb, ks, vs, t + NG * (NST - 1), (STAGE + NST - 1) % NST, ka);
+      if (NG == 1 || t < t1) compute_tile<D, RB, STAGE, NG>(a, L, lds, t, qreg, o, m, thr, lsum);
+    };
+    // the trip count depends on the split only (t0, t1), not on the group: every wave meets every barrier
+    for (int t = t0; t < t1; t += NG * NST) {
+      tile_step(std::integral_constant<int, 0>{}, t + L.grp);
+      if (t + NG >= t1) break;
+      tile_step(std::integral_constant<int, 1>{}, t + NG + L.grp);
+      if constexpr (NST >= 3) {
+        if (t + 2 * NG >= t1) break;
+        tile_step(std::integral_constant<int, 2>{}, t + 2 * NG + L.grp);
+      }
+      if constexpr (NST >= 4) {
+        if (t + 3 * NG >= t1) break;
+        tile_step(std::integral_constant<int, 3>{}, t + 3 * NG + L.grp);
+      }
     }
   }
 
   // ---- two groups: the second hands its (O, m, l) to the first through LDS (the ring is free once every wave is
   // past its last tile); fixed order, so the result does not depend on timing
-  if constexpr (NG == 2) {
+  if constexpr (MODE == 1) {
     constexpr int WAVE_O = RB * NDB * 64 * 16;     // bytes of one wave's accumulators, lane-contiguous 16-byte pieces
     static_assert(4 * (WAVE_O + RB * 64 * 8) <= S::LDS_BYTES, "exchange area fits the ring");
     __builtin_amdgcn_s_barrier();
@@ -674,7 +715,12 @@ AttnPlan plan_attention_bf16(const sdllm_attn_params& p) {
   // one workgroup only, which lets the transfers carry the nontemporal hint (32 layers x 5248 keys, 128 rows:
   // 2650 -> 2510 us per step; with 1312 keys the extra key splits it takes cost more than it gains)
   if (Rtot > 64 && Rtot <= 128 && Nkv >= 64 * kKeyTile) pl.rb = 2;
-  const int rows_wg = 64 * pl.rb;
+  // Many query tiles per K/V head: 8-wave workgroups whose two groups own 64 rb rows each and share every key tile
+  // (mode 2) bring a tile into LDS half as often, with three ring stages (one such workgroup per CU).
+  pl.mode = 0;
+  pl.stages = 2;
+  if (kShareTiles && Rtot >= kShareMinRows) { pl.mode = 2; pl.stages = kShareStages; }
+  const int rows_wg = 64 * pl.rb * (pl.mode == 2 ? 2 : 1);
   pl.q_tiles = (int)((Rtot + rows_wg - 1) / rows_wg);
   pl.key_tiles = (int)((Nkv + kKeyTile - 1) / kKeyTile);
   const long long base = (long long)p.B * p.Hkv * pl.q_tiles;
@@ -701,12 +747,10 @@ AttnPlan plan_attention_bf16(const sdllm_attn_params& p) {
   // Ring depth.  Two stages let two workgroups share a CU (two tiles in flight per CU).  Where the launch has at
   // most one workgroup per CU anyway and a split is long enough to fill it, one workgroup keeps kDeepStages - 1
   // tiles in flight by itself.
-  pl.stages = 2;
-  pl.groups = 1;
-  if (pl.workgroups <= kNumCUs) {
+  if (pl.mode == 0 && pl.workgroups <= kNumCUs) {
     // ... or two 4-wave groups of one workgroup alternate its key tiles (two waves per SIMD, the groups' partial
-    // results merged in LDS)
-    if (kTwoGroups && pl.tiles_per_split >= 4) pl.groups = 2;
+    // results merged in LDS: mode 1)
+    if (kTwoGroups && pl.tiles_per_split >= 4) pl.mode = 1;
     else if (pl.q_tiles == 1 && pl.tiles_per_split >= 2 * kDeepStages) pl.stages = kDeepStages;
   }
   return pl;
@@ -718,35 +762,39 @@ size_t attention_bf16_workspace_bytes(const sdllm_attn_params& p, const AttnPlan
   return rows * pl.kv_splits * (size_t)(p.D + 2) * sizeof(float);
 }
 
-template <int D, int RB, bool ONCE, int NST, int NG>
+template <int D, int RB, bool ONCE, int NST, int MODE>
 static hipError_t opt_in_main() {
   static LdsOptIn st;
-  return ensure_lds_opt_in(reinterpret_cast<const void*>(&attn_bf16_kernel<D, RB, ONCE, NST, NG>),
-                           Shape<D, NST, NG>::LDS_BYTES, st);
+  return ensure_lds_opt_in(reinterpret_cast<const void*>(&attn_bf16_kernel<D, RB, ONCE, NST, MODE>),
+                           Shape<D, NST, MODE == 1 ? 2 : 1>::LDS_BYTES, st);
 }
 
 // launch == false: only the kernel's LDS opt-in on the current device (the preparation pass of sdllm_init)
-template <int D, int RB, bool ONCE, int NST, int NG>
+template <int D, int RB, bool ONCE, int NST, int MODE>
 static hipError_t launch_main(const AttnArgs& a, const AttnPlan& pl, hipStream_t stream, bool launch) {
-  constexpr size_t lds_bytes = Shape<D, NST, NG>::LDS_BYTES;
-  hipError_t e = opt_in_main<D, RB, ONCE, NST, NG>();
+  constexpr size_t lds_bytes = Shape<D, NST, MODE == 1 ? 2 : 1>::LDS_BYTES;
+  hipError_t e = opt_in_main<D, RB, ONCE, NST, MODE>();
   if (e != hipSuccess || !launch) return e;
-  hipLaunchKernelGGL((attn_bf16_kernel<D, RB, ONCE, NST, NG>), dim3(pl.workgroups), dim3(256 * NG), lds_bytes, stream, a);
+  hipLaunchKernelGGL((attn_bf16_kernel<D, RB, ONCE, NST, MODE>), dim3(pl.workgroups), dim3(MODE ? 512 : 256), lds_bytes,
+                     stream, a);
   return hipGetLastError();
 }
 
 template <int D, int RB>
 static hipError_t launch_rb(const AttnArgs& a, const AttnPlan& pl, hipStream_t stream, bool launch) {
+  if (pl.mode == 2)           // row-split groups sharing the tiles (several query tiles per K/V head)
+    return pl.stages == 3 ? launch_main<D, RB, false, 3, 2>(a, pl, stream, launch)
+                          : launch_main<D, RB, false, 2, 2>(a, pl, stream, launch);
   // one query tile per K/V head (and split): every K/V byte is read by one workgroup only (nontemporal hint);
   // the deeper rings are only built for that case (the plan asks for them only there)
   if (pl.q_tiles == 1) {
-    if (pl.groups == 2) return launch_main<D, RB, true, 2, 2>(a, pl, stream, launch);
-    if (pl.stages == 4) return launch_main<D, RB, true, 4, 1>(a, pl, stream, launch);
-    if (pl.stages == 3) return launch_main<D, RB, true, 3, 1>(a, pl, stream, launch);
-    return launch_main<D, RB, true, 2, 1>(a, pl, stream, launch);
+    if (pl.mode == 1) return launch_main<D, RB, true, 2, 1>(a, pl, stream, launch);
+    if (pl.stages == 4) return launch_main<D, RB, true, 4, 0>(a, pl, stream, launch);
+    if (pl.stages == 3) return launch_main<D, RB, true, 3, 0>(a, pl, stream, launch);
+    return launch_main<D, RB, true, 2, 0>(a, pl, stream, launch);
   }
-  if (pl.groups == 2) return launch_main<D, RB, false, 2, 2>(a, pl, stream, launch);
-  return launch_main<D, RB, false, 2, 1>(a, pl, stream, launch);
+  if (pl.mode == 1) return launch_main<D, RB, false, 2, 1>(a, pl, stream, launch);
+  return launch_main<D, RB, false, 2, 0>(a, pl, stream, launch);
 }
 
 template <int D>
@@ -760,9 +808,12 @@ hipError_t prepare_attention_bf16() {
   hipError_t e = hipSuccess;
   for (int rb = 1; rb <= 2; ++rb)
     for (int q_tiles = 1; q_tiles <= 2; ++q_tiles)
-      for (int groups = 1; groups <= 2; ++groups)
-        for (int stages = 2; stages <= (q_tiles == 1 && groups == 1 ? 4 : 2); ++stages) {
-          pl.rb = rb; pl.q_tiles = q_tiles; pl.stages = stages; pl.groups = groups;
+      for (int mode = 0; mode <= 2; ++mode)
+        for (int stages = 2; stages <= 4; ++stages) {
+          if (mode == 1 && stages > 2) continue;
+          if (mode == 2 && (stages > 3 || q_tiles == 1)) continue;
+          if (mode == 0 && stages > 2 && q_tiles > 1) continue;
+          pl.rb = rb; pl.q_tiles = q_tiles; pl.stages = stages; pl.mode = mode;
           if (e == hipSuccess) e = launch_d<128>(a, pl, nullptr, false);
           if (e == hipSuccess) e = launch_d<64>(a, pl, nullptr, false);
         }

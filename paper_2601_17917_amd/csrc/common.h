@@ -36,7 +36,8 @@ struct AttnPlan {
   int kv_splits;        // key-range splits (grid factor)
   int rb;               // 16-row query blocks per wave (rows per workgroup = 64 * rb)
   int stages;           // LDS ring depth of the K/V stream (2..4)
-  int groups;           // 4-wave groups per workgroup that alternate key tiles of the same query rows (1 or 2)
+  int mode;             // 0: one 4-wave group; 1: two groups, same rows, alternating key tiles; 2: two groups,
+                        // different rows, shared key tiles
   int q_tiles;          // query tiles per (batch, kv head) group
   int key_tiles;        // 64-key tiles over Nkv
   int tiles_per_split;  // key tiles handled by one split
