@@ -5,7 +5,9 @@
 //   group   = (batch, KV head).  The g = Hq/Hkv query heads of a group share its K/V, so their
 //             g*Nq query rows are treated as one list of "virtual rows" and tiled together.
 //   workgroup = (group, query tile of 64*RB rows, key-range split); 4 waves, wave w owns the
-//             16*RB rows  [w*16*RB, (w+1)*16*RB) of the tile for all keys of the split.
+//             16*RB rows  [w*16*RB, (w+1)*16*RB) of the tile for all keys of the split.  Two 8-wave shapes
+//             (template MODE, see the kernel): two 4-wave groups on the same rows that alternate key tiles,
+//             or two groups on different rows that share every key tile.
 //   K/V tiles of 64 keys stream through a two-stage LDS ring.  They are moved global -> LDS
 //             directly (global_load_lds_dwordx4: no register staging), one tile ahead of the
 //             one being computed, one workgroup barrier per tile.  Rows come from three places

@@ -7,6 +7,11 @@
 //     triple.  Rows of unmasked positions are never read.
 //  2. unmask_commit: one workgroup per sequence merges the triples in a fixed pattern,
 //     forms c_i = 1 / sum, evaluates the threshold, commits, and writes the flags.
+// The rows kernel is bound by its vector arithmetic, not by the stream: per 32 logits of a lane (one trip of four
+// 16-byte bf16 vectors) it issues 197 instructions -- unpack 32, max 24, FMA 31, exp 33, add 31, addressing and
+// bookkeeping 46 -- i.e. (164 + 33 * 2.4) / 32 = 7.6 issue slots per logit with v_exp_f32 at the 2.4 slots it costs
+// against an FMA (fp32 logits need no unpack: 6.6).  On 256 CUs x 4 SIMDs at 2.4 GHz, one wave-wide instruction per
+// four cycles, that is the plain-ALU roof the benchmark quotes next to the HBM one.
 // (A single launch in which the last workgroup to arrive commits its sequence was measured
 // and dropped: the device-scope release/acquire fences it needs write back and invalidate
 // the L2 of an XCD on every workgroup and cost several times the second launch.)
