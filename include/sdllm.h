@@ -345,7 +345,8 @@ int sdllm_rope_gathered(const sdllm_rope_params* p,
 
 /* ---------------------------------------------------------------------------------------
  * Diagnostics.  sdllm_plan_attention reports the launch plan the library would use (host
- * only, no HIP call): number of key-range splits, query rows per workgroup, workgroups.
+ * only, no HIP call): number of key-range splits, query rows per workgroup, workgroups, the
+ * workgroup shape and its ring depth.
  * Returns SDLLM_OK or the validation error.
  * ------------------------------------------------------------------------------------- */
 typedef struct sdllm_attn_plan {
@@ -353,6 +354,9 @@ typedef struct sdllm_attn_plan {
   int32_t rows_per_workgroup;
   int32_t workgroups;
   int32_t key_tiles_per_split;
+  int32_t workgroup_shape;   /* 0: 4 waves; 1: 8 waves, two groups on the same rows alternating key tiles;
+                                2: 8 waves, two groups on different rows sharing every key tile (bf16 only) */
+  int32_t ring_stages;       /* K/V tiles the LDS ring of a workgroup holds per group (2..4) */
 } sdllm_attn_plan;
 
 int sdllm_plan_attention(const sdllm_attn_params* p, sdllm_attn_plan* plan);

@@ -70,7 +70,8 @@ class RopeParams(ctypes.Structure):
 
 class AttnPlan(ctypes.Structure):
     _fields_ = [("kv_splits", ctypes.c_int32), ("rows_per_workgroup", ctypes.c_int32),
-                ("workgroups", ctypes.c_int32), ("key_tiles_per_split", ctypes.c_int32)]
+                ("workgroups", ctypes.c_int32), ("key_tiles_per_split", ctypes.c_int32),
+                ("workgroup_shape", ctypes.c_int32), ("ring_stages", ctypes.c_int32)]
 
 
 class SdllmError(RuntimeError):

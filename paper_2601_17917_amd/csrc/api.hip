@@ -195,11 +195,13 @@ int sdllm_plan_attention(const sdllm_attn_params* p, sdllm_attn_plan* plan) {
     plan->kv_splits = 1; plan->rows_per_workgroup = 4;
     plan->workgroups = ((p->K + p->n_keep + 3) / 4) * p->Hq * p->B;
     plan->key_tiles_per_split = (p->prefix_len + p->K + p->n_keep + 63) / 64;
+    plan->workgroup_shape = 0; plan->ring_stages = 2;
     return SDLLM_OK;
   }
   sdllm::AttnPlan pl = sdllm::plan_attention_bf16(*p);
   plan->kv_splits = pl.kv_splits; plan->rows_per_workgroup = 64 * pl.rb * (pl.mode == 2 ? 2 : 1);
   plan->workgroups = pl.workgroups; plan->key_tiles_per_split = pl.tiles_per_split;
+  plan->workgroup_shape = pl.mode; plan->ring_stages = pl.stages;
   return SDLLM_OK;
 }
 

@@ -40,7 +40,7 @@ def test_struct_layouts_match_header():
     assert sd.UnmaskParams.ld.offset == 16
     assert ctypes.sizeof(sd.AppendParams) == 48
     assert sd.AppendParams.cache_layer_stride.offset == 32
-    assert ctypes.sizeof(sd.AttnPlan) == 16
+    assert ctypes.sizeof(sd.AttnPlan) == 24
     assert ctypes.sizeof(sd.LmHeadPlan) == 28
     assert ctypes.sizeof(sd.LmHeadParams) == 64
     assert sd.LmHeadParams.ld_h.offset == 16 and sd.LmHeadParams.tau0.offset == 32
@@ -109,6 +109,26 @@ def test_plan_is_consistent(lib):
         assert pl.workgroups >= B * Hkv * pl.kv_splits * q_tiles
         ws = sd.attention_workspace_bytes(p)
         assert ws == (0 if pl.kv_splits == 1 else B * Hq * (K + s) * pl.kv_splits * 130 * 4)
+
+
+def test_plan_picks_the_workgroup_shape_from_the_parameters(lib):
+    """Host-only: which of the three workgroup shapes a launch takes.  One workgroup per CU at most and splits
+    of >= 4 key tiles: two groups on the same rows; K/V heads with >= 512 query rows: two groups on different rows
+    sharing the tiles (256 rows per workgroup, three ring stages); everything else: the 4-wave workgroup."""
+    def plan(B, Hq, Hkv, P, K, S, s, splits=0):
+        return sd.plan_attention(sd.attn_params(sd.BF16, B, Hq, Hkv, 128, P, max(P, 1), K, S, s, 0.0, splits))
+    cfg5 = plan(4, 32, 32, 5120, 64, 960, 64)
+    assert (cfg5.workgroup_shape, cfg5.kv_splits, cfg5.rows_per_workgroup, cfg5.workgroups) == (1, 2, 128, 256)
+    cfg3a = plan(8, 32, 32, 1024, 32, 992, 32)
+    assert (cfg3a.workgroup_shape, cfg3a.kv_splits, cfg3a.rows_per_workgroup) == (1, 1, 64)
+    cfg3b = plan(8, 32, 32, 1024, 32, 992, 992)
+    assert (cfg3b.workgroup_shape, cfg3b.rows_per_workgroup, cfg3b.ring_stages, cfg3b.workgroups) == (2, 256, 3, 1024)
+    cfg4 = plan(16, 28, 4, 512, 32, 224, 32)
+    assert (cfg4.workgroup_shape, cfg4.rows_per_workgroup, cfg4.ring_stages) == (0, 64, 2)
+    cfg2 = plan(1, 32, 32, 608, 32, 128, 32)
+    assert cfg2.workgroup_shape == 0 and cfg2.key_tiles_per_split < 4        # three tiles per split: too short to share
+    fp32 = sd.plan_attention(sd.attn_params(sd.FP32, 1, 4, 4, 64, 64, 64, 32, 224, 16))
+    assert fp32.workgroup_shape == 0
 
 
 @pytest.mark.parametrize("kw,status", [

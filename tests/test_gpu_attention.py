@@ -110,6 +110,40 @@ def test_attention_bf16_slab_paths(gpu_lib, B, Hq, Hkv, D, P, cap, K, S, keep, s
     assert_bf16_close(got, t, P, what="bf16 slab-path")
 
 
+@pytest.mark.parametrize("shape,B,Hq,Hkv,D,P,cap,K,S,keep,splits", [
+    # shape 1: two 4-wave groups on the same rows alternate key tiles and merge through LDS.  Odd and even tile
+    # counts (the second group then has one tile less or as many), ragged last tile, tiles that straddle the cache /
+    # block / suffix borders, gaps in keep_idx, D = 64, a forced split, two query tiles, 32-row waves
+    (1, 1, 2, 2, 128, 300, 300, 32, 40, tuple(range(0, 30)) + (39,), 1),      # 363 keys: 6 tiles, the last ragged
+    (1, 2, 2, 1, 128, 270, 280, 24, 50, tuple(range(3, 43)), 1),              # 334 keys: 6 tiles; nothing on the slab grid
+    (1, 1, 3, 3, 128, 256, 256, 32, 64, tuple(range(0, 32)), 1),              # 320 keys: exactly 5 tiles (odd)
+    (1, 1, 2, 2, 128, 200, 256, 32, 80, tuple(range(0, 80, 2)), 1),           # gathered suffix with gaps: per-row transfers
+    (1, 2, 2, 2, 64, 500, 512, 32, 33, tuple(range(33)), 1),                  # D = 64, 565 keys: 9 tiles
+    (1, 1, 2, 2, 128, 1000, 1024, 32, 64, tuple(range(0, 63)) + (63,), 2),    # two splits of 9 tiles, each shared by two groups
+    (1, 1, 8, 2, 128, 400, 400, 16, 20, tuple(range(0, 16)), 1),              # GQA 4:1, 128 rows per K/V head: two query tiles
+    (1, 1, 1, 1, 128, 4100, 4100, 64, 64, tuple(range(0, 63)) + (63,), 2),    # 128 rows on 4228 keys: 32-row waves, 67 tiles
+    (1, 1, 1, 1, 128, 4100, 4100, 50, 64, tuple(range(0, 40)), 2),            # the same with 90 rows: ragged 32-row blocks
+    # shape 2: two groups on different rows (256 per workgroup) share every key tile through a three-stage ring
+    (2, 1, 4, 1, 128, 100, 128, 64, 70, tuple(range(0, 64)), 0),              # 512 rows = 2 full workgroups, 228 keys: 4 tiles
+    (0, 1, 8, 2, 128, 37, 40, 32, 40, tuple(range(0, 33)), 0),                # 260 rows per head, 2 key tiles: the 4-wave workgroup
+    (2, 1, 9, 1, 128, 70, 70, 32, 40, tuple(range(2, 28)), 0),                # 522 rows: 3 workgroups, the last with 10 rows
+    (2, 2, 8, 1, 64, 130, 140, 32, 60, tuple(range(0, 60, 1))[:36], 0),       # D = 64, 544 rows, 198 keys
+    (2, 1, 16, 2, 128, 5, 8, 32, 33, tuple(range(33)), 0),                    # 520 rows on 70 keys: 2 tiles, ring deeper than the stream
+    (2, 1, 8, 1, 128, 0, 0, 64, 1, (0,), 3),                                  # 520 rows, no cache, forced splits of one tile
+])
+def test_attention_bf16_workgroup_shapes(gpu_lib, shape, B, Hq, Hkv, D, P, cap, K, S, keep, splits):
+    """The 8-wave workgroup shapes at sizes the oracle checks element by element (every output element, the
+    element-wise bf16 bound).  `shape` is the workgroup shape the plan must pick for the case (the split count is
+    given where the automatic one would cut a small batch into splits too short to share)."""
+    sd = gpu_lib
+    t = wl.make_custom_attention_inputs("bf16", B, Hq, Hkv, D, P, max(cap, 1), K, max(S, 1), keep, seed=7 * P + K + len(keep))
+    pl = sd.plan_attention(sd.attn_params(sd.BF16, B, Hq, Hkv, D, P, max(cap, 1), K, max(S, 1), len(keep), 0.0, splits))
+    assert pl.workgroup_shape == shape, (pl.workgroup_shape, pl.kv_splits, pl.key_tiles_per_split)
+    got = run_gpu(sd, t, P, kv_splits=splits)
+    assert_bf16_close(got, t, P, what=f"workgroup shape {pl.workgroup_shape}, {pl.kv_splits} split(s), "
+                                      f"{pl.key_tiles_per_split} tiles per split:")
+
+
 def test_attention_bf16_keep_all_equals_full_context(gpu_lib):
     """Keeping every suffix row = dense attention over the concatenated sequence: feed the same rows
     through the cache operand instead and compare the two GPU results with each other and the oracle."""
