@@ -167,6 +167,7 @@ int sdllm_version(void) { return SDLLM_VERSION; }
 
 int sdllm_init(void) {
   hipError_t e = sdllm::prepare_attention_bf16();
+  if (e == hipSuccess) e = sdllm::prepare_attention_f32();
   if (e == hipSuccess) e = sdllm::prepare_lm_head();
   void* ptr = nullptr;
   if (e == hipSuccess) e = scratch_of_current_device(&ptr);

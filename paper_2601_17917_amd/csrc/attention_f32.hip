@@ -2,10 +2,10 @@
 // after it).  Plain fp32 FMA arithmetic with an accurate exp: this is the correctness-grade
 // path (max-abs error <= 1e-5 against the fp64 definition), not the throughput path.
 //
-// One wave per query row.  Keys are visited in chunks of 64: lane j scores key j of the chunk
-// (dot product over D with 16-byte loads), the chunk's maximum and sum are formed with wave
-// reductions (online softmax), and for the output lane l owns columns l, l+64, ... so that the
-// V rows are read coalesced.
+// A workgroup = four query rows of one (batch, head), one wave per row.  Keys are visited in chunks of 64:
+// the workgroup brings the chunk's K and V rows into LDS with coalesced 16-byte loads (the four waves share
+// them), lane j scores key j of the chunk (dot product over D from LDS), the chunk's maximum and sum are formed
+// with wave reductions (online softmax), and for the output lane l owns columns l, l+64, ...
 #include "common.h"
 
 namespace sdllm {
@@ -35,23 +35,27 @@ __device__ __forceinline__ const float* kv_row(const AttnF32Args& a, const float
   return suffix + (bh * a.S + a.keep_idx[r]) * a.D;
 }
 
+// LDS: K chunk [64][D + 4] (the pad keeps 16-byte alignment and spreads the rows over the banks), V chunk [64][D]
+__host__ __device__ constexpr size_t f32_lds_bytes(int D) { return (size_t)64 * (2 * D + 4) * sizeof(float); }
+
 __global__ __launch_bounds__(64 * kF32Waves) void attention_f32_kernel(AttnF32Args a) {
   __shared__ float q_s[kF32Waves][kF32MaxD];
+  extern __shared__ __attribute__((aligned(16))) float kv_s[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int Nq = a.K + a.n_keep, Nkv = a.P + a.K + a.n_keep;
   const int qi = blockIdx.x * kF32Waves + wave;
   const int hq = blockIdx.y, b = blockIdx.z;
-  const bool valid = qi < Nq;
+  const bool valid = qi < Nq;                // a wave without a row still helps to load and keeps the barriers
   const int kvh = hq / (a.Hq / a.Hkv);
-  const int D = a.D;
+  const int D = a.D, D4 = D / 4, KP = D + 4;
+  float* k_s = kv_s;
+  float* v_s = kv_s + 64 * KP;
   const long long qbh = (long long)b * a.Hq + hq;
   if (valid) {
     const float* qrow = (qi < a.K) ? a.q_block + (qbh * a.K + qi) * D
                                    : a.q_suffix + (qbh * a.S + a.keep_idx[qi - a.K]) * D;
     for (int d = lane; d < D; d += 64) q_s[wave][d] = qrow[d];
   }
-  __syncthreads();
-  if (!valid) return;                        // no barrier below this point
 
   constexpr int kCols = kF32MaxD / 64;       // output columns per lane
   float o[kCols];
@@ -60,13 +64,23 @@ __global__ __launch_bounds__(64 * kF32Waves) void attention_f32_kernel(AttnF32Ar
   float m = -INFINITY, l = 0.f;
 
   for (int k0 = 0; k0 < Nkv; k0 += 64) {
-    const int r = k0 + lane;
+    const int nk = min(64, Nkv - k0);
+    __syncthreads();                         // the previous chunk is consumed (first trip: q_s is written)
+    for (int i = threadIdx.x; i < nk * D4; i += 64 * kF32Waves) {
+      const int j = i / D4, c4 = i - j * D4;
+      const float4 kk = reinterpret_cast<const float4*>(kv_row(a, a.k_cache, a.k_block, a.k_suffix, b, kvh, k0 + j))[c4];
+      const float4 vv = reinterpret_cast<const float4*>(kv_row(a, a.v_cache, a.v_block, a.v_suffix, b, kvh, k0 + j))[c4];
+      *reinterpret_cast<float4*>(k_s + j * KP + 4 * c4) = kk;
+      *reinterpret_cast<float4*>(v_s + j * D + 4 * c4) = vv;
+    }
+    __syncthreads();
+    if (!valid) continue;
     float sc = -INFINITY;
-    if (r < Nkv) {
-      const float4* kr = reinterpret_cast<const float4*>(kv_row(a, a.k_cache, a.k_block, a.k_suffix, b, kvh, r));
+    if (lane < nk) {
+      const float4* kr = reinterpret_cast<const float4*>(k_s + lane * KP);
       float acc = 0.f;
-      for (int d4 = 0; d4 < D / 4; ++d4) {
-        float4 kk = kr[d4];
+      for (int d4 = 0; d4 < D4; ++d4) {
+        const float4 kk = kr[d4];
         const float* qq = &q_s[wave][4 * d4];
         acc = fmaf(qq[0], kk.x, acc); acc = fmaf(qq[1], kk.y, acc);
         acc = fmaf(qq[2], kk.z, acc); acc = fmaf(qq[3], kk.w, acc);
@@ -78,7 +92,7 @@ __global__ __launch_bounds__(64 * kF32Waves) void attention_f32_kernel(AttnF32Ar
     for (int off = 32; off >= 1; off >>= 1) cmax = fmaxf(cmax, __shfl_xor(cmax, off));
     const float m_new = fmaxf(m, cmax);
     const float corr = (m == -INFINITY) ? 0.f : expf(m - m_new);
-    const float p = (r < Nkv) ? expf(sc - m_new) : 0.f;
+    const float p = (lane < nk) ? expf(sc - m_new) : 0.f;
     float psum = p;
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) psum += __shfl_xor(psum, off);
@@ -86,10 +100,9 @@ __global__ __launch_bounds__(64 * kF32Waves) void attention_f32_kernel(AttnF32Ar
     m = m_new;
 #pragma unroll
     for (int c = 0; c < kCols; ++c) o[c] *= corr;
-    const int nk = min(64, Nkv - k0);
     for (int j = 0; j < nk; ++j) {
       const float pj = __shfl(p, j);
-      const float* vr = kv_row(a, a.v_cache, a.v_block, a.v_suffix, b, kvh, k0 + j);
+      const float* vr = v_s + j * D;
 #pragma unroll
       for (int c = 0; c < kCols; ++c) {
         const int d = lane + 64 * c;
@@ -97,6 +110,7 @@ __global__ __launch_bounds__(64 * kF32Waves) void attention_f32_kernel(AttnF32Ar
       }
     }
   }
+  if (!valid) return;
   float* orow = a.out + (qbh * Nq + qi) * D;
   const float inv = 1.0f / l;
 #pragma unroll
@@ -104,6 +118,11 @@ __global__ __launch_bounds__(64 * kF32Waves) void attention_f32_kernel(AttnF32Ar
     const int d = lane + 64 * c;
     if (d < D) orow[d] = o[c] * inv;
   }
+}
+
+hipError_t prepare_attention_f32() {
+  static LdsOptIn st;
+  return ensure_lds_opt_in(reinterpret_cast<const void*>(&attention_f32_kernel), f32_lds_bytes(kF32MaxD), st);
 }
 
 hipError_t launch_attention_f32(const sdllm_attn_params& p,
@@ -123,7 +142,9 @@ hipError_t launch_attention_f32(const sdllm_attn_params& p,
   a.scale = p.scale > 0.f ? p.scale : 1.0f / sqrtf((float)p.D);
   const int Nq = p.K + p.n_keep;
   dim3 grid((Nq + kF32Waves - 1) / kF32Waves, p.Hq, p.B);
-  hipLaunchKernelGGL(attention_f32_kernel, grid, dim3(64 * kF32Waves), 0, stream, a);
+  hipError_t e = prepare_attention_f32();     // opt-in to the LDS size of the largest head dim, once per device
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(attention_f32_kernel, grid, dim3(64 * kF32Waves), f32_lds_bytes(p.D), stream, a);
   return hipGetLastError();
 }
 

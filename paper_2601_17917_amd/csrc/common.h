@@ -29,6 +29,7 @@ inline hipError_t ensure_lds_opt_in(const void* kernel, size_t bytes, LdsOptIn& 
   return hipSuccess;
 }
 hipError_t prepare_attention_bf16();   // every opt-in of the module, for the current device
+hipError_t prepare_attention_f32();
 hipError_t prepare_lm_head();
 
 // ---- attention launch plan (host, pure function of the parameters) ----
