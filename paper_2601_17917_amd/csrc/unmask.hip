@@ -124,11 +124,7 @@ __device__ __forceinline__ Partial reduce_row_slice(const UnmaskArgs& a, int row
   // LDS.  Vectors cover disjoint, increasing id ranges, so the lowest vector index among equal
   // maxima contains the lowest arg-max id; it is located at the end by ONE lane re-reading ONE
   // vector (a per-lane re-read would add a scattered 64-byte fetch per lane to the stream).
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    float m2 = __shfl_xor(m, off); float s2 = __shfl_xor(s, off); int i2 = __shfl_xor(mvec, off);
-    merge_partial(m, s, mvec, m2, s2, i2);
-  }
+  wave_merge_triples(m, s, mvec);
   if ((tid & 63) == 0) red[tid >> 6] = Partial{m, s, mvec};
   __syncthreads();
   int idx = 0x7fffffff;

@@ -2,6 +2,7 @@
 // logits and the vocabulary projection that never stores them) and by the commit kernel.
 #pragma once
 #include "common.h"
+#include <type_traits>
 
 namespace sdllm {
 
@@ -22,6 +23,44 @@ __device__ __forceinline__ void merge_partial(float& m, float& s, int& i, float 
   float b = fast_exp2((m2 - M) * kLog2e);
   s = s * a + s2 * b;
   i = (m2 > m) ? i2 : ((m2 == m) ? min(i, i2) : i);
+  m = M;
+}
+
+// Wave-wide reductions on the vector ALU's own lane network (DPP row operations inside each row of 16 lanes, then
+// the two row swaps): ~10 cycles per step where a shuffle through the LDS crossbar is a memory-pipe round trip.
+// Every lane ends with the result.
+template <typename T, typename F>
+__device__ __forceinline__ T wave_allreduce(T v, F op) {
+  static_assert(sizeof(T) == 4, "32-bit values");
+  auto dpp = [](T x, auto ctrl_c) {
+    constexpr int CTRL = decltype(ctrl_c)::value;
+    return __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+  };
+  v = op(v, dpp(v, std::integral_constant<int, 0xB1>{}));    // quad_perm [1,0,3,2]
+  v = op(v, dpp(v, std::integral_constant<int, 0x4E>{}));    // quad_perm [2,3,0,1]
+  v = op(v, dpp(v, std::integral_constant<int, 0x141>{}));   // row_half_mirror: the other quad of each 8
+  v = op(v, dpp(v, std::integral_constant<int, 0x140>{}));   // row_mirror: the other half of each row of 16
+  // the two swaps exchange rows 1 <-> 0, 3 <-> 2 and then the halves between their two operands (the same value
+  // twice here); the results are copied into scalars before the bit casts (a bit cast applied to a vector element
+  // expression reads element 0 with this compiler)
+  const unsigned u = __builtin_bit_cast(unsigned, v);
+  const auto r16 = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const unsigned a0 = r16[0], a1 = r16[1];
+  v = op(__builtin_bit_cast(T, a0), __builtin_bit_cast(T, a1));
+  const unsigned w = __builtin_bit_cast(unsigned, v);
+  const auto r32 = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+  const unsigned b0 = r32[0], b1 = r32[1];
+  return op(__builtin_bit_cast(T, b0), __builtin_bit_cast(T, b1));
+}
+
+// (max, sum of exp relative to the max, lowest index among the lanes that hold the max) of a wave's 64 lane triples:
+// maximum first, one rescale per lane, then plain sums -- the same result as 63 pairwise merges up to rounding order
+__device__ __forceinline__ void wave_merge_triples(float& m, float& s, int& idx) {
+  const float M = wave_allreduce(m, [](float a, float b) { return fmaxf(a, b); });
+  s *= fast_exp2((m - M) * kLog2e);
+  idx = (m == M) ? idx : 0x7fffffff;
+  s = wave_allreduce(s, [](float a, float b) { return a + b; });
+  idx = wave_allreduce(idx, [](int a, int b) { return min(a, b); });
   m = M;
 }
 
