@@ -44,6 +44,43 @@ def test_noalloc_matches_workspace_entry_point_twice_in_a_row(gpu_lib):
         assert (got[3] >= 1).all()
 
 
+def test_noalloc_call_replays_from_a_captured_graph(gpu_lib):
+    """What the entry point is for: recorded into a HIP graph (no allocation, no workspace to keep alive) and
+    replayed, with eager work between the replays; every replay must equal the eager workspace entry point."""
+    sd = gpu_lib
+    sd.init()                                            # scratch address looked up before the capture
+    w = wl.WORKLOADS["small_bf16"]
+    u = wl.make_unmask_inputs(w, seed=4)
+    want = _run(sd, sd.confidence_unmask, u, w)
+    lg = to_dev(u["logits"])
+    tok0, msk0 = torch.from_numpy(u["tokens"]).cuda(), torch.from_numpy(u["masked"]).cuda()
+    tk, mk = tok0.clone(), msk0.clone()
+    B, K = u["tokens"].shape
+    conf = torch.full((B, K), -7.0, dtype=torch.float32, device="cuda")
+    es = torch.zeros((B,), dtype=torch.uint8, device="cuda")
+    ncom = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+    done = torch.full((B,), 9, dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        call = sd.bind_confidence_unmask_noalloc(lg, tk, mk, w.tau0, w.alpha, confidence=conf, n_committed=ncom,
+                                                 block_done=done, eos_seen=es, eos_id=3, stream=side)
+        torch.cuda.synchronize()
+        graph.capture_begin()
+        call()
+        graph.capture_end()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        tk.copy_(tok0); mk.copy_(msk0); conf.fill_(-7.0); es.zero_(); ncom.fill_(-1); done.fill_(9)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [x.cpu().numpy() for x in (tk, mk, conf, ncom, done, es)]
+        for g, x, what in zip(got, want, ("tokens", "masked", "confidence", "n_committed", "block_done", "eos_seen")):
+            assert g.tobytes() == x.tobytes(), (rep, what)
+
+
 def test_noalloc_rejects_sizes_beyond_its_scratch(gpu_lib):
     sd = gpu_lib
     lib = sd.load_library()
