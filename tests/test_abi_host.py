@@ -111,6 +111,38 @@ def test_plan_is_consistent(lib):
         assert ws == (0 if pl.kv_splits == 1 else B * Hq * (K + s) * pl.kv_splits * 130 * 4)
 
 
+def test_plan_invariants_over_random_parameters(lib):
+    """Host-only: for a few hundred seeded random parameter sets the plan covers every key tile exactly once with
+    non-empty splits, launches enough workgroups for every (K/V head, split, query tile), uses the 8-wave shapes
+    only where they are built for, and the workspace query matches it."""
+    import numpy as np
+    g = np.random.Generator(np.random.Philox(key=2024))
+    seen = set()
+    for _ in range(400):
+        D = int(g.choice([64, 128])); Hkv = int(g.integers(1, 33)); ratio = int(g.choice([1, 2, 4, 7, 8]))
+        B = int(g.integers(1, 17)); K = int(g.choice([1, 16, 32, 64])); P = int(g.integers(0, 9000))
+        S = int(g.choice([0, 32, 224, 992])); s = int(g.integers(0, S + 1)); splits = int(g.choice([0, 0, 0, 1, 2, 5]))
+        p = sd.attn_params(sd.BF16, B, ratio * Hkv, Hkv, D, P, max(P, 1), K, S, s, 0.0, splits)
+        pl = sd.plan_attention(p)
+        key_tiles = -(-(P + K + s) // 64)
+        rows = ratio * (K + s)
+        assert 1 <= pl.kv_splits <= max(key_tiles, 1) and pl.key_tiles_per_split >= 1
+        assert (pl.kv_splits - 1) * pl.key_tiles_per_split < key_tiles <= pl.kv_splits * pl.key_tiles_per_split
+        if splits:
+            assert pl.kv_splits <= splits
+        q_tiles = -(-rows // pl.rows_per_workgroup)
+        assert pl.workgroups >= B * Hkv * pl.kv_splits * q_tiles and pl.workgroups % 8 == 0
+        assert pl.workgroup_shape in (0, 1, 2) and 2 <= pl.ring_stages <= 4
+        if pl.workgroup_shape == 2:
+            assert rows >= 512 and pl.rows_per_workgroup in (128, 256)
+        if pl.workgroup_shape == 1:
+            assert pl.workgroups <= 256 and pl.key_tiles_per_split >= 4 and pl.ring_stages == 2
+        ws = sd.attention_workspace_bytes(p)
+        assert ws == (0 if pl.kv_splits == 1 else B * ratio * Hkv * (K + s) * pl.kv_splits * (D + 2) * 4)
+        seen.add(pl.workgroup_shape)
+    assert seen == {0, 1, 2}
+
+
 def test_plan_picks_the_workgroup_shape_from_the_parameters(lib):
     """Host-only: which of the three workgroup shapes a launch takes.  One workgroup per CU at most and splits
     of >= 4 key tiles: two groups on the same rows; K/V heads with >= 512 query rows: two groups on different rows

@@ -144,6 +144,36 @@ def test_attention_bf16_workgroup_shapes(gpu_lib, shape, B, Hq, Hkv, D, P, cap, 
                                       f"{pl.key_tiles_per_split} tiles per split:")
 
 
+def _random_case(seed):
+    """A seeded random problem: small enough for the oracle, wide enough to reach every workgroup shape, both head
+    dims, GQA ratios up to 8, empty caches / suffixes, forced and automatic key splits."""
+    g = np.random.Generator(np.random.Philox(key=1000 + seed))
+    D = int(g.choice([64, 128]))
+    Hkv = int(g.integers(1, 4))
+    ratio = int(g.choice([1, 1, 2, 4, 7, 8]))
+    B = int(g.integers(1, 4))
+    K = int(g.choice([1, 7, 16, 32, 33, 64]))
+    P = int(g.choice([0, 5, 63, 64, 130, 333, 700, 1500]))
+    cap = P + int(g.integers(0, 40))
+    S = int(g.choice([0, 1, 9, 40, 80]))
+    n_keep = int(g.integers(0, S + 1))
+    keep = tuple(sorted(g.choice(S, size=n_keep, replace=False).tolist())) if n_keep else ()
+    splits = int(g.choice([0, 0, 1, 2, 3]))
+    return B, ratio * Hkv, Hkv, D, P, cap, K, S, keep, splits
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_attention_bf16_random_shapes(gpu_lib, seed):
+    """Seeded random shapes against the oracle, every output element, with the element-wise bf16 bound."""
+    sd = gpu_lib
+    B, Hq, Hkv, D, P, cap, K, S, keep, splits = _random_case(seed)
+    t = wl.make_custom_attention_inputs("bf16", B, Hq, Hkv, D, P, max(cap, 1), K, max(S, 1), keep, seed=seed)
+    pl = sd.plan_attention(sd.attn_params(sd.BF16, B, Hq, Hkv, D, P, max(cap, 1), K, max(S, 1), len(keep), 0.0, splits))
+    got = run_gpu(sd, t, P, kv_splits=splits)
+    assert_bf16_close(got, t, P, what=f"seed {seed}: B{B} H{Hq}/{Hkv} D{D} P{P} K{K} kept {len(keep)}/{S}, shape "
+                                      f"{pl.workgroup_shape}, {pl.kv_splits} split(s) of {pl.key_tiles_per_split} tiles:")
+
+
 def test_attention_bf16_keep_all_equals_full_context(gpu_lib):
     """Keeping every suffix row = dense attention over the concatenated sequence: feed the same rows
     through the cache operand instead and compare the two GPU results with each other and the oracle."""
