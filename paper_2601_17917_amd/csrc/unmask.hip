@@ -181,10 +181,13 @@ __device__ __forceinline__ void commit_sequence(const UnmaskArgs& a, int b, floa
           if (k0 + u * P2 < a.nsplit) merge_partial(m, s, idx, q[u].m, q[u].s, q[u].idx);
       }
     }
-    for (int off = P2 >> 1; off >= 1; off >>= 1) {
-      float m2 = __shfl_xor(m, off); float s2 = __shfl_xor(s, off); int i2 = __shfl_xor(idx, off);
-      merge_partial(m, s, idx, m2, s2, i2);
-    }
+    // butterfly over the P2 adjacent lanes of a position (P2 is uniform), fixed pattern, lane network only
+    if (P2 >= 2)  merge_partial(m, s, idx, lane_partner<0>(m), lane_partner<0>(s), lane_partner<0>(idx));
+    if (P2 >= 4)  merge_partial(m, s, idx, lane_partner<1>(m), lane_partner<1>(s), lane_partner<1>(idx));
+    if (P2 >= 8)  merge_partial(m, s, idx, lane_partner<2>(m), lane_partner<2>(s), lane_partner<2>(idx));
+    if (P2 >= 16) merge_partial(m, s, idx, lane_partner<3>(m), lane_partner<3>(s), lane_partner<3>(idx));
+    if (P2 >= 32) merge_partial(m, s, idx, lane_partner<4>(m), lane_partner<4>(s), lane_partner<4>(idx));
+    if (P2 >= 64) merge_partial(m, s, idx, lane_partner<5>(m), lane_partner<5>(s), lane_partner<5>(idx));
     if (in && k == 0) {
       float c = 0.f;
       if (is_masked) {
@@ -229,10 +232,10 @@ __device__ __forceinline__ void commit_sequence(const UnmaskArgs& a, int b, floa
     if (c > bc) { bc = c; bi = i; }       // ascending i: strict > keeps the lowest position
   }
   if (my_thr) atomicAdd(&cnt_thr, my_thr);
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    float c2 = __shfl_xor(bc, off); int i2 = __shfl_xor(bi, off);
-    if (c2 > bc || (c2 == bc && i2 < bi)) { bc = c2; bi = i2; }
+  {   // the wave's best candidate: highest confidence, lowest position among equals
+    const float wave_c = wave_allreduce(bc, [](float x, float y) { return fmaxf(x, y); });
+    bi = wave_allreduce(bc == wave_c ? bi : 0x7fffffff, [](int x, int y) { return min(x, y); });
+    bc = wave_c;
   }
   if ((tid & 63) == 0) { best_c[tid >> 6] = bc; best_i[tid >> 6] = bi; }
   __syncthreads();

@@ -53,6 +53,30 @@ __device__ __forceinline__ T wave_allreduce(T v, F op) {
   return op(__builtin_bit_cast(T, b0), __builtin_bit_cast(T, b1));
 }
 
+// The value a partner lane holds, for a butterfly over groups of 2^(LEVEL+1) adjacent lanes: level 0 / 1 pair lane i
+// with i ^ 1 / i ^ 2, level 2 / 3 mirror inside 8 / 16 lanes (lane i with 7 - i / 15 - i: the partner lies in the other
+// half of the group, which is all a butterfly needs once both halves are reduced), level 4 / 5 take the same lane of
+// the neighbouring row of 16 / the other half of the wave.  All on the vector ALU's lane network.
+template <int LEVEL, typename T>
+__device__ __forceinline__ T lane_partner(T x) {
+  static_assert(sizeof(T) == 4 && LEVEL >= 0 && LEVEL <= 5, "32-bit values, 64 lanes");
+  const int xi = __builtin_bit_cast(int, x);
+  if constexpr (LEVEL < 4) {
+    constexpr int CTRL = LEVEL == 0 ? 0xB1 : LEVEL == 1 ? 0x4E : LEVEL == 2 ? 0x141 : 0x140;
+    return __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(0, xi, CTRL, 0xf, 0xf, true));
+  } else if constexpr (LEVEL == 4) {
+    const auto r = __builtin_amdgcn_permlane16_swap((unsigned)xi, (unsigned)xi, false, false);
+    const unsigned even_rows = r[1], odd_rows = r[0];      // [r1,r1,r3,r3] and [r0,r0,r2,r2]
+    const bool odd = (__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)) >> 4) & 1;
+    return __builtin_bit_cast(T, odd ? odd_rows : even_rows);
+  } else {
+    const auto r = __builtin_amdgcn_permlane32_swap((unsigned)xi, (unsigned)xi, false, false);
+    const unsigned lo_half = r[1], hi_half = r[0];         // [hi,hi] and [lo,lo]
+    const bool hi = (__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)) >> 5) & 1;
+    return __builtin_bit_cast(T, hi ? hi_half : lo_half);
+  }
+}
+
 // (max, sum of exp relative to the max, lowest index among the lanes that hold the max) of a wave's 64 lane triples:
 // maximum first, one rescale per lane, then plain sums -- the same result as 63 pairwise merges up to rounding order
 __device__ __forceinline__ void wave_merge_triples(float& m, float& s, int& idx) {
