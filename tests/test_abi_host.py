@@ -34,6 +34,21 @@ def test_exports_every_declared_symbol(lib):
     assert "sdllm_probe_" not in re.sub(r"/\*.*?\*/", "", main, flags=re.S)
 
 
+def test_headers_compile_as_plain_c(tmp_path):
+    """The boundary is a C ABI: both headers must compile as C99 on their own, without warnings."""
+    import shutil, subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "c.c"
+    src.write_text('#include "sdllm.h"\n#include "sdllm_diag.h"\n'
+                   'int main(void) { sdllm_attn_params a; sdllm_unmask_params u; sdllm_append_params k; (void)a; (void)u; (void)k;\n'
+                   '  return sdllm_version() == SDLLM_VERSION ? 0 : 1; }\n')
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+                        "-c", str(src), "-o", str(tmp_path / "c.o")], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+
+
 def test_struct_layouts_match_header():
     assert ctypes.sizeof(sd.AttnParams) == 12 * 4
     assert ctypes.sizeof(sd.UnmaskParams) == 48
