@@ -33,8 +33,6 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 constexpr int kKeyTile = 64;
-constexpr int kDeepStages = 3;    // ring depth of the launches that have one workgroup per CU ...
-constexpr bool kTwoGroups = true; // ... unless they run two 4-wave groups per workgroup
 constexpr bool kShareTiles = true;   // 8-wave workgroups with row-split groups for heads with many query rows
 constexpr int kShareMinRows = 512;   // ... from this many query rows per K/V head
 constexpr int kShareStages = 3;
@@ -438,11 +436,11 @@ __device__ __forceinline__ void compute_tile(const AttnArgs& a, const Lane<D>& L
 //   groups take turns moving tiles into the ring (group g moves tiles t0 + g, t0 + g + 2, ...).  Two waves per SIMD
 //   from one workgroup, and a K/V tile is brought into LDS once per 128 RB query rows instead of once per 64 RB.
 template <int D, int RB, bool ONCE, int NST, int MODE>
-__global__ __launch_bounds__(MODE ? 512 : 256, (MODE || NST > 2) ? 1 : 2) void attn_bf16_kernel(AttnArgs a) {
+__global__ __launch_bounds__(MODE ? 512 : 256, MODE ? 1 : 2) void attn_bf16_kernel(AttnArgs a) {
   constexpr int NG = (MODE == 1) ? 2 : 1;          // key tiles per ring stage
   constexpr int STEP = MODE ? 2 : 1;               // distance between the tiles one group moves
   using S = Shape<D, NST, NG>;
-  static_assert(MODE == 0 || NST <= 3, "the wait below assumes at most one older tile of a group in flight");
+  static_assert(MODE == 2 ? (NST == 2 || NST == 3) : NST == 2, "ring depths that are built");
   constexpr int CPR = S::CPR, RPI = S::RPI, IPT = S::IPT, R256 = S::R256, NS = S::NS, NDB = S::NDB, ROWB = S::ROWB;
   // LDS rows are unpadded (a transfer writes 1 KiB contiguous); bank conflicts are avoided by
   // storing chunk c of row r at position c ^ f(r):  f_K(r) = (r / R256) % CPR makes the 16 rows of
@@ -537,18 +535,13 @@ __global__ __launch_bounds__(MODE ? 512 : 256, (MODE || NST > 2) ? 1 : 2) void a
     for (int db = 0; db < NDB; ++db) o[rb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  // NST steps per trip so that the ring stage is a compile-time constant; in step i every group works on its tile
-  // tg0 + NG i (a group whose tile lies past the split's end only keeps the barriers).  Per step: wait for the
-  // tile's transfers (every tile is 2 IPT transfers of this wave and transfers complete in issue order, so all but
-  // those of the NST - 2 younger tiles in flight must be done; towards the end of the split fewer are in flight),
-  // barrier (every wave's part has landed and the previous step's tiles are consumed), put the tile of step
-  // i + NST - 1 in flight into the stage just freed, compute.  The query-row loads are complete after the first
-  // wait, so the compiler places no vector-memory wait of its own inside the loop.
-  constexpr int PER_TILE = 2 * IPT;                // transfers of one wave per tile
-  // where the first wait of the loop leaves transfers in flight (a deeper ring) or is skipped by some waves (MODE 2),
-  // complete everything once here: the query-row loads were issued after the first transfers, and the compiler
-  // would otherwise wait for them inside the loop
-  if constexpr (NST > 2 || MODE == 2) wait_vmcnt<0>();
+  // NST steps per trip so that the ring stage is a compile-time constant.  Per step: wait for the tile's transfers
+  // (transfers complete in issue order; a wave never has a younger tile in flight when it waits, so the wait is
+  // vmcnt(0)), barrier (every wave's part has landed and the previous step's tiles are consumed), put the next tile
+  // in flight into the stage just freed, compute.  The query-row loads are complete after the first wait, so the
+  // compiler places no vector-memory wait of its own inside the loop; in MODE 2 half of the waves skip that first
+  // wait, so everything is completed once before the loop.
+  if constexpr (MODE == 2) wait_vmcnt<0>();
   if constexpr (MODE == 2) {
     // step s works on tile t0 + s in stage s % NST; the tile was moved by group s & 1, whose waves have nothing
     // younger in flight when they wait for it (their next tile, t0 + s + 2, goes in flight during this step or later)
@@ -571,20 +564,13 @@ __global__ __launch_bounds__(MODE ? 512 : 256, (MODE || NST > 2) ? 1 : 2) void a
       }
     }
   } else {
+    static_assert(NST == 2, "modes 0 and 1 are built with two ring stages");
     auto tile_step = [&](auto stage_c, int t) {    // t: this group's tile of the step
       constexpr int STAGE = decltype(stage_c)::value;
-      if constexpr (NST == 2) {
-        wait_vmcnt<0>();
-      } else if constexpr (NST == 3) {
-        if (t + NG < t1) wait_vmcnt<PER_TILE>(); else wait_vmcnt<0>();
-      } else {
-        if (t + 2 * NG < t1) wait_vmcnt<2 * PER_TILE>();
-        else if (t + NG < t1) wait_vmcnt<PER_TILE>();
-        else wait_vmcnt<0>();
-      }
+      wait_vmcnt<0>();                             // only this tile's transfers are in flight
       __builtin_amdgcn_s_barrier();
-      if (t + NG * (NST - 1) < t1)
-        issue_tile<D, ONCE, NST, NG, STEP>(a, L, R, kc, vc, kb, vb, ks, vs, t + NG * (NST - 1), (STAGE + NST - 1) % NST, ka);
+      if (t + NG < t1)
+        issue_tile<D, ONCE, NST, NG, STEP>(a, L, R, kc, vc, kb, vb, ks, vs, t + NG, (STAGE + 1) % 2, ka);
       if (NG == 1 || t < t1) compute_tile<D, RB, STAGE, NG>(a, L, lds, t, qreg, o, m, thr, lsum);
     };
     // the trip count depends on the split only (t0, t1), not on the group: every wave meets every barrier
@@ -592,14 +578,6 @@ __global__ __launch_bounds__(MODE ? 512 : 256, (MODE || NST > 2) ? 1 : 2) void a
       tile_step(std::integral_constant<int, 0>{}, t + L.grp);
       if (t + NG >= t1) break;
       tile_step(std::integral_constant<int, 1>{}, t + NG + L.grp);
-      if constexpr (NST >= 3) {
-        if (t + 2 * NG >= t1) break;
-        tile_step(std::integral_constant<int, 2>{}, t + 2 * NG + L.grp);
-      }
-      if constexpr (NST >= 4) {
-        if (t + 3 * NG >= t1) break;
-        tile_step(std::integral_constant<int, 3>{}, t + 3 * NG + L.grp);
-      }
     }
   }
 
@@ -754,15 +732,11 @@ AttnPlan plan_attention_bf16(const sdllm_attn_params& p) {
   pl.kv_splits = (pl.key_tiles + pl.tiles_per_split - 1) / pl.tiles_per_split;   // no empty split
   const long long units = (long long)p.B * p.Hkv * pl.kv_splits;
   pl.workgroups = (int)(((units + kNumXCDs - 1) / kNumXCDs) * kNumXCDs * pl.q_tiles);
-  // Ring depth.  Two stages let two workgroups share a CU (two tiles in flight per CU).  Where the launch has at
-  // most one workgroup per CU anyway and a split is long enough to fill it, one workgroup keeps kDeepStages - 1
-  // tiles in flight by itself.
-  if (pl.mode == 0 && pl.workgroups <= kNumCUs) {
-    // ... or two 4-wave groups of one workgroup alternate its key tiles (two waves per SIMD, the groups' partial
-    // results merged in LDS: mode 1)
-    if (kTwoGroups && pl.tiles_per_split >= 4) pl.mode = 1;
-    else if (pl.q_tiles == 1 && pl.tiles_per_split >= 2 * kDeepStages) pl.stages = kDeepStages;
-  }
+  // Two ring stages let two 4-wave workgroups share a CU (two tiles in flight per CU).  Where the launch has at most
+  // one workgroup per CU anyway and a split is long enough, two 4-wave groups of one workgroup alternate its key
+  // tiles instead (two waves per SIMD, the groups' partial results merged in LDS: mode 1).  (A deeper ring in the
+  // 4-wave workgroup, three or four stages, measured no faster on any shape.)
+  if (pl.mode == 0 && pl.workgroups <= kNumCUs && pl.tiles_per_split >= 4) pl.mode = 1;
   return pl;
 }
 
@@ -795,12 +769,9 @@ static hipError_t launch_rb(const AttnArgs& a, const AttnPlan& pl, hipStream_t s
   if (pl.mode == 2)           // row-split groups sharing the tiles (several query tiles per K/V head)
     return pl.stages == 3 ? launch_main<D, RB, false, 3, 2>(a, pl, stream, launch)
                           : launch_main<D, RB, false, 2, 2>(a, pl, stream, launch);
-  // one query tile per K/V head (and split): every K/V byte is read by one workgroup only (nontemporal hint);
-  // the deeper rings are only built for that case (the plan asks for them only there)
+  // one query tile per K/V head (and split): every K/V byte is read by one workgroup only (nontemporal hint)
   if (pl.q_tiles == 1) {
     if (pl.mode == 1) return launch_main<D, RB, true, 2, 1>(a, pl, stream, launch);
-    if (pl.stages == 4) return launch_main<D, RB, true, 4, 0>(a, pl, stream, launch);
-    if (pl.stages == 3) return launch_main<D, RB, true, 3, 0>(a, pl, stream, launch);
     return launch_main<D, RB, true, 2, 0>(a, pl, stream, launch);
   }
   if (pl.mode == 1) return launch_main<D, RB, false, 2, 1>(a, pl, stream, launch);
@@ -819,10 +790,9 @@ hipError_t prepare_attention_bf16() {
   for (int rb = 1; rb <= 2; ++rb)
     for (int q_tiles = 1; q_tiles <= 2; ++q_tiles)
       for (int mode = 0; mode <= 2; ++mode)
-        for (int stages = 2; stages <= 4; ++stages) {
-          if (mode == 1 && stages > 2) continue;
-          if (mode == 2 && (stages > 3 || q_tiles == 1)) continue;
-          if (mode == 0 && stages > 2 && q_tiles > 1) continue;
+        for (int stages = 2; stages <= 3; ++stages) {
+          if (mode != 2 && stages > 2) continue;
+          if (mode == 2 && q_tiles == 1) continue;
           pl.rb = rb; pl.q_tiles = q_tiles; pl.stages = stages; pl.mode = mode;
           if (e == hipSuccess) e = launch_d<128>(a, pl, nullptr, false);
           if (e == hipSuccess) e = launch_d<64>(a, pl, nullptr, false);
