@@ -34,19 +34,39 @@ def test_exports_every_declared_symbol(lib):
     assert "sdllm_probe_" not in re.sub(r"/\*.*?\*/", "", main, flags=re.S)
 
 
-def test_headers_compile_as_plain_c(tmp_path):
-    """The boundary is a C ABI: both headers must compile as C99 on their own, without warnings."""
+def test_headers_compile_as_plain_c_and_a_c_program_links(tmp_path, lib):
+    """The boundary is a C ABI: both headers compile as C99 without warnings, and a plain C program links against
+    the library and calls it (host-only entry points: no GPU needed)."""
     import shutil, subprocess
     gcc = shutil.which("gcc")
     if gcc is None:
         pytest.skip("no gcc")
     src = tmp_path / "c.c"
-    src.write_text('#include "sdllm.h"\n#include "sdllm_diag.h"\n'
-                   'int main(void) { sdllm_attn_params a; sdllm_unmask_params u; sdllm_append_params k; (void)a; (void)u; (void)k;\n'
-                   '  return sdllm_version() == SDLLM_VERSION ? 0 : 1; }\n')
+    src.write_text('''#include <stdio.h>
+#include "sdllm.h"
+#include "sdllm_diag.h"
+int main(void) {
+  sdllm_attn_params a = {SDLLM_BF16, 4, 32, 32, 128, 5120, 6144, 64, 960, 64, 0.0f, 0};
+  sdllm_attn_plan pl;
+  int32_t idx[80], n = 0;
+  if (sdllm_version() != SDLLM_VERSION) return 1;
+  if (sdllm_plan_attention(&a, &pl) != SDLLM_OK || pl.kv_splits != 2 || pl.workgroups != 256) return 2;
+  if (sdllm_suffix_keep_indices(960, 64, 1, 1, idx, 80, &n) != SDLLM_OK || n != 65 || idx[63] != 63 || idx[64] != 959) return 3;
+  a.D = 96;
+  if (sdllm_plan_attention(&a, &pl) != SDLLM_ERR_UNSUPPORTED || sdllm_last_error()[0] == 0) return 4;
+  if (sdllm_probe_read(NULL, 0, NULL, NULL) != SDLLM_ERR_INVALID_ARG) return 5;
+  printf("ok %s\\n", sdllm_status_string(SDLLM_OK));
+  return 0;
+}
+''')
+    exe = tmp_path / "c_prog"
+    libdir = os.path.dirname(sd.LIB_PATH)
     r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
-                        "-c", str(src), "-o", str(tmp_path / "c.o")], capture_output=True, text=True)
+                        str(src), "-o", str(exe), "-L", libdir, "-l:libsdllm.so", "-Wl,-rpath," + libdir,
+                        "-Wl,-rpath,/opt/rocm/lib"], capture_output=True, text=True)
     assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and r.stdout.startswith("ok ok"), (r.returncode, r.stdout, r.stderr[-500:])
 
 
 def test_struct_layouts_match_header():
