@@ -363,7 +363,8 @@ def main():
     # the attention call: mean over the layers of a step (events before the first and after the last layer); the
     # first layer's own duration is reported too (it follows the previous step's append and reads 3-4 % slower)
     layer0_ms_ev, unmask_ms_ev, append_ms_ev = ev_mean(0, 1), ev_mean(2, 3), ev_mean(3, 4)
-    attn_ms_ev = ev_mean(0, 2) / w.n_layers if use_ev else None
+    # (a single-layer workload has just the one call between events 0 and 1; going on to event 2 would add an event)
+    attn_ms_ev = (ev_mean(0, 2) / w.n_layers if w.n_layers > 1 else layer0_ms_ev) if use_ev else None
     attn_bytes = w.attn_bytes()
     attn_flops = w.attn_flops()
     intensity = attn_flops / attn_bytes
@@ -487,8 +488,9 @@ def main():
                  "launch_ms": dur, "algorithmic_bytes": attn_bytes, "algorithmic_flops": attn_flops,
                  "frac_mfma_peak": (attn_flops / dur / 1e9 / MFMA_BF16_PEAK_TFLOPS) if dur and w.dtype == "bf16" else None,
                  "layer0_launch_ms": layer0_ms_ev,
-                 "events": (f"HIP events before the first and after the last attention call of {len(evs)} of {K} timed "
-                            f"steps, divided by the {w.n_layers} layer(s)") if use_ev else None})
+                 "events": ((f"HIP events before the first and after the last attention call of {len(evs)} of {K} timed "
+                             f"steps, divided by the {w.n_layers} layers") if w.n_layers > 1 else
+                            f"HIP events around the attention call of {len(evs)} of {K} timed steps") if use_ev else None})
     # the other two calls of the step, each bracketed by HIP events inside the timed region (same steps)
     elems = masked_rows * w.V
     # plain-ALU roof of the row reduction: vector-ALU issue slots per logit (a wave-wide instruction occupies its
