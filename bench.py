@@ -377,7 +377,7 @@ def main():
         st.attention[rot[0] % len(st.attention)]()
         rot[0] += 1
 
-    t_attn = time_kernel(attention_rotating)
+    t_attn = time_kernel(attention_rotating, iters=300, warm=100)    # long enough to sit at the steady clock
     # the unmask call alone: HIP events around the real call, the state slot restored (untimed) before every call
     tok_fresh, msk_fresh = to_dev(st.host_unmask["tokens"]), to_dev(st.host_unmask["masked"])
 
