@@ -656,19 +656,22 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a, long long
   // the first four splits' loads go out together with their (max, sum) pairs: the common maximum needs only the
   // latter, so a row costs one memory round trip (more than four splits: the remaining maxima are read first)
   f32x4 ov[4]; float mk[4], lk[4];
-  auto load_batch = [&](int k0) {
+  auto load_batch = [&](int k0) {                  // splits past the last one: weight 0 (uniform branches, no loads)
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const int k = min(k0 + u, a.nsplit - 1);
-      ov[u] = *reinterpret_cast<const f32x4*>(po + (long long)k * D);
-      mk[u] = ml[2 * k]; lk[u] = ml[2 * k + 1];
+      ov[u] = f32x4{0.f, 0.f, 0.f, 0.f}; mk[u] = kNegBigA; lk[u] = 0.f;
+      if (k0 + u < a.nsplit) {
+        const int k = k0 + u;
+        ov[u] = *reinterpret_cast<const f32x4*>(po + (long long)k * D);
+        mk[u] = ml[2 * k]; lk[u] = ml[2 * k + 1];
+      }
     }
   };
   load_batch(0);
   float M = kNegBigA;
   for (int k = 4; k < a.nsplit; ++k) M = fmaxf(M, ml[2 * k]);
 #pragma unroll
-  for (int u = 0; u < 4; ++u) M = fmaxf(M, mk[u]);     // entries past nsplit repeat the last split
+  for (int u = 0; u < 4; ++u) M = fmaxf(M, mk[u]);
   float L = 0.f;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   for (int k0 = 0; k0 < a.nsplit; k0 += 4) {
