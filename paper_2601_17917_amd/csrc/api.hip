@@ -8,6 +8,12 @@
 #include <vector>
 #include <atomic>
 
+// ---- the device-resident scratch of sdllm_confidence_unmask_noalloc (file scope).  Every GPU the library runs on
+// holds its own copy of the array at its own address; in host code the array's name is only a handle for the symbol
+// lookup, never an address: the per-device address found by scratch_of_current_device() is what kernels and runtime
+// calls are given.
+static __device__ __align__(256) unsigned char scratch[SDLLM_NOALLOC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local char g_err[512] = "";
@@ -134,11 +140,6 @@ int check_rope_params(const sdllm_rope_params* p) {
     return fail(SDLLM_ERR_UNSUPPORTED, "rope: problem too large");
   return SDLLM_OK;
 }
-
-// ---- the device-resident scratch of sdllm_confidence_unmask_noalloc.  Every GPU the library runs on holds its
-// own copy of the array at its own address; in host code the array's name is only a handle for the symbol
-// lookup, never an address: the per-device address found below is what kernels and runtime calls are given.
-static __device__ __align__(256) unsigned char scratch[SDLLM_NOALLOC_SCRATCH_BYTES];
 
 constexpr int kMaxDevices = 64;
 std::atomic<void*> g_scratch_ptr[kMaxDevices];
