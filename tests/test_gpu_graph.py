@@ -125,3 +125,39 @@ def test_validate_keep_idx_on_device_lists(gpu_lib):
         with pytest.raises(sd.SdllmError) as e:
             sd.validate_keep_idx(bad.cuda(), S)
         assert e.value.status == sd.ERR_INVALID_ARG
+
+
+def test_init_and_first_calls_from_several_threads(gpu_lib):
+    """sdllm_init and the launchers' own first-use set-up are safe when several threads run them at once (the
+    opt-in of a kernel to its LDS size is idempotent and recorded atomically per device)."""
+    import threading
+    sd = gpu_lib
+    w = wl.WORKLOADS["small_bf16"]
+    t = wl.make_attention_inputs(w, seed=77)
+    d = {k: to_dev(v) for k, v in t.items()}
+    torch.cuda.synchronize()
+    outs, errors = [None] * 6, []
+
+    def work(i):
+        try:
+            torch.cuda.set_device(0)
+            sd.init()
+            s = torch.cuda.Stream()
+            s.wait_stream(torch.cuda.default_stream())
+            outs[i] = sd.block_attention(d["q_block"], d["q_suffix"], d["k_cache"], d["v_cache"], d["k_block"], d["v_block"],
+                                         d["k_suffix"], d["v_suffix"], d["keep_idx"], w.P, kv_splits=1 + i % 3, stream=s)
+            s.synchronize()
+        except Exception as e:          # noqa: BLE001
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(6)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors, errors
+    f = {k: (wl.to_f64(v) if k != "keep_idx" else v) for k, v in t.items()}
+    want = oracle.block_attention(f["q_block"], f["q_suffix"], f["k_cache"], f["v_cache"], f["k_block"], f["v_block"],
+                                  f["k_suffix"], f["v_suffix"], f["keep_idx"], w.P)
+    for o in outs:
+        assert np.abs(to_f64_host(o) - want).max() <= 2e-2
