@@ -297,6 +297,9 @@ __device__ __forceinline__ void compute_tile(const AttnArgs& a, const Lane<D>& L
   using S = Shape<D, 2, NG>;
   constexpr int NS = S::NS, NDB = S::NDB;
   constexpr bool kMfmaRowSum = (RB == 1);
+  // the compiler's interleaving strategy for matrix instructions and LDS reads in this block (dense-suffix shape
+  // 269 -> 263 us; the stream-bound shapes do not notice)
+  __builtin_amdgcn_iglp_opt(0);
   // ---- S^T = K Q^T
   f32x4 sacc[RB][4];
 #pragma unroll
