@@ -32,7 +32,7 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # vector-ALU issue slots the unmask rows kernel spends per logit (from its instruction mix per 32 logits of a lane:
 # see the kernel's header comment), v_exp_f32 weighted 2.4
-UNMASK_VALU_SLOTS_PER_ELEMENT = {"bf16": (164 + 33 * 2.4) / 32.0, "fp32": (132 + 33 * 2.4) / 32.0}
+UNMASK_VALU_SLOTS_PER_ELEMENT = {"bf16": (156 + 33 * 2.4) / 32.0, "fp32": (124 + 33 * 2.4) / 32.0}
 
 
 def parse_args():

@@ -8,9 +8,9 @@
 //  2. unmask_commit: one workgroup per sequence merges the triples in a fixed pattern,
 //     forms c_i = 1 / sum, evaluates the threshold, commits, and writes the flags.
 // The rows kernel is bound by its vector arithmetic, not by the stream: per 32 logits of a lane (one trip of four
-// 16-byte bf16 vectors) it issues 197 instructions -- unpack 32, max 24, FMA 31, exp 33, add 31, addressing and
-// bookkeeping 46 -- i.e. (164 + 33 * 2.4) / 32 = 7.6 issue slots per logit with v_exp_f32 at the 2.4 slots it costs
-// against an FMA (fp32 logits need no unpack: 6.6).  On 256 CUs x 4 SIMDs at 2.4 GHz, one wave-wide instruction per
+// 16-byte bf16 vectors) it issues 189 instructions -- unpack 32, max 16, FMA 31, exp 33, add 31, addressing and
+// bookkeeping 46 -- i.e. (156 + 33 * 2.4) / 32 = 7.35 issue slots per logit with v_exp_f32 at the 2.4 slots it costs
+// against an FMA (fp32 logits need no unpack: 6.35).  On 256 CUs x 4 SIMDs at 2.4 GHz, one wave-wide instruction per
 // four cycles, that is the plain-ALU roof the benchmark quotes next to the HBM one.
 // (A single launch in which the last workgroup to arrive commits its sequence was measured
 // and dropped: the device-scope release/acquire fences it needs write back and invalidate
@@ -41,6 +41,27 @@ template <> struct Vec<float> {      // 4 per 16 bytes
   }
 };
 
+// Maximum of the N values of one vector with the three-input instruction, written out: through fmaxf the compiler
+// first canonicalises every value it cannot prove canonical (an extra v_max x, x per unpacked logit pair).  The
+// instruction itself returns the other operand when one is NaN, like fmaxf.
+__device__ __forceinline__ float max3_raw(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+template <int N>
+__device__ __forceinline__ float vector_max(const float (&x)[N]) {
+  static_assert(N == 4 || N == 8, "16-byte vectors of fp32 / bf16");
+  float c = max3_raw(x[0], x[1], x[2]);
+  if constexpr (N == 8) {
+    c = max3_raw(c, x[3], x[4]);
+    c = max3_raw(c, x[5], x[6]);
+    return max3_raw(c, x[7], x[7]);
+  } else {
+    return max3_raw(c, x[3], x[3]);
+  }
+}
+
 // Folds kVecPerIter unpacked vectors per lane (vector indices v0, v0 + 256, ...) into the lane's running
 // (max, sum of exp2 relative to that max, first vector holding the max).  Elements that do not exist
 // hold -inf: they never win the maximum and add exp2(-inf) = 0.
@@ -49,9 +70,7 @@ __device__ __forceinline__ void accumulate_trip(const float (&x)[kVecPerIter][N]
   float bm = m;
 #pragma unroll
   for (int u = 0; u < kVecPerIter; ++u) {
-    float c = x[u][0];
-#pragma unroll
-    for (int j = 1; j < N; ++j) c = fmaxf(c, x[u][j]);
+    const float c = vector_max<N>(x[u]);
     const bool up = c > bm;                // strict: the earliest vector keeps the maximum
     mvec = up ? v0 + u * kRowThreads : mvec;
     bm = up ? c : bm;
