@@ -496,24 +496,11 @@ __global__ __launch_bounds__(MODE ? 512 : 256, MODE ? 1 : 2) void attn_bf16_kern
       L.vro[db] = gofs + S::VBASE + (4 * G + e4) * ROWB + (((2 * db + (c4 >> 1)) ^ fv) << 4) + ((c4 & 1) << 3);
   }
 
-  // ---- the first NST - 1 steps' tiles go in flight, then the query rows
-  const int tg0 = t0 + (MODE ? wgrp : 0);          // the tiles this wave's group moves: tg0, tg0 + STEP, ...
-  const SlabRanges R = slab_ranges(a, wave);
-  KeepAhead ka;
-  load_keep_ahead(a, wave, tg0, ka);
-  if constexpr (MODE == 2) {
-#pragma unroll
-    for (int j = 0; j < NST - 1; ++j)              // tile t0 + j belongs to group j & 1
-      if ((j & 1) == wgrp && t0 + j < t1)
-        issue_tile<D, ONCE, NST, NG, STEP>(a, L, R, kc, vc, kb, vb, ks, vs, t0 + j, j, ka);
-  } else {
-#pragma unroll
-    for (int j = 0; j < NST - 1; ++j)
-      if (tg0 + NG * j < t1) issue_tile<D, ONCE, NST, NG, STEP>(a, L, R, kc, vc, kb, vb, ks, vs, tg0 + NG * j, j, ka);
-  }
-
   // ---- query rows of this wave, as MFMA B operands (lane: row l16, d = 32*s + 8*G .. +7); in MODE 1 both groups
-  // hold the same rows
+  // hold the same rows.  Requested BEFORE the first K/V transfers: a kept suffix row needs its keep_idx entry first,
+  // and the wait for that entry covers everything older in the vector-memory queue -- behind the first tile's
+  // transfers the query rows would only be requested once that tile had landed (two memory round trips in a row
+  // instead of one short one and two in parallel).
   const int row_base = (MODE == 2) ? qt * (128 * RB) + wgrp * (64 * RB) + wave * (16 * RB)
                                    : qt * (64 * RB) + wave * (16 * RB);
   bf16x8 qreg[RB][NS];
@@ -527,6 +514,22 @@ __global__ __launch_bounds__(MODE ? 512 : 256, MODE ? 1 : 2) void attn_bf16_kern
 #pragma unroll
     for (int s = 0; s < NS; ++s)
       qreg[rb][s] = *reinterpret_cast<const bf16x8*>(qp + 32 * s + 8 * G);
+  }
+
+  // ---- the first NST - 1 steps' tiles go in flight
+  const int tg0 = t0 + (MODE ? wgrp : 0);          // the tiles this wave's group moves: tg0, tg0 + STEP, ...
+  const SlabRanges R = slab_ranges(a, wave);
+  KeepAhead ka;
+  load_keep_ahead(a, wave, tg0, ka);
+  if constexpr (MODE == 2) {
+#pragma unroll
+    for (int j = 0; j < NST - 1; ++j)              // tile t0 + j belongs to group j & 1
+      if ((j & 1) == wgrp && t0 + j < t1)
+        issue_tile<D, ONCE, NST, NG, STEP>(a, L, R, kc, vc, kb, vb, ks, vs, t0 + j, j, ka);
+  } else {
+#pragma unroll
+    for (int j = 0; j < NST - 1; ++j)
+      if (tg0 + NG * j < t1) issue_tile<D, ONCE, NST, NG, STEP>(a, L, R, kc, vc, kb, vb, ks, vs, tg0 + NG * j, j, ka);
   }
 
   f32x4 o[RB][NDB];
