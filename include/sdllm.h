@@ -153,7 +153,9 @@ size_t sdllm_unmask_workspace_bytes(const sdllm_unmask_params* p);
 
 /*
  *   logits      [B,K,ld]  read only; only rows of masked positions are read
- *   tokens      [B,K] int32   in/out        masked [B,K] uint8 (0 / non-zero)  in/out
+ *   tokens      [B,K] int32   in/out        masked [B,K] uint8 (0 / non-zero)  in/out (the kernels read the
+ *               aligned 4-byte words that hold its bytes: up to 3 bytes on either side of the array are read,
+ *               never used, and lie in the same page as an array byte)
  *   confidence  [B,K] float   out, optional (NULL ok): c_i for positions masked on entry,
  *               other entries untouched
  *   n_committed [B] int32 out      block_done [B] uint8 out

@@ -283,7 +283,13 @@ __global__ __launch_bounds__(kRowThreads) void unmask_rows_kernel(UnmaskArgs a) 
   __shared__ Partial red[kRowThreads / 64];
   const int row = blockIdx.x / a.nsplit;
   const int split = blockIdx.x - row * a.nsplit;
-  if (a.masked[row] == 0) return;            // uniform per workgroup
+  // The row's mask byte through the scalar data cache: the aligned dword that holds it (an aligned dword lies inside
+  // one page, so reading it cannot fault even where the byte array does not fill it; only the row's own byte is
+  // used).  A vector load of the byte costs every workgroup a longer round trip before its first logits load.
+  typedef const __attribute__((address_space(4))) uint32_t* const_u32_ptr;
+  const uintptr_t mb = reinterpret_cast<uintptr_t>(a.masked) + (uintptr_t)row;
+  const uint32_t mword = *reinterpret_cast<const_u32_ptr>(mb & ~(uintptr_t)3);
+  if (((mword >> (8 * (unsigned)(mb & 3))) & 0xffu) == 0) return;            // uniform per workgroup
   const Partial p = reduce_row_slice<T>(a, row, split, red);
   if (threadIdx.x == 0) a.partials[(long long)row * a.nsplit + split] = p;
 }
