@@ -466,6 +466,20 @@ __global__ __launch_bounds__(MODE ? 512 : 256, MODE ? 1 : 2) void attn_bf16_kern
   const int wave = wave_wg & 3, wgrp = wave_wg >> 2;   // wave within its group, group within the workgroup
   const int l16 = lane & 15, G = lane >> 4;
 
+  // The query rows of this wave (both groups of MODE 1 hold the same rows).  A kept suffix row needs its keep_idx
+  // entry before its address is known: those entries are requested first of all, for every row block at once, so
+  // that their round trip overlaps the set-up below.
+  const int row_base = (MODE == 2) ? qt * (128 * RB) + wgrp * (64 * RB) + wave * (16 * RB)
+                                   : qt * (64 * RB) + wave * (16 * RB);
+  int q_hl[RB], q_qi[RB], q_keep[RB];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    const int R = min(row_base + rb * 16 + l16, a.Rtot - 1);
+    q_hl[rb] = R / a.Nq; q_qi[rb] = R - q_hl[rb] * a.Nq;
+    q_keep[rb] = 0;
+    if (q_qi[rb] >= a.K) q_keep[rb] = a.keep_idx[q_qi[rb] - a.K];
+  }
+
   Lane<D> L;
   L.lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)lds;
   L.wave = wave; L.grp = (MODE == 1) ? wgrp : 0; L.lane = lane; L.G = G;
@@ -496,25 +510,24 @@ __global__ __launch_bounds__(MODE ? 512 : 256, MODE ? 1 : 2) void attn_bf16_kern
       L.vro[db] = gofs + S::VBASE + (4 * G + e4) * ROWB + (((2 * db + (c4 >> 1)) ^ fv) << 4) + ((c4 & 1) << 3);
   }
 
-  // ---- query rows of this wave, as MFMA B operands (lane: row l16, d = 32*s + 8*G .. +7); in MODE 1 both groups
-  // hold the same rows.  Requested BEFORE the first K/V transfers: a kept suffix row needs its keep_idx entry first,
-  // and the wait for that entry covers everything older in the vector-memory queue -- behind the first tile's
-  // transfers the query rows would only be requested once that tile had landed (two memory round trips in a row
-  // instead of one short one and two in parallel).
-  const int row_base = (MODE == 2) ? qt * (128 * RB) + wgrp * (64 * RB) + wave * (16 * RB)
-                                   : qt * (64 * RB) + wave * (16 * RB);
-  bf16x8 qreg[RB][NS];
+  // ---- query rows of this wave, as MFMA B operands (lane: row l16, d = 32*s + 8*G .. +7).  Requested BEFORE the
+  // first K/V transfers: the wait for the keep_idx entries covers everything older in the vector-memory queue --
+  // behind the first tile's transfers the query rows would only be requested once that tile had landed (two memory
+  // round trips in a row instead of one short one and two in parallel).  All row blocks' addresses first, then all
+  // loads, so that one block's loads do not wait for the other's.
+  const uint16_t* qp[RB];
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
-    int R = min(row_base + rb * 16 + l16, a.Rtot - 1);
-    const int hl = R / a.Nq, qi = R - hl * a.Nq;
-    const long long qbh = (long long)b * a.Hq + (long long)kvh * a.g + hl;
-    const uint16_t* qp = (qi < a.K) ? a.q_block + (qbh * a.K + qi) * D
-                                    : a.q_suffix + (qbh * a.S + a.keep_idx[qi - a.K]) * D;
+    const long long qbh = (long long)b * a.Hq + (long long)kvh * a.g + q_hl[rb];
+    qp[rb] = (q_qi[rb] < a.K) ? a.q_block + (qbh * a.K + q_qi[rb]) * D
+                              : a.q_suffix + (qbh * a.S + q_keep[rb]) * D;
+  }
+  bf16x8 qreg[RB][NS];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
     for (int s = 0; s < NS; ++s)
-      qreg[rb][s] = *reinterpret_cast<const bf16x8*>(qp + 32 * s + 8 * G);
-  }
+      qreg[rb][s] = *reinterpret_cast<const bf16x8*>(qp[rb] + 32 * s + 8 * G);
 
   // ---- the first NST - 1 steps' tiles go in flight
   const int tg0 = t0 + (MODE ? wgrp : 0);          // the tiles this wave's group moves: tg0, tg0 + STEP, ...
